@@ -1,0 +1,352 @@
+"""CPU oracle for one MoE layer under Dynamic Expert Sharing (DES).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the
+HIP path is checked against.  Only the tests, the smoke entry and the
+benchmark's cpu_baseline leg may import it; the product path never does.  It
+shares no code with the HIP path and imports nothing from the package.
+
+Everything is numpy in float64 on the exact input values (bf16 / fp32 inputs
+are upcast by the caller; nothing is rounded in here).  Each function follows
+one passage of the paper:
+
+  router_logits        Background, "Efficient Mixture-of-Experts": G: R^D -> R^M
+  softmax_rows         Sec. 4.3 (per-token softmax of the selection kernel)
+  rank_order           TopK = "the K highest-scoring experts" (below Eq. 1)
+  coreset_seq          Eq. 5 / Alg. 2  (DES-Seq)
+  coreset_vote         Eq. 6 / Alg. 3  (DES-Vote)
+  constrained_topk     Alg. 1, stage 2, S_n
+  gates                Alg. 1, stage 2, g_n   (sigma = softmax, i.e. Eq. 1's
+                       normalisation by the selected sum)
+  expert_ffn           E_i(x): SwiGLU sub-network (form fixed by the workload)
+  moe_forward          Alg. 1 as a whole (+ Eq. 1 when mode == "vanilla")
+  moe_stack_forward    residual stack of such layers
+  expected_unique_uniform   closed form of Sec. 3 (Motivation)
+  coreset_size_from_beta    M_core = beta * M (Sec. 5.1), floor (Table 1)
+
+Readings taken where the paper is silent (each is listed with its reason in
+the design notes of the repository):
+  * ties in every TopK go to the lowest expert index; values are compared as
+    numbers (+0 == -0);
+  * votes are post-softmax probabilities over all M experts, masked to each
+    token's own top-K (model K), not renormalised;
+  * only experts nominated by at least one token can enter a vote coreset, so
+    the coreset may be smaller than C;
+  * a token uses k_eff = min(K, |coreset|) experts; unused slots carry
+    index -1 and weight 0;
+  * DES-Seq with k_seq == 0 picks the largest k' <= K whose union has at most C
+    members; if even k' = 1 overflows, the C most often top-1-nominated experts
+    are kept (ties to the lowest index).
+
+Pins: tests/test_oracle_pins.py (brute force over subsets, a hand-worked
+3-token x 5-expert example, the closed form for uniform routing, Table 1's
+rounding, reductions to a plain numpy MLP and to a dense one-hot einsum,
+and the invariants the method fixes).  The token-level statistics the paper
+reports on trained routers (hit-rate cosine similarity, accuracy) are
+"parity unpinned": they need trained weights.
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+MODES = ("vanilla", "seq", "vote")
+
+
+# --------------------------------------------------------------------------
+# Router
+# --------------------------------------------------------------------------
+def router_logits(x: np.ndarray, w_router: np.ndarray,
+                  bias: Optional[np.ndarray] = None) -> np.ndarray:
+    """Router scores G(x) for every token (Background, definition of G).
+
+    x: [T, D]; w_router: [M, D] (row i is expert i's router vector);
+    bias: [M] or None.  Returns float64 [T, M].
+    """
+    x = np.asarray(x, dtype=np.float64)
+    w = np.asarray(w_router, dtype=np.float64)
+    logits = x @ w.T
+    if bias is not None:
+        logits = logits + np.asarray(bias, dtype=np.float64)[None, :]
+    return logits
+
+
+def softmax_rows(logits: np.ndarray) -> np.ndarray:
+    """Per-token softmax over all M experts (Sec. 4.3)."""
+    z = np.asarray(logits, dtype=np.float64)
+    z = z - z.max(axis=-1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def rank_order(row: Sequence[float]) -> List[int]:
+    """Expert ids of one token sorted best first: value descending, ties to the
+    lowest index (TopK below Eq. 1 with the tie rule stated in the header)."""
+    vals = [float(v) for v in row]
+    for v in vals:
+        if not math.isfinite(v):
+            raise ValueError("router logits must be finite")
+    return sorted(range(len(vals)), key=lambda i: (-vals[i], i))
+
+
+def topk(row: Sequence[float], k: int) -> List[int]:
+    """TopK(row, k) in rank order."""
+    return rank_order(row)[:k]
+
+
+# --------------------------------------------------------------------------
+# Coreset selection functions Phi
+# --------------------------------------------------------------------------
+def coreset_seq(logits: np.ndarray, k_seq: int) -> List[int]:
+    """Eq. 5 / Alg. 2: union over tokens of each token's top-k_seq experts."""
+    core = set()
+    for n in range(logits.shape[0]):
+        core |= set(topk(logits[n], k_seq))
+    return sorted(core)
+
+
+def coreset_seq_capped(logits: np.ndarray, K: int, C: int) -> Tuple[List[int], int]:
+    """DES-Seq under a size cap C (extension; see header).  Returns
+    (coreset ascending, k_seq used); k_seq used is 0 in the overflow case."""
+    best_k = 0
+    for kp in range(1, K + 1):
+        if len(coreset_seq(logits, kp)) <= C:
+            best_k = kp
+        else:
+            break  # union size is monotone in k'
+    if best_k > 0:
+        return coreset_seq(logits, best_k), best_k
+    M = logits.shape[1]
+    nominations = [0] * M
+    for n in range(logits.shape[0]):
+        nominations[topk(logits[n], 1)[0]] += 1
+    cand = [i for i in range(M) if nominations[i] > 0]
+    cand.sort(key=lambda i: (-nominations[i], i))
+    return sorted(cand[:C]), 0
+
+
+def vote_vector(logits: np.ndarray, K: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Alg. 3, lines 1-2: V_i = sum over tokens of the token's softmax weight
+    for expert i, counted only where i is inside that token's own top-K.
+    Returns (V float64 [M], nominated bool [M])."""
+    N, M = logits.shape
+    P = softmax_rows(logits)
+    V = np.zeros(M, dtype=np.float64)
+    nominated = np.zeros(M, dtype=bool)
+    for n in range(N):
+        for i in topk(logits[n], K):
+            V[i] += P[n, i]
+            nominated[i] = True
+    return V, nominated
+
+
+def coreset_vote(logits: np.ndarray, K: int, C: int) -> Tuple[List[int], np.ndarray, float]:
+    """Eq. 6 / Alg. 3: the C experts with the largest total vote among the
+    nominated ones (ties to the lowest index).
+
+    Returns (coreset ascending, V, margin) where margin is the relative gap
+    (V_(C) - V_(C+1)) / V_(C) between the last expert taken and the first one
+    left out (inf when nothing was left out).
+    """
+    V, nominated = vote_vector(logits, K)
+    cand = [i for i in range(len(V)) if nominated[i]]
+    cand.sort(key=lambda i: (-V[i], i))
+    taken = cand[:C]
+    if len(cand) > C and len(taken) > 0:
+        last_in, first_out = V[taken[-1]], V[cand[C]]
+        margin = float((last_in - first_out) / last_in) if last_in > 0 else 0.0
+    else:
+        margin = math.inf
+    return sorted(taken), V, margin
+
+
+def select_coreset(logits: np.ndarray, mode: str, K: int, C: int,
+                   k_seq: int = 0) -> Dict[str, object]:
+    """Stage 1 of Alg. 1 for one sequence: coreset = Phi(logits)."""
+    if mode not in MODES:
+        raise ValueError(f"unknown mode {mode!r}")
+    N, M = logits.shape
+    out: Dict[str, object] = {"votes": None, "k_seq_used": 0, "margin": math.inf}
+    if mode == "vanilla":
+        out["coreset"] = list(range(M))           # Eq. 1: no restriction
+    elif mode == "seq":
+        if k_seq > 0:
+            out["coreset"] = coreset_seq(logits, k_seq)
+            out["k_seq_used"] = k_seq
+        else:
+            core, used = coreset_seq_capped(logits, K, C)
+            out["coreset"], out["k_seq_used"] = core, used
+    else:
+        core, V, margin = coreset_vote(logits, K, C)
+        out["coreset"], out["votes"], out["margin"] = core, V, margin
+    return out
+
+
+# --------------------------------------------------------------------------
+# Stage 2: constrained routing
+# --------------------------------------------------------------------------
+def constrained_topk(row: Sequence[float], coreset: Sequence[int], K: int) -> List[int]:
+    """Alg. 1 stage 2: S_n = TopK(row restricted to the coreset, K), rank order."""
+    inside = set(int(c) for c in coreset)
+    return [i for i in rank_order(row) if i in inside][:K]
+
+
+def gates(row: Sequence[float], selected: Sequence[int]) -> np.ndarray:
+    """Alg. 1 stage 2: g_n = softmax of the token's logits over S_n
+    (equal to P_i / sum_{j in S_n} P_j, the normalisation of Eq. 1)."""
+    if len(selected) == 0:
+        return np.zeros(0, dtype=np.float64)
+    z = np.array([float(row[i]) for i in selected], dtype=np.float64)
+    e = np.exp(z - z.max())
+    return e / e.sum()
+
+
+# --------------------------------------------------------------------------
+# Experts
+# --------------------------------------------------------------------------
+def silu(z: np.ndarray) -> np.ndarray:
+    return z / (1.0 + np.exp(-z))
+
+
+def expert_ffn(x: np.ndarray, wg: np.ndarray, wu: np.ndarray, wd: np.ndarray) -> np.ndarray:
+    """E(x) for one token.  wg, wu: [F, D] (row f is the weight vector of
+    intermediate unit f); wd: [D, F] (row d produces output coordinate d).
+    E(x) = wd @ (silu(wg @ x) * (wu @ x))."""
+    h = silu(wg @ x) * (wu @ x)
+    return wd @ h
+
+
+class _F64Cache:
+    """Memo of float64 upcasts of per-expert weight matrices (conversion only)."""
+
+    def __init__(self, w_gate, w_up, w_down):
+        self.w = (w_gate, w_up, w_down)
+        self.memo: Dict[int, Tuple[np.ndarray, np.ndarray, np.ndarray]] = {}
+
+    def get(self, e: int):
+        if e not in self.memo:
+            self.memo[e] = tuple(np.asarray(m[e], dtype=np.float64) for m in self.w)
+        return self.memo[e]
+
+
+# --------------------------------------------------------------------------
+# The layer (Alg. 1)
+# --------------------------------------------------------------------------
+def route_block(logits: np.ndarray, mode: str, K: int, C: int, k_seq: int = 0) -> Dict[str, object]:
+    """Routing part of Alg. 1 for ONE sequence given its logits [N, M]:
+    coreset, per-token S_n (rank order, padded with -1) and gates (padded 0)."""
+    logits = np.asarray(logits, dtype=np.float64)
+    N, M = logits.shape
+    sel = select_coreset(logits, mode, K, C, k_seq)
+    core = sel["coreset"]
+    idx = -np.ones((N, K), dtype=np.int32)
+    w = np.zeros((N, K), dtype=np.float64)
+    for n in range(N):
+        s_n = constrained_topk(logits[n], core, K)
+        g_n = gates(logits[n], s_n)
+        idx[n, :len(s_n)] = s_n
+        w[n, :len(s_n)] = g_n
+    sel.update(topk_idx=idx, topk_w=w)
+    return sel
+
+
+def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
+                w_gate: np.ndarray, w_up: np.ndarray, w_down: np.ndarray,
+                K: int, C: int, mode: str, k_seq: int = 0,
+                shared: Optional[Tuple[np.ndarray, np.ndarray, np.ndarray]] = None,
+                logits_override: Optional[np.ndarray] = None,
+                compute_y: bool = True, residual: bool = False) -> Dict[str, object]:
+    """Alg. 1 for B independent sequences.
+
+    x: [B, N, D].  w_router [M, D]; w_gate, w_up [M, F, D]; w_down [M, D, F].
+    shared: optional (wg [Fs, D], wu [Fs, D], wd [D, Fs]) always-on expert added
+    with weight 1.  logits_override [B, N, M]: use these router logits instead
+    of computing them (the routing decisions are then a function of exactly
+    these numbers).  Each sequence elects its own coreset.
+    """
+    x = np.asarray(x)
+    B, N, D = x.shape
+    M = w_router.shape[0]
+    x64 = x.astype(np.float64)
+    if logits_override is not None:
+        logits = np.asarray(logits_override, dtype=np.float64).reshape(B, N, M)
+    else:
+        logits = router_logits(x64.reshape(B * N, D), w_router, bias).reshape(B, N, M)
+
+    topk_idx = -np.ones((B, N, K), dtype=np.int32)
+    topk_w = np.zeros((B, N, K), dtype=np.float64)
+    coresets: List[List[int]] = []
+    votes: List[Optional[np.ndarray]] = []
+    margins: List[float] = []
+    k_seq_used: List[int] = []
+    for b in range(B):
+        r = route_block(logits[b], mode, K, C, k_seq)
+        topk_idx[b], topk_w[b] = r["topk_idx"], r["topk_w"]
+        coresets.append(r["coreset"])
+        votes.append(r["votes"])
+        margins.append(r["margin"])
+        k_seq_used.append(r["k_seq_used"])
+
+    counts = np.zeros(M, dtype=np.int32)        # cnt_i of Eq. 2, summed over sequences
+    for e in topk_idx.reshape(-1):
+        if e >= 0:
+            counts[e] += 1
+    n_unique = int((counts > 0).sum())           # |union_n S_n|
+
+    y = None
+    if compute_y:
+        cache = _F64Cache(w_gate, w_up, w_down)
+        y = np.zeros((B, N, D), dtype=np.float64)
+        sh = None
+        if shared is not None:
+            sh = tuple(np.asarray(m, dtype=np.float64) for m in shared)
+        for b in range(B):
+            for n in range(N):
+                acc = np.zeros(D, dtype=np.float64)
+                for j in range(K):
+                    e = int(topk_idx[b, n, j])
+                    if e < 0:
+                        continue
+                    wg, wu, wd = cache.get(e)
+                    acc += topk_w[b, n, j] * expert_ffn(x64[b, n], wg, wu, wd)
+                if sh is not None:
+                    acc += expert_ffn(x64[b, n], *sh)
+                if residual:
+                    acc += x64[b, n]
+                y[b, n] = acc
+    return dict(logits=logits, topk_idx=topk_idx, topk_w=topk_w, counts=counts,
+                n_unique=n_unique, coresets=coresets, votes=votes, margins=margins,
+                k_seq_used=k_seq_used, y=y)
+
+
+def moe_stack_forward(x: np.ndarray, layers: Sequence[dict], K: int, C: int, mode: str,
+                      k_seq: int = 0) -> Tuple[np.ndarray, List[Dict[str, object]]]:
+    """x_{l+1} = x_l + MoE_l(x_l) for a list of layers (each a dict with
+    w_router, bias, w_gate, w_up, w_down and optionally shared)."""
+    cur = np.asarray(x, dtype=np.float64)
+    per_layer = []
+    for lw in layers:
+        r = moe_forward(cur, lw["w_router"], lw.get("bias"), lw["w_gate"], lw["w_up"],
+                        lw["w_down"], K, C, mode, k_seq, shared=lw.get("shared"),
+                        residual=True)
+        per_layer.append(r)
+        cur = r["y"]
+    return cur, per_layer
+
+
+# --------------------------------------------------------------------------
+# Closed forms the paper prints
+# --------------------------------------------------------------------------
+def expected_unique_uniform(M: int, K: int, N: int) -> float:
+    """Sec. 3: expected |union S_n| under uniform routing, M (1 - (1 - K/M)^N)."""
+    return M * (1.0 - (1.0 - K / M) ** N)
+
+
+def coreset_size_from_beta(beta: float, M: int) -> int:
+    """M_core = beta * M (Sec. 5.1); Table 1's printed sizes fix the rounding
+    to floor (0.15*256 -> 38, 0.10*256 -> 25, 0.6*64 -> 38, 0.4*64 -> 25).
+    The product is formed exactly (decimal beta) so 0.15*256 is 38.4, not
+    38.39999..."""
+    from fractions import Fraction
+    return int(math.floor(Fraction(str(beta)) * M))

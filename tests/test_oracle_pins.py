@@ -1,0 +1,340 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something
+other than itself - brute force over subsets, a hand-worked example, a closed
+form the paper prints, Table 1's rounding, plain numpy routines, or an
+invariant the method fixes.  CPU only."""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import des_oracle as O
+from paper_2602_00879_amd import workloads as W
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- brute force
+def _best_subset(scores, allowed, k):
+    """All k-subsets of `allowed`: maximal score sum, lexicographically smallest
+    sorted tuple among equal sums (= lowest-index tie rule)."""
+    best = None
+    for comb in itertools.combinations(sorted(allowed), k):
+        s = sum(scores[i] for i in comb)
+        if best is None or s > best[0] or (s == best[0] and comb < best[1]):
+            best = (s, comb)
+    return set(best[1])
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_topk_equals_subset_enumeration(seed):
+    rng = np.random.default_rng(seed)
+    M = int(rng.integers(2, 9))
+    K = int(rng.integers(1, M + 1))
+    # small integers -> many exact ties; sums of integers are exact
+    row = rng.integers(-3, 4, size=M).astype(np.float64)
+    got = O.topk(row, K)
+    assert set(got) == _best_subset(row, range(M), K)
+    # rank order: non-increasing values, ties by ascending index
+    for a, b in zip(got, got[1:]):
+        assert (row[a] > row[b]) or (row[a] == row[b] and a < b)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_constrained_topk_equals_subset_enumeration(seed):
+    rng = np.random.default_rng(100 + seed)
+    M = int(rng.integers(3, 9))
+    core = sorted(rng.choice(M, size=int(rng.integers(1, M + 1)), replace=False).tolist())
+    K = int(rng.integers(1, M + 1))
+    row = rng.integers(-2, 3, size=M).astype(np.float64)
+    got = O.constrained_topk(row, core, K)
+    k_eff = min(K, len(core))
+    assert len(got) == k_eff
+    assert set(got) == _best_subset(row, core, k_eff)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_vote_coreset_equals_subset_enumeration(seed):
+    rng = np.random.default_rng(200 + seed)
+    N, M = int(rng.integers(1, 6)), int(rng.integers(3, 9))
+    K = int(rng.integers(1, M))
+    C = int(rng.integers(1, M + 1))
+    logits = rng.standard_normal((N, M))
+    core, V, margin = O.coreset_vote(logits, K, C)
+    # independent V: dense softmax times a 0/1 mask built from argsort
+    P = np.exp(logits) / np.exp(logits).sum(1, keepdims=True)
+    mask = np.zeros_like(P)
+    for n in range(N):
+        order = np.lexsort((np.arange(M), -logits[n]))
+        mask[n, order[:K]] = 1.0
+    V2 = (P * mask).sum(0)
+    np.testing.assert_allclose(V, V2, rtol=1e-12, atol=0)
+    nominated = [i for i in range(M) if mask[:, i].any()]
+    c_eff = min(C, len(nominated))
+    assert len(core) == c_eff
+    assert set(core) == _best_subset(V2, nominated, c_eff)
+    assert core == sorted(core)
+    assert margin > 0
+
+
+def test_vote_tie_goes_to_lowest_index():
+    # two tokens, identical rows with exact ties between experts 1 and 2
+    logits = np.array([[0.0, 1.0, 1.0, -1.0], [0.0, 1.0, 1.0, -1.0]])
+    core, V, margin = O.coreset_vote(logits, K=2, C=1)
+    assert V[1] == V[2]
+    assert core == [1]
+    assert margin == 0.0
+
+
+# ---------------------------------------------------------- hand-worked example
+def test_hand_worked_example():
+    g = json.load(open(os.path.join(GOLD, "vote_3x5_worked_example.json")))
+    P = np.array(g["probs"])
+    logits = np.log(P)
+    K, C = g["K"], g["C"]
+    core, V, margin = O.coreset_vote(logits, K, C)
+    np.testing.assert_allclose(V, g["votes"], rtol=1e-12, atol=1e-15)
+    assert core == g["vote_coreset"]
+    assert margin == pytest.approx(g["vote_margin"], rel=1e-12)
+    r = O.route_block(logits, "vote", K, C)
+    assert r["topk_idx"].tolist() == g["vote_topk_idx"]
+    np.testing.assert_allclose(r["topk_w"], g["vote_gates"], rtol=1e-12)
+    assert O.coreset_seq(logits, 1) == g["seq_k1_coreset"]
+    assert O.coreset_seq(logits, 2) == g["seq_k2_coreset"]
+    assert O.route_block(logits, "seq", K, 5, k_seq=1)["topk_idx"].tolist() == g["seq_k1_topk_idx"]
+    rv = O.route_block(logits, "vanilla", K, 5)
+    assert rv["topk_idx"].tolist() == g["vanilla_topk_idx"]
+    # counts / unique experts through the layer entry point (weights irrelevant)
+    D, F, M = 4, 2, 5
+    z = np.zeros
+    out = O.moe_forward(z((1, 3, D)), z((M, D)), None, z((M, F, D)), z((M, F, D)), z((M, D, F)),
+                        K, C, "vote", logits_override=logits[None])
+    assert out["counts"].tolist() == g["vote_counts"]
+    out = O.moe_forward(z((1, 3, D)), z((M, D)), None, z((M, F, D)), z((M, F, D)), z((M, D, F)),
+                        K, C, "vanilla", logits_override=logits[None])
+    assert out["n_unique"] == g["vanilla_n_unique"]
+
+
+# ------------------------------------------------------------------ closed form
+@pytest.mark.parametrize("M,K,N", [(128, 8, 4), (128, 8, 32), (128, 8, 128), (256, 8, 32)])
+def test_expected_unique_experts_uniform_routing(M, K, N):
+    """Sec. 3: E|union S_n| = M(1-(1-K/M)^N) under uniform routing.  i.i.d.
+    Gaussian logits make every token's top-K a uniform random K-subset."""
+    seeds = 200
+    tot = 0
+    for s in range(seeds):
+        L = W.make_logits(N, M, seed=1000 + s)
+        r = O.moe_forward(np.zeros((1, N, 1)), np.zeros((M, 1)), None, None, None, None,
+                          K, M, "vanilla", logits_override=L[None], compute_y=False)
+        tot += r["n_unique"]
+    mean = tot / seeds
+    expect = O.expected_unique_uniform(M, K, N)
+    # printed values for the 128-expert shape (derived from the formula)
+    if (M, K) == (128, 8):
+        assert expect == pytest.approx({4: 29.1, 32: 111.8, 128: 128.0}[N], abs=0.06)
+    # per-sample std is below sqrt(M)/2; 5 sigma of the mean
+    tol = 5 * (math.sqrt(M) / 2) / math.sqrt(seeds) + 0.05
+    assert abs(mean - expect) < tol, (mean, expect)
+
+
+def test_beta_rounding_matches_table1():
+    # Table 1: beta=0.15 -> 38 and 0.10 -> 25 (256-expert model);
+    #          beta=0.6 -> 38 and 0.4 -> 25 (64-expert model)
+    assert O.coreset_size_from_beta(0.15, 256) == 38
+    assert O.coreset_size_from_beta(0.10, 256) == 25
+    assert O.coreset_size_from_beta(0.6, 64) == 38
+    assert O.coreset_size_from_beta(0.4, 64) == 25
+    # the other roundings would contradict the table
+    assert round(0.10 * 256) == 26 and math.ceil(0.15 * 256) == 39
+
+
+# ------------------------------------------------------- FFN / combine reductions
+def _rand_layer(rng, B, N, D, M, F, shared=False):
+    x = rng.standard_normal((B, N, D))
+    wr = rng.standard_normal((M, D)) * 0.3
+    wg = rng.standard_normal((M, F, D)) * 0.2
+    wu = rng.standard_normal((M, F, D)) * 0.2
+    wd = rng.standard_normal((M, D, F)) * 0.2
+    sh = None
+    if shared:
+        sh = (rng.standard_normal((F + 1, D)) * 0.2, rng.standard_normal((F + 1, D)) * 0.2,
+              rng.standard_normal((D, F + 1)) * 0.2)
+    return x, wr, wg, wu, wd, sh
+
+
+def test_single_expert_is_plain_swiglu_mlp():
+    rng = np.random.default_rng(7)
+    x, wr, wg, wu, wd, _ = _rand_layer(rng, 1, 5, 12, 1, 9)
+    out = O.moe_forward(x, wr, None, wg, wu, wd, K=1, C=1, mode="vanilla")
+    X = x[0]
+    G = X @ wg[0].T
+    H = (G / (1 + np.exp(-G))) * (X @ wu[0].T)
+    np.testing.assert_allclose(out["y"][0], H @ wd[0].T, rtol=1e-12, atol=1e-14)
+    assert np.all(out["topk_w"] == 1.0)
+
+
+@pytest.mark.parametrize("mode", ["vanilla", "seq", "vote"])
+def test_layer_equals_dense_one_hot_einsum(mode):
+    rng = np.random.default_rng(11)
+    B, N, D, M, F, K, C = 2, 6, 10, 7, 5, 3, 4
+    x, wr, wg, wu, wd, sh = _rand_layer(rng, B, N, D, M, F, shared=True)
+    bias = rng.standard_normal(M)
+    out = O.moe_forward(x, wr, bias, wg, wu, wd, K, C, mode, shared=sh, residual=True)
+    # dense: every expert for every token, times a gate matrix rebuilt from
+    # probabilities restricted to the selected set (Eq. 1's normalisation)
+    G = np.einsum("bnd,mfd->bnmf", x, wg)
+    U = np.einsum("bnd,mfd->bnmf", x, wu)
+    E = np.einsum("bnmf,mdf->bnmd", G / (1 + np.exp(-G)) * U, wd)
+    L = np.einsum("bnd,md->bnm", x, wr) + bias
+    P = np.exp(L) / np.exp(L).sum(-1, keepdims=True)
+    gate = np.zeros((B, N, M))
+    for b in range(B):
+        for n in range(N):
+            S = [e for e in out["topk_idx"][b, n] if e >= 0]
+            gate[b, n, S] = P[b, n, S] / P[b, n, S].sum()
+    y = np.einsum("bnm,bnmd->bnd", gate, E)
+    Gs = x @ sh[0].T
+    y = y + (Gs / (1 + np.exp(-Gs)) * (x @ sh[1].T)) @ sh[2].T + x
+    np.testing.assert_allclose(out["y"], y, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(out["logits"], L, rtol=1e-12, atol=1e-13)
+
+
+def test_output_is_linear_in_down_projection():
+    rng = np.random.default_rng(13)
+    x, wr, wg, wu, wd, _ = _rand_layer(rng, 1, 4, 8, 5, 6)
+    a = O.moe_forward(x, wr, None, wg, wu, wd, 2, 3, "vote")["y"]
+    b = O.moe_forward(x, wr, None, wg, wu, 3.0 * wd, 2, 3, "vote")["y"]
+    np.testing.assert_allclose(b, 3.0 * a, rtol=1e-12)
+
+
+# ------------------------------------------------------------------- invariants
+@pytest.mark.parametrize("mode", ["vanilla", "seq", "vote"])
+@pytest.mark.parametrize("seed", range(6))
+def test_invariants_random(mode, seed):
+    rng = np.random.default_rng(300 + seed)
+    N, M = int(rng.integers(1, 20)), int(rng.integers(2, 40))
+    K = int(rng.integers(1, min(M, 8) + 1))
+    C = int(rng.integers(1, M + 1))
+    L = rng.standard_normal((N, M)).astype(np.float32)
+    r = O.route_block(L, mode, K, C)
+    core = r["coreset"]
+    assert core == sorted(set(core))
+    if mode != "vanilla":
+        assert len(core) <= C
+    k_eff = min(K, len(core))
+    for n in range(N):
+        S = [e for e in r["topk_idx"][n] if e >= 0]
+        assert len(S) == k_eff and len(set(S)) == k_eff
+        assert set(S) <= set(core)                      # Alg. 1: routed inside the coreset
+        assert r["topk_w"][n].sum() == pytest.approx(1.0, abs=1e-12)
+        assert np.all(r["topk_idx"][n, k_eff:] == -1) and np.all(r["topk_w"][n, k_eff:] == 0)
+    # the coreset does not depend on the order of the tokens
+    perm = rng.permutation(N)
+    assert O.route_block(L[perm], mode, K, C)["coreset"] == core
+
+
+def test_vanilla_is_standard_topk_and_degenerate_modes_reduce_to_it():
+    rng = np.random.default_rng(5)
+    N, M, K = 9, 24, 4
+    L = rng.standard_normal((N, M)).astype(np.float32)
+    van = O.route_block(L, "vanilla", K, M)
+    for n in range(N):
+        order = np.lexsort((np.arange(M), -L[n].astype(np.float64)))
+        assert van["topk_idx"][n].tolist() == order[:K].tolist()
+    # vote with C >= M keeps every nominated expert -> same routing as vanilla
+    vote = O.route_block(L, "vote", K, M)
+    assert np.array_equal(vote["topk_idx"], van["topk_idx"])
+    np.testing.assert_allclose(vote["topk_w"], van["topk_w"], rtol=0, atol=0)
+    # seq with k_seq = K: the union of vanilla selections (Eq. 5 with k = K)
+    seq = O.route_block(L, "seq", K, M, k_seq=K)
+    assert np.array_equal(seq["topk_idx"], van["topk_idx"])
+    assert seq["coreset"] == sorted(set(van["topk_idx"].reshape(-1).tolist()))
+    # a single token with C = K elects exactly its own top-K
+    one = O.route_block(L[:1], "vote", K, K)
+    assert np.array_equal(one["topk_idx"], van["topk_idx"][:1])
+
+
+def test_identical_tokens_give_vanilla_output():
+    rng = np.random.default_rng(17)
+    x, wr, wg, wu, wd, _ = _rand_layer(rng, 1, 1, 8, 9, 4)
+    x = np.repeat(x, 5, axis=1)
+    a = O.moe_forward(x, wr, None, wg, wu, wd, 3, 9, "vanilla")
+    for mode in ("seq", "vote"):
+        b = O.moe_forward(x, wr, None, wg, wu, wd, 3, 3, mode)
+        assert np.array_equal(a["topk_idx"], b["topk_idx"])
+        np.testing.assert_allclose(a["y"], b["y"], rtol=1e-13)
+
+
+def test_seq_cap_rule():
+    rng = np.random.default_rng(23)
+    N, M, K = 12, 30, 5
+    L = rng.standard_normal((N, M))
+    sizes = [len(O.coreset_seq(L, k)) for k in range(1, K + 1)]
+    assert sizes == sorted(sizes)                        # monotone in k'
+    for C in (sizes[0], sizes[2], sizes[-1], sizes[1] + 1 if sizes[1] + 1 < sizes[2] else sizes[1]):
+        core, used = O.coreset_seq_capped(L, K, C)
+        assert used >= 1 and len(core) <= C
+        assert core == O.coreset_seq(L, used)
+        assert used == K or len(O.coreset_seq(L, used + 1)) > C
+    # overflow: fewer slots than distinct top-1 experts
+    C = sizes[0] - 1
+    if C >= 1:
+        core, used = O.coreset_seq_capped(L, K, C)
+        assert used == 0 and len(core) == C
+        top1 = [int(np.argmax(L[n])) for n in range(N)]
+        nom = {e: top1.count(e) for e in set(top1)}
+        assert set(core) <= set(top1)
+        worst_in = min(nom[e] for e in core)
+        assert all(nom[e] <= worst_in for e in set(top1) - set(core))
+
+
+def test_counts_and_unique():
+    rng = np.random.default_rng(29)
+    x, wr, wg, wu, wd, _ = _rand_layer(rng, 3, 7, 6, 11, 3)
+    out = O.moe_forward(x, wr, None, wg, wu, wd, 4, 5, "vote", compute_y=False)
+    k_eff = [min(4, len(c)) for c in out["coresets"]]
+    assert out["counts"].sum() == sum(7 * k for k in k_eff)
+    assert out["n_unique"] == (out["counts"] > 0).sum()
+    assert out["n_unique"] <= len(set().union(*map(set, out["coresets"])))
+
+
+def test_stack_is_residual_composition():
+    rng = np.random.default_rng(31)
+    layers = []
+    for _ in range(3):
+        x, wr, wg, wu, wd, _ = _rand_layer(rng, 2, 4, 6, 5, 3)
+        layers.append(dict(w_router=wr, bias=None, w_gate=wg, w_up=wu, w_down=wd))
+    y, per = O.moe_stack_forward(x, layers, 2, 3, "vote")
+    cur = x
+    for lw in layers:
+        cur = cur + O.moe_forward(cur, lw["w_router"], None, lw["w_gate"], lw["w_up"],
+                                  lw["w_down"], 2, 3, "vote")["y"]
+    np.testing.assert_allclose(y, cur, rtol=1e-13)
+
+
+# ------------------------------------------------------------ input generators
+def test_bf16_rounding_is_nearest_even():
+    a = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.1415927], dtype=np.float32)
+    bits = W.f32_to_bf16_bits(a)
+    back = W.bf16_bits_to_f32(bits)
+    # 1 + 2^-8 is a tie between 1.0 and 1+2^-7 -> even mantissa (1.0);
+    # 1 + 3*2^-8 is a tie -> rounds up to 1 + 2^-6 (even)
+    assert back[0] == 1.0 and back[1] == 1.0 and back[2] == np.float32(1.015625)
+    assert back[3] == -2.5
+    assert abs(back[4] - a[4]) <= 2.0 ** -7
+    import torch
+    t = torch.from_numpy(a).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(t, back)
+
+
+def test_workload_shapes_and_seeding():
+    cfg = W.CONFIGS["tiny_f32"]
+    a, b = W.make_layer(cfg), W.make_layer(cfg)
+    assert a["x"].shape == (1, 8, 256) and a["w_router"].shape == (16, 256)
+    assert a["w_gate"].shape == (16, 128, 256) and a["w_down"].shape == (16, 256, 128)
+    assert np.array_equal(a["w_up"], b["w_up"])
+    assert abs(float(a["w_gate"].std()) - 0.02) < 1e-3
+    zb = W.zipf_bias(128, 1.1, np.random.default_rng(0))
+    assert abs(float(zb.mean())) < 1e-5 and sorted(-zb)[1] - sorted(-zb)[0] == pytest.approx(1.1 * math.log(2), rel=1e-5)
