@@ -1,0 +1,194 @@
+/*
+ * des.h - C ABI of the MI355X (gfx950) hot path of Dynamic Expert Sharing (DES):
+ * one Mixture-of-Experts layer applied to a whole parallel-decoding block of N
+ * tokens, where the block elects a shared expert coreset (Alg. 1 stage 1), each
+ * token is re-routed to its top-K experts inside that coreset (Alg. 1 stage 2)
+ * and a grouped SwiGLU expert FFN reads every selected expert's weights from
+ * HBM once.
+ *
+ * Conventions that hold for every entry point unless its comment says otherwise
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates and frees nothing; scratch comes from the caller's `workspace`.
+ *   - Calls validate their arguments on the host, enqueue kernels on
+ *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream)
+ *     and return without synchronising.  No device-to-host copy happens: the
+ *     host never learns which experts were elected, so launches are sized for
+ *     the worst case and pick their work list up from device memory.
+ *   - Return value: DES_OK (0), or a negative des_status_t.  Argument errors
+ *     are detected before anything is launched, so a failing call leaves all
+ *     outputs untouched.  des_strerror() names a code.
+ *   - Router logits must be finite; behaviour is unspecified otherwise.
+ *   - Every TopK breaks ties towards the lowest expert index and compares
+ *     values as numbers (+0 equals -0).
+ *   - Results are run-to-run bit-identical: no floating-point atomics are used.
+ *
+ * Tensor layouts ("rows contiguous along the reduction dimension"):
+ *   x          [B][N][D]       hidden states, dtype
+ *   w_router   [M][D]          row i is expert i's router vector, dtype
+ *   router_bias[M]             fp32, or NULL
+ *   w_gate     [M][F][D]       row f of expert e produces intermediate unit f
+ *   w_up       [M][F][D]
+ *   w_down     [M][D][F]       row d of expert e produces output coordinate d
+ *   (the mathematical orientation is gate/up: D x F, down: F x D; a loader
+ *   transposes once when the model is set up)
+ *   With weight_layout == DES_LAYOUT_PACKED (bf16 only) the three expert
+ *   tensors hold the same values re-tiled by des_pack_expert_weights() so that
+ *   a wavefront's matrix-core operand is one contiguous 1 KiB read.
+ */
+#ifndef DES_H
+#define DES_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DES_VANILLA = 0, /* Eq. 1: every token takes its own top-K of all M experts   */
+  DES_SEQ = 1,     /* Eq. 5 / Alg. 2: coreset = union of per-token top-k_seq     */
+  DES_VOTE = 2     /* Eq. 6 / Alg. 3: coreset = top-C of the masked vote vector  */
+} des_mode_t;
+
+typedef enum { DES_F32 = 0, DES_BF16 = 1 } des_dtype_t;
+
+typedef enum { DES_LAYOUT_ROWMAJOR = 0, DES_LAYOUT_PACKED = 1 } des_layout_t;
+
+typedef enum {
+  DES_OK = 0,
+  DES_ERR_NULL = -1,      /* a required pointer is NULL                          */
+  DES_ERR_SHAPE = -2,     /* a size is out of range or not supported             */
+  DES_ERR_MODE = -3,      /* mode is not a des_mode_t                            */
+  DES_ERR_DTYPE = -4,     /* dtype / weight_layout not supported                 */
+  DES_ERR_WORKSPACE = -5, /* workspace smaller than des_workspace_bytes()        */
+  DES_ERR_HIP = -6        /* a HIP call failed; des_last_hip_error() has text    */
+} des_status_t;
+
+/* Problem shape.  Paper symbol in brackets. */
+typedef struct {
+  int32_t n_seqs;        /* B: independent sequences; each elects its own coreset  */
+  int32_t n_tokens;      /* [N] tokens per sequence (the parallel-decoding block)  */
+  int32_t hidden;        /* [D]                                                    */
+  int32_t n_experts;     /* [M]                                                    */
+  int32_t ffn;           /* F: routed-expert intermediate size                     */
+  int32_t ffn_shared;    /* F_s: always-on shared expert, 0 = none                 */
+  int32_t top_k;         /* [K] experts per token                                  */
+  int32_t coreset;       /* [M_core] C: coreset budget; ignored in vanilla mode    */
+  int32_t k_seq;         /* [k] DES-Seq local count; 0 = largest k' <= K whose     */
+                         /*     union fits in C (see des_select_coreset)           */
+  int32_t mode;          /* des_mode_t                                             */
+  int32_t dtype;         /* des_dtype_t of x, w_router, expert weights and y       */
+  int32_t weight_layout; /* des_layout_t of w_gate / w_up / w_down (+ shared)      */
+  int32_t residual;      /* 1: y = x + MoE(x)  (layer inside a residual stack)     */
+} des_shape_t;
+
+/*
+ * Limits checked by every entry point (DES_ERR_SHAPE otherwise):
+ *   B, N, D, M, F, K >= 1;  K <= M;  K <= 32;  M <= 512;  B*N <= 4096;
+ *   M * ceil(B*N/64) <= 4096;  C >= 1 in seq / vote mode;  0 <= k_seq <= K;
+ *   seq mode with an explicit k_seq needs C >= min(M, N*k_seq) so that the
+ *   union of Eq. 5 always fits the coreset_idx buffer;
+ *   bf16: D, F, F_s multiples of 32 (matrix-core K step); fp32: multiples of 4.
+ */
+
+/* Width of one row of coreset_idx: M in vanilla mode, min(C, M) otherwise. */
+int32_t des_coreset_capacity(const des_shape_t* shape);
+
+/* Bytes of device scratch des_moe_forward needs for `shape`.  Host only: does
+ * not touch the GPU.  Returns 0 if the shape is invalid. */
+size_t des_workspace_bytes(const des_shape_t* shape);
+
+/*
+ * Router scores (Background: G: R^D -> R^M) and their per-token softmax (the
+ * per-token softmax of Sec. 4.3):
+ *   logits[b][n][i] = sum_d x[b][n][d] * w_router[i][d] (+ router_bias[i]),
+ *   probs [b][n][:] = softmax over all M of logits[b][n][:]   (if probs != NULL)
+ * Inputs are read in `dtype`, accumulated in fp32; outputs are fp32
+ * [B][N][M].  Uses no workspace.
+ */
+int des_route(const des_shape_t* shape, const void* x, const void* w_router,
+              const float* router_bias, float* logits, float* probs, void* hip_stream);
+
+/*
+ * Stage 1 of Alg. 1, coreset = Phi(logits), for each of the B sequences.
+ *   vanilla: all M experts.
+ *   seq    : k_seq > 0: union over tokens of TopK(logits[n], k_seq)  (Eq. 5).
+ *            k_seq == 0: the largest k' <= K whose union has at most C members;
+ *            if even k' = 1 does not fit, the C experts with the most top-1
+ *            nominations (ties to the lowest index) and k_seq_used = 0.
+ *   vote   : V[i] = sum over tokens n with i in TopK(logits[n], K) of
+ *            softmax(logits[n])[i] (fp32, fixed summation order);
+ *            coreset = the C experts of largest V among experts nominated by
+ *            at least one token (Eq. 6); it is smaller than C when fewer
+ *            were nominated.
+ * Outputs: coreset_idx [B][des_coreset_capacity] ascending expert ids padded
+ * with -1; coreset_size [B]; votes [B][M] (vote mode; may be NULL);
+ * k_seq_used [B] (may be NULL).  Uses no workspace.
+ */
+int des_select_coreset(const des_shape_t* shape, const float* logits, int32_t* coreset_idx,
+                       int32_t* coreset_size, float* votes, int32_t* k_seq_used,
+                       void* hip_stream);
+
+/*
+ * The whole layer, Alg. 1 (Eq. 1 when mode == DES_VANILLA):
+ *   logits as des_route; coreset as des_select_coreset;
+ *   S_n   = first k_eff = min(K, |coreset|) experts of the coreset in the order
+ *           (logit descending, index ascending)                 -> topk_idx
+ *   g_n   = softmax of logits[n] over S_n                        -> topk_w
+ *   y_n   = sum_j g_n[j] * E_{S_n[j]}(x_n)  (+ E_shared(x_n))  (+ x_n if residual)
+ *   E(x)  = Wd (silu(Wg x) * (Wu x)),  silu(z) = z / (1 + exp(-z))
+ * Outputs (all device): y [B][N][D] dtype; logits [B][N][M] fp32;
+ * topk_idx [B][N][K] int32 in rank order, unused slots -1; topk_w [B][N][K]
+ * fp32, unused slots 0; expert_counts [M] int32 = pairs routed to each expert
+ * summed over sequences (cnt_i of Eq. 2); n_unique [1] int32 = experts with a
+ * non-zero count (|union S_n|); coreset_idx / coreset_size as above.
+ * ws_gate / ws_up / ws_down: the shared expert ([Fs][D], [Fs][D], [D][Fs], same
+ * dtype and layout rule), required iff ffn_shared > 0.
+ * y must not alias x.  workspace: >= des_workspace_bytes(shape), 256-byte
+ * aligned, contents irrelevant on entry.
+ */
+int des_moe_forward(const des_shape_t* shape, const void* x, const void* w_router,
+                    const float* router_bias, const void* w_gate, const void* w_up,
+                    const void* w_down, const void* ws_gate, const void* ws_up,
+                    const void* ws_down, void* y, float* logits, int32_t* topk_idx,
+                    float* topk_w, int32_t* expert_counts, int32_t* n_unique,
+                    int32_t* coreset_idx, int32_t* coreset_size, void* workspace,
+                    size_t workspace_bytes, void* hip_stream);
+
+/*
+ * A residual stack of n_layers such layers, x_{l+1} = x_l + MoE_l(x_l)
+ * (shape->residual is taken as 1).  Layer l's tensors start at
+ * base + l * stride elements: w_router [L][M][D], router_bias [L][M] (or NULL),
+ * w_gate / w_up [L][M][F][D], w_down [L][M][D][F], shared likewise.
+ * Outputs: y [B][N][D] = x_L; n_unique [L]; expert_counts [L][M].
+ * workspace: >= des_stack_workspace_bytes(shape).
+ */
+size_t des_stack_workspace_bytes(const des_shape_t* shape);
+int des_moe_stack_forward(const des_shape_t* shape, int32_t n_layers, const void* x,
+                          const void* w_router, const float* router_bias, const void* w_gate,
+                          const void* w_up, const void* w_down, const void* ws_gate,
+                          const void* ws_up, const void* ws_down, void* y,
+                          int32_t* expert_counts, int32_t* n_unique, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Re-tile bf16 expert weights for DES_LAYOUT_PACKED.  `src` is n_mats
+ * row-major matrices [rows][cols] (cols = reduction dimension; rows a
+ * multiple of 16, cols a multiple of 32); `dst` (same size, must not alias)
+ * receives, per matrix, tiles of 16 rows x 32 columns ordered
+ * [row tile][column tile], each tile stored as 64 groups of 8 values:
+ *   dst[((rt*(cols/32) + ct)*64 + l)*8 + j] = src[rt*16 + l%16][ct*32 + 8*(l/16) + j].
+ * One-time set-up work, not part of the hot path.
+ */
+int des_pack_expert_weights(const void* src, void* dst, int64_t n_mats, int32_t rows,
+                            int32_t cols, void* hip_stream);
+
+const char* des_strerror(int code);
+/* Text of the last HIP error seen by this thread's DES_ERR_HIP ("" if none). */
+const char* des_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DES_H */

@@ -256,14 +256,17 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
                 K: int, C: int, mode: str, k_seq: int = 0,
                 shared: Optional[Tuple[np.ndarray, np.ndarray, np.ndarray]] = None,
                 logits_override: Optional[np.ndarray] = None,
-                compute_y: bool = True, residual: bool = False) -> Dict[str, object]:
+                compute_y: bool = True, residual: bool = False,
+                only_tokens: Optional[Sequence[Tuple[int, int]]] = None) -> Dict[str, object]:
     """Alg. 1 for B independent sequences.
 
     x: [B, N, D].  w_router [M, D]; w_gate, w_up [M, F, D]; w_down [M, D, F].
     shared: optional (wg [Fs, D], wu [Fs, D], wd [D, Fs]) always-on expert added
     with weight 1.  logits_override [B, N, M]: use these router logits instead
     of computing them (the routing decisions are then a function of exactly
-    these numbers).  Each sequence elects its own coreset.
+    these numbers).  Each sequence elects its own coreset.  only_tokens: compute
+    y only for these (sequence, token) pairs (the rest of y stays NaN); routing
+    is always computed for every token.
     """
     x = np.asarray(x)
     B, N, D = x.shape
@@ -298,11 +301,17 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
     if compute_y:
         cache = _F64Cache(w_gate, w_up, w_down)
         y = np.zeros((B, N, D), dtype=np.float64)
+        wanted = None
+        if only_tokens is not None:
+            y[:] = np.nan
+            wanted = set((int(b), int(n)) for b, n in only_tokens)
         sh = None
         if shared is not None:
             sh = tuple(np.asarray(m, dtype=np.float64) for m in shared)
         for b in range(B):
             for n in range(N):
+                if wanted is not None and (b, n) not in wanted:
+                    continue
                 acc = np.zeros(D, dtype=np.float64)
                 for j in range(K):
                     e = int(topk_idx[b, n, j])

@@ -1,0 +1,221 @@
+// C ABI of the DES library: argument validation on the host, then kernel
+// launches on the caller's stream.  Declarations and contracts: include/des.h.
+#include <stdio.h>
+#include <string.h>
+
+#include "des_common.h"
+
+namespace des {
+
+static thread_local char g_hip_error[256] = "";
+
+int hip_fail(hipError_t e, const char* what) {
+  snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+  return DES_ERR_HIP;
+}
+
+// Shape checks shared by all entry points.  `need_ffn` adds the checks that
+// only the expert FFN needs (alignment of F, Fs).
+static int check_shape(const des_shape_t* s, bool need_ffn) {
+  if (!s) return DES_ERR_NULL;
+  if (s->mode != DES_VANILLA && s->mode != DES_SEQ && s->mode != DES_VOTE) return DES_ERR_MODE;
+  if (s->dtype != DES_F32 && s->dtype != DES_BF16) return DES_ERR_DTYPE;
+  if (s->weight_layout != DES_LAYOUT_ROWMAJOR && s->weight_layout != DES_LAYOUT_PACKED)
+    return DES_ERR_DTYPE;
+  if (s->weight_layout == DES_LAYOUT_PACKED && s->dtype != DES_BF16) return DES_ERR_DTYPE;
+  if (s->n_seqs < 1 || s->n_tokens < 1 || s->hidden < 1 || s->n_experts < 1 || s->top_k < 1)
+    return DES_ERR_SHAPE;
+  if (s->top_k > s->n_experts || s->top_k > 32 || s->n_experts > 512) return DES_ERR_SHAPE;
+  const long long T = static_cast<long long>(s->n_seqs) * s->n_tokens;
+  if (T > 4096) return DES_ERR_SHAPE;
+  if (static_cast<long long>(s->n_experts) * ((T + 63) / 64) > 4096) return DES_ERR_SHAPE;
+  if (s->mode != DES_VANILLA && s->coreset < 1) return DES_ERR_SHAPE;
+  if (s->k_seq < 0 || s->k_seq > s->top_k) return DES_ERR_SHAPE;
+  if (s->mode == DES_SEQ && s->k_seq > 0) {
+    long long u = static_cast<long long>(s->n_tokens) * s->k_seq;
+    if (u > s->n_experts) u = s->n_experts;
+    if (s->coreset < u) return DES_ERR_SHAPE;
+  }
+  if (s->residual != 0 && s->residual != 1) return DES_ERR_SHAPE;
+  const int align = s->dtype == DES_BF16 ? 32 : 4;
+  if (s->hidden % align) return DES_ERR_SHAPE;
+  if (need_ffn) {
+    if (s->ffn < 1 || s->ffn_shared < 0) return DES_ERR_SHAPE;
+    if (s->ffn % align || s->ffn_shared % align) return DES_ERR_SHAPE;
+  }
+  return DES_OK;
+}
+
+}  // namespace des
+
+using namespace des;
+
+extern "C" {
+
+int32_t des_coreset_capacity(const des_shape_t* s) {
+  if (!s) return 0;
+  if (s->mode == DES_VANILLA) return s->n_experts;
+  return s->coreset < s->n_experts ? s->coreset : s->n_experts;
+}
+
+size_t des_workspace_bytes(const des_shape_t* s) {
+  if (check_shape(s, true) != DES_OK) return 0;
+  return ws_layout(*s).total;
+}
+
+int des_route(const des_shape_t* s, const void* x, const void* w_router, const float* router_bias,
+              float* logits, float* probs, void* hip_stream) {
+  int rc = check_shape(s, false);
+  if (rc != DES_OK) return rc;
+  if (!x || !w_router || !logits) return DES_ERR_NULL;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  rc = launch_router(*s, x, w_router, router_bias, logits, st);
+  if (rc != DES_OK) return rc;
+  if (probs) rc = launch_softmax(*s, logits, probs, st);
+  return rc;
+}
+
+int des_select_coreset(const des_shape_t* s, const float* logits, int32_t* coreset_idx,
+                       int32_t* coreset_size, float* votes, int32_t* k_seq_used,
+                       void* hip_stream) {
+  int rc = check_shape(s, false);
+  if (rc != DES_OK) return rc;
+  if (!logits || !coreset_idx || !coreset_size) return DES_ERR_NULL;
+  return launch_select(*s, logits, coreset_idx, coreset_size, votes, k_seq_used, nullptr, nullptr,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int des_moe_forward(const des_shape_t* s, const void* x, const void* w_router,
+                    const float* router_bias, const void* w_gate, const void* w_up,
+                    const void* w_down, const void* ws_gate, const void* ws_up,
+                    const void* ws_down, void* y, float* logits, int32_t* topk_idx, float* topk_w,
+                    int32_t* expert_counts, int32_t* n_unique, int32_t* coreset_idx,
+                    int32_t* coreset_size, void* workspace, size_t workspace_bytes,
+                    void* hip_stream) {
+  int rc = check_shape(s, true);
+  if (rc != DES_OK) return rc;
+  if (!x || !w_router || !w_gate || !w_up || !w_down || !y || !logits || !topk_idx || !topk_w ||
+      !expert_counts || !n_unique || !coreset_idx || !coreset_size || !workspace)
+    return DES_ERR_NULL;
+  if (s->ffn_shared > 0 && (!ws_gate || !ws_up || !ws_down)) return DES_ERR_NULL;
+  if (x == y) return DES_ERR_SHAPE;
+  if (workspace_bytes < ws_layout(*s).total) return DES_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return DES_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  rc = launch_router(*s, x, w_router, router_bias, logits, st);
+  if (rc != DES_OK) return rc;
+  rc = launch_select(*s, logits, coreset_idx, coreset_size, nullptr, nullptr, topk_idx, topk_w, st);
+  if (rc != DES_OK) return rc;
+  rc = launch_permute(*s, topk_idx, expert_counts, n_unique, ws, st);
+  if (rc != DES_OK) return rc;
+  return launch_ffn(*s, x, w_gate, w_up, w_down, ws_gate, ws_up, ws_down, topk_idx, topk_w, y, ws,
+                    st);
+}
+
+// Stack scratch: two activation ping-pong buffers, per-layer routing outputs
+// that the stack does not return, then one layer's workspace.
+struct StackLayout {
+  size_t xa, xb, logits, topk_idx, topk_w, core_idx, core_size, layer_ws, total;
+};
+static StackLayout stack_layout(const des_shape_t& s) {
+  const size_t T = static_cast<size_t>(s.n_seqs) * s.n_tokens;
+  const size_t el = s.dtype == DES_BF16 ? 2 : 4;
+  StackLayout l;
+  size_t p = 0;
+  l.xa = p; p = align256(p + T * s.hidden * el);
+  l.xb = p; p = align256(p + T * s.hidden * el);
+  l.logits = p; p = align256(p + 4 * T * s.n_experts);
+  l.topk_idx = p; p = align256(p + 4 * T * s.top_k);
+  l.topk_w = p; p = align256(p + 4 * T * s.top_k);
+  l.core_idx = p; p = align256(p + 4 * static_cast<size_t>(s.n_seqs) * des_coreset_capacity(&s));
+  l.core_size = p; p = align256(p + 4 * static_cast<size_t>(s.n_seqs));
+  l.layer_ws = p; p = p + ws_layout(s).total;
+  l.total = p;
+  return l;
+}
+
+size_t des_stack_workspace_bytes(const des_shape_t* s) {
+  if (check_shape(s, true) != DES_OK) return 0;
+  return stack_layout(*s).total;
+}
+
+int des_moe_stack_forward(const des_shape_t* s_in, int32_t n_layers, const void* x,
+                          const void* w_router, const float* router_bias, const void* w_gate,
+                          const void* w_up, const void* w_down, const void* ws_gate,
+                          const void* ws_up, const void* ws_down, void* y, int32_t* expert_counts,
+                          int32_t* n_unique, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  int rc = check_shape(s_in, true);
+  if (rc != DES_OK) return rc;
+  if (n_layers < 1) return DES_ERR_SHAPE;
+  if (!x || !w_router || !w_gate || !w_up || !w_down || !y || !expert_counts || !n_unique ||
+      !workspace)
+    return DES_ERR_NULL;
+  des_shape_t s = *s_in;
+  s.residual = 1;
+  if (s.ffn_shared > 0 && (!ws_gate || !ws_up || !ws_down)) return DES_ERR_NULL;
+  const StackLayout l = stack_layout(s);
+  if (workspace_bytes < l.total) return DES_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return DES_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  const size_t el = s.dtype == DES_BF16 ? 2 : 4;
+  const size_t M = s.n_experts, D = s.hidden, F = s.ffn, Fs = s.ffn_shared;
+  const char* cur = static_cast<const char*>(x);
+  for (int layer = 0; layer < n_layers; ++layer) {
+    // the last layer writes y; the others alternate between the two buffers
+    char* out = layer == n_layers - 1 ? static_cast<char*>(y)
+                                      : ws + ((layer & 1) ? l.xb : l.xa);
+    const size_t li = static_cast<size_t>(layer);
+    const char* wr = static_cast<const char*>(w_router) + li * M * D * el;
+    const float* rb = router_bias ? router_bias + li * M : nullptr;
+    const char* wg = static_cast<const char*>(w_gate) + li * M * F * D * el;
+    const char* wu = static_cast<const char*>(w_up) + li * M * F * D * el;
+    const char* wd = static_cast<const char*>(w_down) + li * M * F * D * el;
+    const char* sg = ws_gate ? static_cast<const char*>(ws_gate) + li * Fs * D * el : nullptr;
+    const char* su = ws_up ? static_cast<const char*>(ws_up) + li * Fs * D * el : nullptr;
+    const char* sd = ws_down ? static_cast<const char*>(ws_down) + li * Fs * D * el : nullptr;
+    float* logits = reinterpret_cast<float*>(ws + l.logits);
+    int32_t* tidx = reinterpret_cast<int32_t*>(ws + l.topk_idx);
+    float* tw = reinterpret_cast<float*>(ws + l.topk_w);
+    char* lws = ws + l.layer_ws;
+    rc = launch_router(s, cur, wr, rb, logits, st);
+    if (rc != DES_OK) return rc;
+    rc = launch_select(s, logits, reinterpret_cast<int32_t*>(ws + l.core_idx),
+                       reinterpret_cast<int32_t*>(ws + l.core_size), nullptr, nullptr, tidx, tw, st);
+    if (rc != DES_OK) return rc;
+    rc = launch_permute(s, tidx, expert_counts + li * M, n_unique + li, lws, st);
+    if (rc != DES_OK) return rc;
+    rc = launch_ffn(s, cur, wg, wu, wd, sg, su, sd, tidx, tw, out, lws, st);
+    if (rc != DES_OK) return rc;
+    cur = out;
+  }
+  return DES_OK;
+}
+
+int des_pack_expert_weights(const void* src, void* dst, int64_t n_mats, int32_t rows, int32_t cols,
+                            void* hip_stream) {
+  if (!src || !dst) return DES_ERR_NULL;
+  if (src == dst) return DES_ERR_SHAPE;
+  if (n_mats < 1 || rows < 16 || cols < 32 || rows % 16 || cols % 32) return DES_ERR_SHAPE;
+  if (n_mats * rows * static_cast<long long>(cols) / 8 / 256 > 0x7FFFFFFFLL) return DES_ERR_SHAPE;
+  return launch_pack(src, dst, n_mats, rows, cols, static_cast<hipStream_t>(hip_stream));
+}
+
+const char* des_strerror(int code) {
+  switch (code) {
+    case DES_OK: return "ok";
+    case DES_ERR_NULL: return "a required pointer is NULL";
+    case DES_ERR_SHAPE: return "shape out of range or not supported";
+    case DES_ERR_MODE: return "unknown mode";
+    case DES_ERR_DTYPE: return "unsupported dtype or weight layout";
+    case DES_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned";
+    case DES_ERR_HIP: return "a HIP call failed (see des_last_hip_error)";
+    default: return "unknown error code";
+  }
+}
+
+const char* des_last_hip_error(void) { return g_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,140 @@
+// Internal helpers shared by the HIP translation units of the DES library.
+// gfx950 (CDNA4) only: 64-wide wavefronts, DPP row broadcasts, bf16 MFMA.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/des.h"
+
+namespace des {
+
+constexpr int kWave = 64;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------- bf16 <-> f32
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+  return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+// round to nearest even (inputs are finite)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+// ------------------------------------------------------- wavefront reductions
+// DPP controls (GFX9): quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E,
+// row_shr:n = 0x110+n, row_bcast:15 = 0x142, row_bcast:31 = 0x143.
+// Lanes without a source keep `old`, which is the identity of the operation,
+// so after the six steps lane 63 holds the reduction over all 64 lanes.  The
+// combination order is fixed by the lane layout, hence bit-reproducible.
+template <int kCtrl>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t identity, uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(
+      static_cast<int>(identity), static_cast<int>(v), kCtrl, 0xF, 0xF, false));
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  v = max(v, dpp_u32<0xB1>(0u, v));
+  v = max(v, dpp_u32<0x4E>(0u, v));
+  v = max(v, dpp_u32<0x114>(0u, v));
+  v = max(v, dpp_u32<0x118>(0u, v));
+  v = max(v, dpp_u32<0x142>(0u, v));
+  v = max(v, dpp_u32<0x143>(0u, v));
+  return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), 63));
+}
+
+__device__ __forceinline__ float wave_sum_f32(float x) {
+  uint32_t v = __float_as_uint(x);
+#define DES_STEP(ctrl) v = __float_as_uint(__uint_as_float(v) + __uint_as_float(dpp_u32<ctrl>(0u, v)))
+  DES_STEP(0xB1);
+  DES_STEP(0x4E);
+  DES_STEP(0x114);
+  DES_STEP(0x118);
+  DES_STEP(0x142);
+  DES_STEP(0x143);
+#undef DES_STEP
+  return __uint_as_float(
+      static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), 63)));
+}
+
+__device__ __forceinline__ float readlane_f32(float x, int lane_uniform) {
+  return __uint_as_float(static_cast<uint32_t>(
+      __builtin_amdgcn_readlane(static_cast<int>(__float_as_uint(x)), lane_uniform)));
+}
+
+// Order-preserving map float -> uint32 for finite values; +0 and -0 coincide.
+// 0 is below every finite key and marks "not a candidate".
+__device__ __forceinline__ uint32_t order_key(float x) {
+  uint32_t u = __float_as_uint(x + 0.0f);  // -0 + +0 = +0
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// ------------------------------------------------------------ workspace layout
+// All offsets in bytes from the (256-byte aligned) workspace base.
+struct WsLayout {
+  size_t offsets;   // int32 [M + 1]   exclusive scan of expert_counts
+  size_t live;      // int32 [M]       expert ids with a non-zero count, ascending
+  size_t meta;      // int32 [8]       [0] = number of live experts, [1] = routed pairs
+  size_t perm;      // int32 [T*K]     pair ids (t*K + j) sorted by (expert, token)
+  size_t pos;       // int32 [T*K]     inverse of perm; -1 for unused slots
+  size_t h;         // act   [(T*K + Ts) * max(F, Fs)]   SwiGLU activations
+  size_t o;         // f32   [(T*K + Ts) * D]            per-pair expert outputs
+  size_t total;
+};
+
+inline size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+inline WsLayout ws_layout(const des_shape_t& s) {
+  const size_t T = static_cast<size_t>(s.n_seqs) * s.n_tokens;
+  const size_t TK = T * s.top_k;
+  const size_t Ts = s.ffn_shared > 0 ? T : 0;
+  const size_t act = s.dtype == DES_BF16 ? 2 : 4;
+  const size_t Fm = s.ffn > s.ffn_shared ? s.ffn : s.ffn_shared;
+  WsLayout w;
+  size_t p = 0;
+  w.offsets = p; p = align256(p + 4 * (static_cast<size_t>(s.n_experts) + 1));
+  w.live = p;    p = align256(p + 4 * static_cast<size_t>(s.n_experts));
+  w.meta = p;    p = align256(p + 4 * 8);
+  w.perm = p;    p = align256(p + 4 * TK);
+  w.pos = p;     p = align256(p + 4 * TK);
+  w.h = p;       p = align256(p + act * (TK + Ts) * Fm);
+  w.o = p;       p = align256(p + 4 * (TK + Ts) * static_cast<size_t>(s.hidden));
+  w.total = p;
+  return w;
+}
+
+// Worst-case number of live experts the FFN launches must cover.
+inline int max_live_experts(const des_shape_t& s) {
+  const long long TK = static_cast<long long>(s.n_seqs) * s.n_tokens * s.top_k;
+  long long m = s.n_experts;
+  if (s.mode != DES_VANILLA) {
+    long long c = s.coreset < s.n_experts ? s.coreset : s.n_experts;
+    long long u = c * s.n_seqs;
+    if (u < m) m = u;
+  }
+  if (TK < m) m = TK;
+  return static_cast<int>(m);
+}
+
+// Launchers implemented in the .hip files (host functions).
+int launch_router(const des_shape_t& s, const void* x, const void* w_router, const float* bias,
+                  float* logits, hipStream_t st);
+int launch_softmax(const des_shape_t& s, const float* logits, float* probs, hipStream_t st);
+int launch_select(const des_shape_t& s, const float* logits, int32_t* coreset_idx,
+                  int32_t* coreset_size, float* votes, int32_t* k_seq_used, int32_t* topk_idx,
+                  float* topk_w, hipStream_t st);
+int launch_permute(const des_shape_t& s, const int32_t* topk_idx, int32_t* expert_counts,
+                   int32_t* n_unique, char* ws, hipStream_t st);
+int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const void* w_up,
+               const void* w_down, const void* ws_gate, const void* ws_up, const void* ws_down,
+               const int32_t* topk_idx, const float* topk_w, void* y, char* ws, hipStream_t st);
+int launch_pack(const void* src, void* dst, int64_t n_mats, int rows, int cols, hipStream_t st);
+
+int hip_fail(hipError_t e, const char* what);  // records text, returns DES_ERR_HIP
+
+}  // namespace des

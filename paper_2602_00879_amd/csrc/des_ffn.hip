@@ -1,0 +1,599 @@
+// Grouped SwiGLU expert FFN and weighted combine (Alg. 1 stage 2, last line:
+// y_n = sum_{i in S_n} g_{n,i} E_i(x_n)), for gfx950.
+//
+// The layer is bound by the one-time read of the live experts' weights
+// (Eq. 2: the b * |union S_n| term), so the kernels are organised around the
+// weight stream, not around the tokens:
+//   * a wavefront owns 16 weight rows (gate and up rows of the same
+//     intermediate units, or 4 x 16 down rows) and walks the whole reduction
+//     dimension, loading each weight fragment straight into the matrix-core A
+//     operand with 16-byte loads - every weight byte is read by exactly one
+//     wavefront, exactly once;
+//   * the expert's tokens are the matrix-core B operand (16 tokens per tile,
+//     up to 16 tiles held in accumulators), so a partly empty token tile
+//     wastes matrix-core cycles, which are free here, and no bandwidth;
+//   * the grid is sized for the worst case and every wavefront looks its
+//     expert up in the device-resident live list, so the host never waits for
+//     the routing result.
+// Nothing is accumulated with floating-point atomics: gate/up writes the
+// SwiGLU activations H, down writes one fp32 row per (token, expert) pair, and
+// the combine adds a token's K rows in slot order.
+#include <type_traits>
+
+#include "des_common.h"
+
+namespace des {
+
+typedef std::integral_constant<int, 0> S0;
+typedef std::integral_constant<int, 1> S1;
+
+struct FfnArgs {
+  const void* x;
+  const void *wg, *wu, *wd;     // routed experts
+  const void *sg, *su, *sd;     // shared expert (or null)
+  const int32_t* topk_idx;      // [T][K]
+  const float* topk_w;          // [T][K]
+  const int32_t *offsets, *live, *meta, *perm, *pos;
+  void* h;                      // [(TK) x F] then [T x Fs]
+  float* o;                     // [(TK + T) x D]
+  void* y;                      // [T][D]
+  int T, D, M, F, Fs, K, n_slots, residual;
+};
+
+// Work item of one wavefront: which expert's rows, which pairs.
+struct Task {
+  const uint16_t *w0, *w1;  // weight matrices of the expert (gate, up) or (down, -)
+  int count;                // pairs of this expert
+  int pair0;                // first sorted position (routed) or 0 (shared)
+  bool shared;
+  size_t row_base;          // first H / O row of these pairs
+  int fdim;                 // F of this expert (F or Fs)
+};
+
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + expf(-z)); }
+
+// ------------------------------------------------------------------ bf16 path
+// MFMA 16x16x32 bf16: lane l supplies row (l%16), reduction elements
+// 8*(l/16)..+7 of both operands; the accumulator of lane l holds token column
+// (l%16) and weight rows 4*(l/16)..+3.
+//
+// Weight fragment address for (row tile rt, k-step ks):
+//   row-major [rows][kd]:  base + (rt*16 + l%16)*kd + ks*32 + 8*(l/16)
+//   packed tiles          :  base + ((rt*(kd/32) + ks)*64 + l)*8
+template <bool PACKED>
+__device__ __forceinline__ const uint16_t* frag_ptr(const uint16_t* base, int rt, int kd, int lane) {
+  if (PACKED) return base + (static_cast<size_t>(rt) * (kd / 32) * 64 + lane) * 8;
+  return base + (static_cast<size_t>(rt) * 16 + (lane & 15)) * kd + (lane >> 4) * 8;
+}
+template <bool PACKED>
+__device__ __forceinline__ constexpr int frag_step() { return PACKED ? 512 : 32; }
+
+__device__ __forceinline__ bf16x8 ld8(const uint16_t* p) {
+  return *reinterpret_cast<const bf16x8*>(p);
+}
+__device__ __forceinline__ bf16x8 zero8() {
+  bf16x8 z;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) z[i] = static_cast<__bf16>(0.0f);
+  return z;
+}
+
+// gate/up for pairs [g0, g0 + 16*NT) of the task, intermediate rows ft*16..+15
+template <int NT, int U, bool PACKED>
+__device__ __forceinline__ void gateup_group(const FfnArgs& a, const Task& t, int ft, int g0,
+                                             int lane) {
+  const int D = a.D;
+  const int nks = D / 32;
+  const uint16_t* x = static_cast<const uint16_t*>(a.x);
+  const uint16_t* gp = frag_ptr<PACKED>(t.w0, ft, D, lane);
+  const uint16_t* up = frag_ptr<PACKED>(t.w1, ft, D, lane);
+  const uint16_t* xp[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    int pi = min(g0 + i * 16 + (lane & 15), t.count - 1);  // clamped rows are dropped at the store
+    const int tok = t.shared ? pi : a.perm[t.pair0 + pi] / a.K;
+    xp[i] = x + static_cast<size_t>(tok) * D + (lane >> 4) * 8;
+  }
+  f32x4 accg[NT], accu[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    accg[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    accu[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  bf16x8 ag[2][U], au[2][U], bx[2][U][NT];
+
+  auto load = [&](int ks, auto stage) {
+    constexpr int s = decltype(stage)::value;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (ks + u < nks) {
+        ag[s][u] = ld8(gp + static_cast<size_t>(ks + u) * frag_step<PACKED>());
+        au[s][u] = ld8(up + static_cast<size_t>(ks + u) * frag_step<PACKED>());
+#pragma unroll
+        for (int i = 0; i < NT; ++i) bx[s][u][i] = ld8(xp[i] + (ks + u) * 32);
+      } else {
+        ag[s][u] = zero8();
+        au[s][u] = zero8();
+#pragma unroll
+        for (int i = 0; i < NT; ++i) bx[s][u][i] = zero8();
+      }
+    }
+  };
+  auto compute = [&](auto stage) {
+    constexpr int s = decltype(stage)::value;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        accg[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag[s][u], bx[s][u][i], accg[i], 0, 0, 0);
+        accu[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au[s][u], bx[s][u][i], accu[i], 0, 0, 0);
+      }
+  };
+  load(0, S0{});
+  for (int ks = 0; ks < nks; ks += 2 * U) {
+    load(ks + U, S1{});
+    compute(S0{});
+    load(ks + 2 * U, S0{});
+    compute(S1{});
+  }
+  uint16_t* h = static_cast<uint16_t*>(a.h);
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    const int pi = g0 + i * 16 + (lane & 15);
+    if (pi < t.count) {
+      u16x4 v;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) v[q] = f32_to_bf16_bits(silu_f(accg[i][q]) * accu[i][q]);
+      uint16_t* dst = h + (t.row_base + pi) * t.fdim + ft * 16 + 4 * (lane >> 4);
+      *reinterpret_cast<u16x4*>(dst) = v;
+    }
+  }
+}
+
+__device__ __forceinline__ bool make_task(const FfnArgs& a, int slot_or_shared, bool shared,
+                                          bool down, Task& t) {
+  const size_t TK = static_cast<size_t>(a.T) * a.K;
+  if (!shared) {
+    if (slot_or_shared >= a.meta[0]) return false;
+    const int e = a.live[slot_or_shared];
+    const int off = a.offsets[e];
+    t.count = a.offsets[e + 1] - off;
+    t.pair0 = off;
+    t.shared = false;
+    t.row_base = static_cast<size_t>(off);
+    t.fdim = a.F;
+    const size_t mat = static_cast<size_t>(a.F) * a.D;
+    if (down) {
+      t.w0 = static_cast<const uint16_t*>(a.wd) + e * mat;
+      t.w1 = nullptr;
+    } else {
+      t.w0 = static_cast<const uint16_t*>(a.wg) + e * mat;
+      t.w1 = static_cast<const uint16_t*>(a.wu) + e * mat;
+    }
+  } else {
+    t.count = a.T;
+    t.pair0 = 0;
+    t.shared = true;
+    t.row_base = TK;  // H: row index in units of its own stride, see h_base below
+    t.fdim = a.Fs;
+    t.w0 = static_cast<const uint16_t*>(down ? a.sd : a.sg);
+    t.w1 = static_cast<const uint16_t*>(down ? nullptr : a.su);
+  }
+  return true;
+}
+
+// H rows of the shared expert start after the TK routed rows of width F; they
+// have width Fs.  Express that start as a row offset in Fs-wide rows by
+// shifting the base pointer instead (keeps one indexing formula).
+__device__ __forceinline__ FfnArgs shared_view(const FfnArgs& a, Task& t, size_t elem_size) {
+  FfnArgs v = a;
+  const size_t TK = static_cast<size_t>(a.T) * a.K;
+  v.h = static_cast<char*>(a.h) + TK * a.F * elem_size;
+  t.row_base = 0;
+  return v;
+}
+
+constexpr int kFfnWaves = 2;  // wavefronts per workgroup; each is an independent task
+
+// MAXNT bounds the token tiles a task can have (the host knows T >= any expert's
+// count), so that small blocks get a kernel with few registers and high
+// occupancy.
+template <int MAXNT, bool PACKED>
+__global__ __launch_bounds__(kFfnWaves* kWave) void gateup_bf16_kernel(FfnArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int task = blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
+  const int tiles_r = a.F / 16;
+  const int routed = a.n_slots * tiles_r;
+  const int tiles_s = a.Fs / 16;
+  Task t;
+  int ft;
+  FfnArgs v = a;
+  if (task < routed) {
+    if (!make_task(a, task / tiles_r, false, false, t)) return;
+    ft = task % tiles_r;
+  } else if (task < routed + tiles_s) {
+    make_task(a, 0, true, false, t);
+    v = shared_view(a, t, 2);
+    ft = task - routed;
+  } else {
+    return;
+  }
+  const int nt = (t.count + 15) / 16;
+  if (MAXNT == 1 || nt <= 1) {
+    gateup_group<1, 4, PACKED>(v, t, ft, 0, lane);
+    return;
+  }
+  if constexpr (MAXNT >= 2) {
+    if (MAXNT == 2 || nt <= 2) {
+      gateup_group<2, 4, PACKED>(v, t, ft, 0, lane);
+      return;
+    }
+  }
+  if constexpr (MAXNT >= 4) {
+    if (MAXNT == 4 || nt <= 4) {
+      gateup_group<4, 2, PACKED>(v, t, ft, 0, lane);
+      return;
+    }
+  }
+  if constexpr (MAXNT >= 8) {
+    if (MAXNT == 8 || nt <= 8) {
+      gateup_group<8, 1, PACKED>(v, t, ft, 0, lane);
+      return;
+    }
+  }
+  if constexpr (MAXNT >= 16) {
+    for (int g0 = 0; g0 < t.count; g0 += 256) gateup_group<16, 1, PACKED>(v, t, ft, g0, lane);
+  }
+}
+
+// down for pairs [g0, g0+16*NT), output rows (dt0 .. dt0+RT-1)*16
+template <int RT, int NT, int U, bool PACKED>
+__device__ __forceinline__ void down_group(const FfnArgs& a, const Task& t, int dt0, int g0,
+                                           int lane) {
+  const int F = t.fdim;
+  const int nks = F / 32;
+  const uint16_t* h = static_cast<const uint16_t*>(a.h);
+  const uint16_t* ap[RT];
+#pragma unroll
+  for (int r = 0; r < RT; ++r) ap[r] = frag_ptr<PACKED>(t.w0, dt0 + r, F, lane);
+  const uint16_t* hp[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    const int pi = min(g0 + i * 16 + (lane & 15), t.count - 1);
+    hp[i] = h + (t.row_base + pi) * F + (lane >> 4) * 8;
+  }
+  f32x4 acc[RT][NT];
+#pragma unroll
+  for (int r = 0; r < RT; ++r)
+#pragma unroll
+    for (int i = 0; i < NT; ++i) acc[r][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  bf16x8 aw[2][U][RT], bh[2][U][NT];
+  auto load = [&](int ks, auto stage) {
+    constexpr int s = decltype(stage)::value;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (ks + u < nks) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+          aw[s][u][r] = ld8(ap[r] + static_cast<size_t>(ks + u) * frag_step<PACKED>());
+#pragma unroll
+        for (int i = 0; i < NT; ++i) bh[s][u][i] = ld8(hp[i] + (ks + u) * 32);
+      } else {
+#pragma unroll
+        for (int r = 0; r < RT; ++r) aw[s][u][r] = zero8();
+#pragma unroll
+        for (int i = 0; i < NT; ++i) bh[s][u][i] = zero8();
+      }
+    }
+  };
+  auto compute = [&](auto stage) {
+    constexpr int s = decltype(stage)::value;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+          acc[r][i] =
+              __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw[s][u][r], bh[s][u][i], acc[r][i], 0, 0, 0);
+  };
+  load(0, S0{});
+  for (int ks = 0; ks < nks; ks += 2 * U) {
+    load(ks + U, S1{});
+    compute(S0{});
+    load(ks + 2 * U, S0{});
+    compute(S1{});
+  }
+  const size_t orow0 = t.shared ? static_cast<size_t>(a.T) * a.K : static_cast<size_t>(t.pair0);
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    const int pi = g0 + i * 16 + (lane & 15);
+    if (pi < t.count) {
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+        float* dst = a.o + (orow0 + pi) * a.D + (dt0 + r) * 16 + 4 * (lane >> 4);
+        *reinterpret_cast<f32x4*>(dst) = acc[r][i];
+      }
+    }
+  }
+}
+
+template <int MAXNT, bool PACKED>
+__global__ __launch_bounds__(kFfnWaves* kWave) void down_bf16_kernel(FfnArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int task = blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
+  const int dtiles = a.D / 16;
+  const int groups = (dtiles + 3) / 4;  // 64 output rows per task
+  const int routed = a.n_slots * groups;
+  Task t;
+  int dg;
+  FfnArgs v = a;
+  if (task < routed) {
+    if (!make_task(a, task / groups, false, true, t)) return;
+    dg = task % groups;
+  } else if (a.Fs > 0 && task < routed + groups) {
+    make_task(a, 0, true, true, t);
+    v = shared_view(a, t, 2);
+    dg = task - routed;
+  } else {
+    return;
+  }
+  const int dt_begin = dg * 4;
+  const int dt_end = min(dt_begin + 4, dtiles);
+  const int nt = (t.count + 15) / 16;
+  if (dt_end - dt_begin == 4) {
+    if (MAXNT == 1 || nt <= 1) {
+      down_group<4, 1, 4, PACKED>(v, t, dt_begin, 0, lane);
+      return;
+    }
+    if constexpr (MAXNT >= 2) {
+      if (MAXNT == 2 || nt <= 2) {
+        down_group<4, 2, 2, PACKED>(v, t, dt_begin, 0, lane);
+        return;
+      }
+    }
+    if constexpr (MAXNT >= 4) {
+      if (MAXNT == 4 || nt <= 4) {
+        down_group<4, 4, 1, PACKED>(v, t, dt_begin, 0, lane);
+        return;
+      }
+    }
+    if constexpr (MAXNT >= 8) {
+      if (MAXNT == 8 || nt <= 8) {
+        down_group<2, 8, 1, PACKED>(v, t, dt_begin, 0, lane);
+        down_group<2, 8, 1, PACKED>(v, t, dt_begin + 2, 0, lane);
+        return;
+      }
+    }
+  }
+  // ragged row group, or more than 128 pairs: one row tile at a time
+  for (int dt = dt_begin; dt < dt_end; ++dt) {
+    if constexpr (MAXNT <= 4) {
+      down_group<1, MAXNT, 2, PACKED>(v, t, dt, 0, lane);
+    } else {
+      for (int g0 = 0; g0 < t.count; g0 += 16 * MAXNT)
+        down_group<1, MAXNT, 1, PACKED>(v, t, dt, g0, lane);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ fp32 path
+// Plain fused-multiply-add kernels for the small fp32 configuration: one
+// wavefront per output element row-chunk, lanes stride the reduction
+// dimension with 16-byte loads, fixed-order wave reduction.
+__device__ __forceinline__ float dot_f32(const float* a, const float* b, int n, int lane) {
+  const float4* pa = reinterpret_cast<const float4*>(a);
+  const float4* pb = reinterpret_cast<const float4*>(b);
+  float s = 0.f;
+  for (int v = lane; v < n / 4; v += 64) {
+    const float4 p = pa[v], q = pb[v];
+    s = fmaf(p.x, q.x, s);
+    s = fmaf(p.y, q.y, s);
+    s = fmaf(p.z, q.z, s);
+    s = fmaf(p.w, q.w, s);
+  }
+  return wave_sum_f32(s);
+}
+
+// grid.x = sorted pair row r in [0, TK + Ts); grid.y tiles the F (or D) rows.
+__device__ __forceinline__ bool f32_row(const FfnArgs& a, int r, int& e, int& tok, bool& shared) {
+  const int TK = a.T * a.K;
+  if (r < TK) {
+    if (r >= a.meta[1]) return false;  // fewer routed pairs than slots (k_eff < K)
+    const int p = a.perm[r];
+    e = a.topk_idx[p];
+    tok = p / a.K;
+    shared = false;
+    return true;
+  }
+  e = 0;
+  tok = r - TK;
+  shared = true;
+  return a.Fs > 0;
+}
+
+__global__ __launch_bounds__(256) void gateup_f32_kernel(FfnArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x;
+  int e, tok;
+  bool sh;
+  if (!f32_row(a, r, e, tok, sh)) return;
+  const int F = sh ? a.Fs : a.F;
+  const size_t TK = static_cast<size_t>(a.T) * a.K;
+  const float* xg = static_cast<const float*>(a.x) + static_cast<size_t>(tok) * a.D;
+  const float* wg = sh ? static_cast<const float*>(a.sg)
+                       : static_cast<const float*>(a.wg) + static_cast<size_t>(e) * a.F * a.D;
+  const float* wu = sh ? static_cast<const float*>(a.su)
+                       : static_cast<const float*>(a.wu) + static_cast<size_t>(e) * a.F * a.D;
+  float* h = static_cast<float*>(a.h) +
+             (sh ? TK * a.F + static_cast<size_t>(tok) * a.Fs : static_cast<size_t>(r) * a.F);
+  for (int f = blockIdx.y * 4 + wave; f < F; f += gridDim.y * 4) {
+    const float g = dot_f32(xg, wg + static_cast<size_t>(f) * a.D, a.D, lane);
+    const float u = dot_f32(xg, wu + static_cast<size_t>(f) * a.D, a.D, lane);
+    if (lane == 0) h[f] = silu_f(g) * u;
+  }
+}
+
+__global__ __launch_bounds__(256) void down_f32_kernel(FfnArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x;
+  int e, tok;
+  bool sh;
+  if (!f32_row(a, r, e, tok, sh)) return;
+  const int F = sh ? a.Fs : a.F;
+  const size_t TK = static_cast<size_t>(a.T) * a.K;
+  const float* h = static_cast<const float*>(a.h) +
+                   (sh ? TK * a.F + static_cast<size_t>(tok) * a.Fs : static_cast<size_t>(r) * a.F);
+  const float* wd = sh ? static_cast<const float*>(a.sd)
+                       : static_cast<const float*>(a.wd) + static_cast<size_t>(e) * a.F * a.D;
+  float* o = a.o + static_cast<size_t>(r) * a.D;
+  for (int d = blockIdx.y * 4 + wave; d < a.D; d += gridDim.y * 4) {
+    const float s = dot_f32(h, wd + static_cast<size_t>(d) * F, F, lane);
+    if (lane == 0) o[d] = s;
+  }
+}
+
+// ---------------------------------------------------------------- combine
+// y[t][d] = sum_j topk_w[t][j] * O[pos[t*K+j]][d]  (slot order j = 0..K-1)
+//           (+ O[TK + t][d] shared) (+ x[t][d] residual); 4 columns per thread.
+template <bool BF16>
+__global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
+  const int t = blockIdx.x;
+  const int d = (blockIdx.y * 256 + threadIdx.x) * 4;
+  if (d >= a.D) return;
+  const int K = a.K;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int j = 0; j < K; ++j) {
+    const int r = a.pos[t * K + j];
+    if (r < 0) continue;
+    const float w = a.topk_w[t * K + j];
+    const float4 v = *reinterpret_cast<const float4*>(a.o + static_cast<size_t>(r) * a.D + d);
+    acc.x = fmaf(w, v.x, acc.x);
+    acc.y = fmaf(w, v.y, acc.y);
+    acc.z = fmaf(w, v.z, acc.z);
+    acc.w = fmaf(w, v.w, acc.w);
+  }
+  if (a.Fs > 0) {
+    const size_t r = static_cast<size_t>(a.T) * K + t;
+    const float4 v = *reinterpret_cast<const float4*>(a.o + r * a.D + d);
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  const size_t xo = static_cast<size_t>(t) * a.D + d;
+  if (BF16) {
+    if (a.residual) {
+      const u16x4 xv = *reinterpret_cast<const u16x4*>(static_cast<const uint16_t*>(a.x) + xo);
+      acc.x += bf16_bits_to_f32(xv[0]); acc.y += bf16_bits_to_f32(xv[1]);
+      acc.z += bf16_bits_to_f32(xv[2]); acc.w += bf16_bits_to_f32(xv[3]);
+    }
+    u16x4 out;
+    out[0] = f32_to_bf16_bits(acc.x); out[1] = f32_to_bf16_bits(acc.y);
+    out[2] = f32_to_bf16_bits(acc.z); out[3] = f32_to_bf16_bits(acc.w);
+    *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(a.y) + xo) = out;
+  } else {
+    if (a.residual) {
+      const float4 xv = *reinterpret_cast<const float4*>(static_cast<const float*>(a.x) + xo);
+      acc.x += xv.x; acc.y += xv.y; acc.z += xv.z; acc.w += xv.w;
+    }
+    *reinterpret_cast<float4*>(static_cast<float*>(a.y) + xo) = acc;
+  }
+}
+
+// ------------------------------------------------------------------ packing
+// dst tile layout documented in des.h (des_pack_expert_weights).
+__global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ src,
+                                                   uint16_t* __restrict__ dst, int rows, int cols,
+                                                   long long groups_total) {
+  // one thread per group of 8 values
+  const long long g = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
+  if (g >= groups_total) return;
+  const long long per_mat = static_cast<long long>(rows) * cols / 8;
+  const long long m = g / per_mat;
+  long long q = g % per_mat;
+  const int l = static_cast<int>(q % 64);
+  q /= 64;
+  const int ct = static_cast<int>(q % (cols / 32));
+  const int rt = static_cast<int>(q / (cols / 32));
+  const uint16_t* s = src + m * rows * cols + static_cast<long long>(rt * 16 + (l & 15)) * cols +
+                      ct * 32 + 8 * (l >> 4);
+  *reinterpret_cast<uint4*>(dst + g * 8) = *reinterpret_cast<const uint4*>(s);
+}
+
+int launch_pack(const void* src, void* dst, int64_t n_mats, int rows, int cols, hipStream_t st) {
+  const long long groups = n_mats * rows * static_cast<long long>(cols) / 8;
+  const long long blocks = (groups + 255) / 256;
+  hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
+                     static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), rows, cols,
+                     groups);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? DES_OK : hip_fail(e, "pack launch");
+}
+
+// ------------------------------------------------------------------ launcher
+int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const void* w_up,
+               const void* w_down, const void* ws_gate, const void* ws_up, const void* ws_down,
+               const int32_t* topk_idx, const float* topk_w, void* y, char* ws, hipStream_t st) {
+  const WsLayout w = ws_layout(s);
+  FfnArgs a;
+  a.x = x;
+  a.wg = w_gate; a.wu = w_up; a.wd = w_down;
+  a.sg = ws_gate; a.su = ws_up; a.sd = ws_down;
+  a.topk_idx = topk_idx;
+  a.topk_w = topk_w;
+  a.offsets = reinterpret_cast<const int32_t*>(ws + w.offsets);
+  a.live = reinterpret_cast<const int32_t*>(ws + w.live);
+  a.meta = reinterpret_cast<const int32_t*>(ws + w.meta);
+  a.perm = reinterpret_cast<const int32_t*>(ws + w.perm);
+  a.pos = reinterpret_cast<const int32_t*>(ws + w.pos);
+  a.h = ws + w.h;
+  a.o = reinterpret_cast<float*>(ws + w.o);
+  a.y = y;
+  a.T = s.n_seqs * s.n_tokens;
+  a.D = s.hidden; a.M = s.n_experts; a.F = s.ffn; a.Fs = s.ffn_shared; a.K = s.top_k;
+  a.n_slots = max_live_experts(s);
+  a.residual = s.residual;
+  const int TK = a.T * a.K;
+
+  if (s.dtype == DES_BF16) {
+    const bool packed = s.weight_layout == DES_LAYOUT_PACKED;
+    const int gu_tasks = a.n_slots * (a.F / 16) + a.Fs / 16;
+    const int gu_blocks = (gu_tasks + kFfnWaves - 1) / kFfnWaves;
+    const int groups = (a.D / 16 + 3) / 4;
+    const int dn_tasks = a.n_slots * groups + (a.Fs > 0 ? groups : 0);
+    const int dn_blocks = (dn_tasks + kFfnWaves - 1) / kFfnWaves;
+    // an expert serves a token at most once, so no task has more than T pairs
+    const int maxnt = (a.T + 15) / 16;
+    const dim3 blk(kFfnWaves * kWave);
+#define DES_LAUNCH_FFN(NTV, PK)                                                             \
+  do {                                                                                      \
+    hipLaunchKernelGGL((gateup_bf16_kernel<NTV, PK>), dim3(gu_blocks), blk, 0, st, a);      \
+    hipLaunchKernelGGL((down_bf16_kernel<NTV, PK>), dim3(dn_blocks), blk, 0, st, a);        \
+  } while (0)
+#define DES_LAUNCH_BY_NT(PK)                                                                \
+  do {                                                                                      \
+    if (maxnt <= 1) DES_LAUNCH_FFN(1, PK);                                                  \
+    else if (maxnt <= 2) DES_LAUNCH_FFN(2, PK);                                             \
+    else if (maxnt <= 4) DES_LAUNCH_FFN(4, PK);                                             \
+    else if (maxnt <= 8) DES_LAUNCH_FFN(8, PK);                                             \
+    else DES_LAUNCH_FFN(16, PK);                                                            \
+  } while (0)
+    if (packed) DES_LAUNCH_BY_NT(true);
+    else DES_LAUNCH_BY_NT(false);
+#undef DES_LAUNCH_BY_NT
+#undef DES_LAUNCH_FFN
+    dim3 cg(a.T, (a.D / 4 + 255) / 256);
+    hipLaunchKernelGGL(combine_kernel<true>, cg, dim3(256), 0, st, a);
+  } else {
+    const int rows = TK + (a.Fs > 0 ? a.T : 0);
+    const int Fm = a.F > a.Fs ? a.F : a.Fs;
+    hipLaunchKernelGGL(gateup_f32_kernel, dim3(rows, (Fm + 3) / 4 > 64 ? 64 : (Fm + 3) / 4),
+                       dim3(256), 0, st, a);
+    hipLaunchKernelGGL(down_f32_kernel, dim3(rows, (a.D + 3) / 4 > 64 ? 64 : (a.D + 3) / 4),
+                       dim3(256), 0, st, a);
+    dim3 cg(a.T, (a.D / 4 + 255) / 256);
+    hipLaunchKernelGGL(combine_kernel<false>, cg, dim3(256), 0, st, a);
+  }
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? DES_OK : hip_fail(e, "ffn launch");
+}
+
+}  // namespace des

@@ -1,0 +1,124 @@
+"""Glue for the GPU parity tests: moves seeded workloads to the device, calls
+the C ABI through the binding and compares with the CPU oracle.  Holds no
+arithmetic of the method."""
+from __future__ import annotations
+
+import math
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from oracle import des_oracle as O
+from paper_2602_00879_amd import binding as B
+from paper_2602_00879_amd import workloads as W
+
+# Output tolerances of the benchmark definition.
+BF16_MAX_ABS, BF16_REL_L2 = 2e-2, 1e-2
+F32_REL = 1e-5
+# fp32 router accumulation against the float64 oracle (sqrt(D)*eps*|logit| << this)
+LOGIT_ATOL = 5e-5
+GATE_RTOL, GATE_ATOL = 1e-5, 1e-7
+VOTE_MARGIN_MIN = 1e-5
+
+
+def dev_tensor(a: Optional[np.ndarray], device="cuda") -> Optional[torch.Tensor]:
+    if a is None:
+        return None
+    if a.dtype == np.uint16:  # bf16 bit patterns
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+def to_numpy(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return t.float().cpu().numpy()
+    return t.cpu().numpy()
+
+
+def layer_to_device(layer: Dict, device="cuda") -> Dict:
+    d = {k: dev_tensor(layer[k], device) for k in ("x", "w_router", "bias", "w_gate", "w_up", "w_down")}
+    d["shared"] = tuple(dev_tensor(m, device) for m in layer["shared"]) if layer.get("shared") else None
+    return d
+
+
+def shape_of(cfg: W.LayerConfig, mode: str, C: Optional[int] = None, k_seq: int = 0,
+             layout: int = B.DES_LAYOUT_ROWMAJOR, residual: int = 0) -> B.DesShape:
+    return B.make_shape(cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k,
+                        cfg.coreset if C is None else C, mode, cfg.dtype, ffn_shared=cfg.ffn_shared,
+                        k_seq=k_seq, weight_layout=layout, residual=residual)
+
+
+def oracle_inputs(layer: Dict) -> Dict:
+    """float64 views of a workload for the oracle (exact widening)."""
+    o = {k: (None if layer[k] is None else W.to_f64(layer[k]))
+         for k in ("x", "w_router", "w_gate", "w_up", "w_down")}
+    o["bias"] = None if layer["bias"] is None else layer["bias"].astype(np.float64)
+    o["shared"] = tuple(W.to_f64(m) for m in layer["shared"]) if layer.get("shared") else None
+    return o
+
+
+def run_gpu(cfg, layer_dev, mode, C=None, k_seq=0, layout=B.DES_LAYOUT_ROWMAJOR, residual=0,
+            packed_weights=None):
+    shape = shape_of(cfg, mode, C, k_seq, layout, residual)
+    wg, wu, wd = (layer_dev["w_gate"], layer_dev["w_up"], layer_dev["w_down"])
+    sh = layer_dev["shared"]
+    if packed_weights is not None:
+        wg, wu, wd, sh = packed_weights
+    out = B.des_moe_forward(shape, layer_dev["x"], layer_dev["w_router"], layer_dev["bias"],
+                            wg, wu, wd, shared=sh)
+    torch.cuda.synchronize()
+    return out
+
+
+def check_against_oracle(cfg, layer, out, mode, C=None, k_seq=0, residual=False,
+                         only_tokens=None, label=""):
+    """Teacher-forced parity: the oracle is fed the GPU's fp32 logits, so every
+    index decision is a function of identical numbers and must match exactly."""
+    C = cfg.coreset if C is None else C
+    oi = oracle_inputs(layer)
+    B_, N, M, K = cfg.n_seqs, cfg.n_tokens, cfg.n_experts, cfg.top_k
+    g_logits = out.logits.cpu().numpy()
+    # 1. router scores against the float64 definition
+    ref_logits = O.router_logits(oi["x"].reshape(B_ * N, -1), oi["w_router"], oi["bias"]).reshape(B_, N, M)
+    err = np.abs(g_logits - ref_logits).max()
+    assert err <= LOGIT_ATOL, f"{label}: router logits off by {err}"
+    # 2. routing, teacher-forced
+    ref = O.moe_forward(oi["x"], oi["w_router"], oi["bias"], oi["w_gate"], oi["w_up"], oi["w_down"],
+                        K, C, mode, k_seq=k_seq, shared=oi["shared"], logits_override=g_logits,
+                        residual=residual, only_tokens=only_tokens)
+    if mode == "vote":
+        assert min(ref["margins"]) > VOTE_MARGIN_MIN, f"{label}: vote boundary too close to call"
+    cap = out.coreset_idx.shape[1]
+    g_core = out.coreset_idx.cpu().numpy()
+    g_size = out.coreset_size.cpu().numpy()
+    for b in range(B_):
+        core = ref["coresets"][b]
+        assert g_size[b] == len(core), f"{label}: coreset size {g_size[b]} vs {len(core)}"
+        assert g_core[b, :len(core)].tolist() == core, f"{label}: coreset differs (seq {b})"
+        assert np.all(g_core[b, len(core):] == -1)
+        assert len(core) <= cap
+    assert np.array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"]), f"{label}: topk_idx differs"
+    np.testing.assert_allclose(out.topk_w.cpu().numpy(), ref["topk_w"], rtol=GATE_RTOL, atol=GATE_ATOL,
+                               err_msg=f"{label}: gates")
+    assert np.array_equal(out.expert_counts.cpu().numpy(), ref["counts"]), f"{label}: counts differ"
+    assert int(out.n_unique.cpu()[0]) == ref["n_unique"], f"{label}: n_unique differs"
+    # 3. layer output
+    y = to_numpy(out.y).astype(np.float64)
+    y_ref = ref["y"]
+    if only_tokens is not None:
+        sel = np.zeros((B_, N), dtype=bool)
+        for (b, n) in only_tokens:
+            sel[b, n] = True
+        y, y_ref = y[sel], y_ref[sel]
+    max_abs = np.abs(y - y_ref).max()
+    rel_l2 = math.sqrt(((y - y_ref) ** 2).sum() / max((y_ref ** 2).sum(), 1e-300))
+    if cfg.dtype == "bf16":
+        assert max_abs <= BF16_MAX_ABS and rel_l2 <= BF16_REL_L2, \
+            f"{label}: max_abs {max_abs:.3e} rel_l2 {rel_l2:.3e}"
+    else:
+        rel_max = max_abs / max(np.abs(y_ref).max(), 1e-300)
+        assert rel_l2 <= F32_REL and rel_max <= F32_REL, \
+            f"{label}: rel_l2 {rel_l2:.3e} rel_max {rel_max:.3e}"
+    return dict(max_abs=max_abs, rel_l2=rel_l2, n_unique=ref["n_unique"],
+                min_margin=min(ref["margins"]))

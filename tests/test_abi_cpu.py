@@ -1,0 +1,98 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the
+header declares, sizes its workspace and rejects bad arguments before any
+launch.  No compute call is made, so this runs without a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_00879_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "des.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(des_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS), (names, B.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def _shape(**kw):
+    base = dict(n_seqs=1, n_tokens=32, hidden=2048, n_experts=128, ffn=768, top_k=8, coreset=32,
+                mode="vote", dtype="bf16")
+    base.update(kw)
+    return B.make_shape(**base)
+
+
+def test_workspace_and_capacity_are_host_only():
+    s = _shape()
+    assert B.des_coreset_capacity(s) == 32
+    assert B.des_coreset_capacity(_shape(mode="vanilla")) == 128
+    assert B.des_coreset_capacity(_shape(coreset=500)) == 128
+    n = B.des_workspace_bytes(s)
+    TK = 32 * 8
+    assert n >= TK * 768 * 2 + TK * 2048 * 4 and n % 256 == 0
+    assert B.des_workspace_bytes(_shape(ffn_shared=512)) > n
+    assert B.des_stack_workspace_bytes(s) > n
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(mode=7), -3),
+    (dict(dtype=5), -4),
+    (dict(dtype="f32", weight_layout=1), -4),
+    (dict(n_tokens=0), -2),
+    (dict(top_k=129), -2),
+    (dict(top_k=33, n_experts=64), -2),
+    (dict(n_experts=513), -2),
+    (dict(coreset=0), -2),
+    (dict(k_seq=9), -2),
+    (dict(hidden=2040), -2),
+    (dict(ffn=100), -2),
+    (dict(n_seqs=200), -2),
+    (dict(mode="seq", k_seq=2, coreset=32), -2),   # union of 32*2 may not fit 32
+    (dict(residual=2), -2),
+])
+def test_bad_shapes_are_rejected_before_launch(kw, code):
+    s = _shape(**kw)
+    L = B.lib()
+    args = [ctypes.c_void_p(256 * (i + 1)) for i in range(18)]  # never dereferenced
+    rc = L.des_moe_forward(ctypes.byref(s), *args, ctypes.c_size_t(1 << 40), None)
+    assert rc == code, B.strerror(rc)
+    assert B.des_workspace_bytes(s) == 0
+
+
+def test_null_and_workspace_errors():
+    s = _shape()
+    L = B.lib()
+    one = ctypes.c_void_p(256)
+    args = [ctypes.c_void_p(256 * (i + 1)) for i in range(18)]   # never dereferenced
+    assert L.des_moe_forward(ctypes.byref(s), *args, ctypes.c_size_t(16), None) == -5
+    misaligned = list(args)
+    misaligned[17] = ctypes.c_void_p(257 + 3)
+    assert L.des_moe_forward(ctypes.byref(s), *misaligned, ctypes.c_size_t(1 << 40), None) == -5
+    bad = list(args)
+    bad[0] = None
+    assert L.des_moe_forward(ctypes.byref(s), *bad, ctypes.c_size_t(1 << 40), None) == -1
+    sh = _shape(ffn_shared=512)
+    no_shared = list(args)
+    no_shared[6] = None
+    assert L.des_moe_forward(ctypes.byref(sh), *no_shared, ctypes.c_size_t(1 << 40), None) == -1
+    assert L.des_route(ctypes.byref(s), None, one, None, one, None, None) == -1
+    assert L.des_select_coreset(ctypes.byref(s), one, None, one, None, None, None) == -1
+    assert L.des_pack_expert_weights(one, one, 1, 16, 32, None) == -2
+    assert L.des_pack_expert_weights(one, ctypes.c_void_p(512), 1, 15, 32, None) == -2
+    assert L.des_moe_forward(None, *args, ctypes.c_size_t(0), None) == -1
+    assert "workspace" in B.strerror(-5) and B.strerror(0) == "ok"
+    # x and y must differ
+    alias = list(args)
+    alias[9] = alias[0]
+    assert L.des_moe_forward(ctypes.byref(s), *alias, ctypes.c_size_t(1 << 40), None) == -2

@@ -1,0 +1,254 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Integer outputs (coreset, per-token experts, counts)
+must be bit-exact given the GPU's own fp32 logits; gates within 1e-5; layer
+outputs within the tolerances of the benchmark definition."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import des_oracle as O
+from paper_2602_00879_amd import binding as B
+from paper_2602_00879_amd import workloads as W
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ des_route
+@pytest.mark.parametrize("dtype,T,D,M,bias", [
+    ("f32", 8, 256, 16, False), ("f32", 5, 64, 7, True),
+    ("bf16", 32, 2048, 128, True), ("bf16", 19, 96, 40, False), ("bf16", 256, 2048, 256, False),
+])
+def test_route_logits_and_softmax(dtype, T, D, M, bias):
+    _say(f"route {dtype} T={T} D={D} M={M}")
+    cfg = W.LayerConfig("r", dtype, 1, T, D, M, 32, 0, 1, 1, 1.1 if bias else 0.0, 41)
+    rng = np.random.default_rng(41)
+    x = W._normal(rng, (1, T, D), 1.0, dtype)
+    wr = W._normal(rng, (M, D), 0.05, dtype)
+    b = W.zipf_bias(M, 1.1, rng) if bias else None
+    shape = H.shape_of(cfg, "vanilla")
+    logits, probs = B.des_route(shape, H.dev_tensor(x), H.dev_tensor(wr), H.dev_tensor(b))
+    torch.cuda.synchronize()
+    ref = O.router_logits(W.to_f64(x)[0], W.to_f64(wr), None if b is None else b.astype(np.float64))
+    assert np.abs(logits.cpu().numpy()[0] - ref).max() <= H.LOGIT_ATOL
+    pref = O.softmax_rows(logits.cpu().numpy()[0].astype(np.float64))
+    np.testing.assert_allclose(probs.cpu().numpy()[0], pref, rtol=1e-5, atol=1e-9)
+
+
+# --------------------------------------------------------- des_select_coreset
+def _select_case(N, M, K, C, mode, k_seq, seed, B_=1, ties=False, zipf=0.0):
+    Ls = []
+    for b in range(B_):
+        L = W.make_logits(N, M, seed * 31 + b, zipf_s=zipf, scale=2.0)
+        if ties:  # few distinct values -> many exact ties, also between +0 and -0
+            L = np.round(L).astype(np.float32)
+            L[L == 0] = np.where(np.arange((L == 0).sum()) % 2 == 0, 0.0, -0.0).astype(np.float32)
+        Ls.append(L)
+    logits = np.stack(Ls)
+    shape = B.make_shape(B_, N, 32, M, 32, K, C, mode, "f32", k_seq=k_seq)
+    out = B.des_select_coreset(shape, torch.from_numpy(logits).cuda())
+    torch.cuda.synchronize()
+    cap = B.des_coreset_capacity(shape)
+    for b in range(B_):
+        ref = O.select_coreset(logits[b].astype(np.float64), mode, K, C, k_seq)
+        core = ref["coreset"]
+        tag = f"N={N} M={M} K={K} C={C} {mode} k_seq={k_seq} seed={seed} b={b} ties={ties}"
+        if mode == "vote" and not ties:
+            assert ref["margin"] > H.VOTE_MARGIN_MIN, tag
+        if mode == "vote" and ties and ref["margin"] <= H.VOTE_MARGIN_MIN:
+            continue  # fp32 vs float64 vote sums may order a near-tie either way
+        assert int(out["coreset_size"][b]) == len(core), tag
+        got = out["coreset_idx"][b].cpu().numpy()
+        assert got[:len(core)].tolist() == core, tag
+        assert np.all(got[len(core):] == -1) and len(core) <= cap, tag
+        if mode == "vote":
+            np.testing.assert_allclose(out["votes"][b].cpu().numpy(), ref["votes"], rtol=1e-5,
+                                       atol=1e-9, err_msg=tag)
+        if mode == "seq":
+            assert int(out["k_seq_used"][b]) == ref["k_seq_used"], tag
+
+
+@pytest.mark.parametrize("mode", ["vanilla", "seq", "vote"])
+def test_select_coreset_shapes(mode):
+    cases = [  # N, M, K, C
+        (1, 16, 2, 4), (8, 16, 2, 4), (32, 128, 8, 32), (32, 256, 8, 16), (32, 256, 8, 64),
+        (4, 128, 8, 32), (128, 128, 8, 32), (33, 100, 5, 17), (7, 65, 3, 65), (64, 512, 8, 48),
+        (17, 3, 3, 2), (50, 300, 32, 100), (3, 40, 8, 64),
+    ]
+    for i, (N, M, K, C) in enumerate(cases):
+        _say(f"select {mode} N={N} M={M} K={K} C={C}")
+        _select_case(N, M, K, C, mode, 0, seed=100 + i, B_=1 + (i % 3))
+        _select_case(N, M, K, C, mode, 0, seed=200 + i, ties=True)
+
+
+def test_select_seq_explicit_k_and_overflow():
+    for (N, M, K, k) in [(8, 16, 2, 1), (32, 128, 8, 3), (32, 128, 8, 2), (32, 256, 8, 8), (5, 64, 4, 4)]:
+        _say(f"seq explicit N={N} M={M} K={K} k={k}")
+        _select_case(N, M, K, min(M, N * k), "seq", k, seed=300 + k)
+    # C below the number of distinct top-1 experts -> nomination-count rule
+    for (N, M, K, C) in [(32, 128, 8, 3), (64, 256, 8, 10), (16, 64, 4, 1)]:
+        _say(f"seq overflow N={N} M={M} K={K} C={C}")
+        _select_case(N, M, K, C, "seq", 0, seed=400 + C)
+        _select_case(N, M, K, C, "seq", 0, seed=500 + C, ties=True)
+
+
+def test_select_zipf_skew_many_seeds():
+    for seed in range(20):
+        _select_case(32, 128, 8, 32, "vote", 0, seed=600 + seed, zipf=1.1)
+        _select_case(32, 128, 8, 32, "seq", 0, seed=700 + seed, zipf=1.1)
+
+
+# ------------------------------------------------------------ des_moe_forward
+@pytest.mark.parametrize("mode,C,k_seq", [("vanilla", 4, 0), ("seq", 8, 1), ("seq", 4, 0), ("vote", 4, 0)])
+def test_tiny_f32_layer(mode, C, k_seq):
+    cfg = W.CONFIGS["tiny_f32"]
+    _say(f"tiny_f32 {mode} C={C} k_seq={k_seq}")
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    out = H.run_gpu(cfg, dev, mode, C=C, k_seq=k_seq)
+    r = H.check_against_oracle(cfg, layer, out, mode, C=C, k_seq=k_seq, label=f"tiny {mode}")
+    _say(f"  rel_l2={r['rel_l2']:.2e} unique={r['n_unique']}")
+
+
+MID = dict(
+    # several row tiles with ragged tails: F=96 (6 tiles), D=160 (10 tiles: 2.5 groups of 4),
+    # N=20 tokens (two token tiles, the second ragged), two sequences, shared expert
+    mid_bf16=W.LayerConfig("mid_bf16", "bf16", 2, 20, 160, 40, 96, 64, 4, 10, 1.1, 11),
+    mid_f32=W.LayerConfig("mid_f32", "f32", 2, 9, 72, 24, 20, 12, 3, 6, 1.1, 12),
+    wide_tok=W.LayerConfig("wide_tok", "bf16", 1, 150, 128, 12, 64, 0, 4, 3, 0.0, 13),
+    many_tok=W.LayerConfig("many_tok", "bf16", 3, 100, 64, 8, 32, 32, 2, 2, 0.0, 14),
+)
+
+
+@pytest.mark.parametrize("name", list(MID))
+@pytest.mark.parametrize("mode", ["vanilla", "seq", "vote"])
+def test_mid_layers(name, mode):
+    cfg = MID[name]
+    _say(f"{name} {mode}")
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    for residual in (0, 1):
+        out = H.run_gpu(cfg, dev, mode, residual=residual)
+        r = H.check_against_oracle(cfg, layer, out, mode, residual=bool(residual),
+                                   label=f"{name} {mode} res={residual}")
+    _say(f"  rel_l2={r['rel_l2']:.2e} max_abs={r['max_abs']:.2e} unique={r['n_unique']}")
+    if cfg.dtype == "bf16":
+        packed = tuple(B.des_pack_expert_weights(dev[k]) for k in ("w_gate", "w_up", "w_down"))
+        psh = tuple(B.des_pack_expert_weights(m) for m in dev["shared"]) if dev["shared"] else None
+        out2 = H.run_gpu(cfg, dev, mode, layout=B.DES_LAYOUT_PACKED, packed_weights=(*packed, psh))
+        out1 = H.run_gpu(cfg, dev, mode)
+        assert torch.equal(out1.y, out2.y), "packed layout must give bit-identical output"
+        assert torch.equal(out1.topk_idx, out2.topk_idx)
+
+
+def test_pack_layout_definition():
+    rows, cols, n = 32, 64, 3
+    src = torch.arange(n * rows * cols, dtype=torch.int16, device="cuda").view(torch.bfloat16).view(n, rows, cols)
+    dst = B.des_pack_expert_weights(src)
+    torch.cuda.synchronize()
+    s = src.view(torch.int16).cpu().numpy()
+    d = dst.view(torch.int16).cpu().numpy().reshape(n, -1)
+    for m in range(n):
+        for rt in range(rows // 16):
+            for ct in range(cols // 32):
+                for l in (0, 1, 15, 16, 37, 63):
+                    for j in (0, 3, 7):
+                        got = d[m, ((rt * (cols // 32) + ct) * 64 + l) * 8 + j]
+                        assert got == s[m, rt * 16 + l % 16, ct * 32 + 8 * (l // 16) + j]
+
+
+def test_runs_are_bit_identical():
+    cfg = MID["mid_bf16"]
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    a = H.run_gpu(cfg, dev, "vote")
+    ya, ia, wa = a.y.clone(), a.topk_idx.clone(), a.topk_w.clone()
+    for _ in range(3):
+        b = H.run_gpu(cfg, dev, "vote")
+        assert torch.equal(ya, b.y) and torch.equal(ia, b.topk_idx) and torch.equal(wa, b.topk_w)
+
+
+def test_coreset_smaller_than_k():
+    # a single token with C=2 < K=4: k_eff = 2, unused slots are -1 / 0
+    cfg = W.LayerConfig("small_core", "bf16", 1, 1, 64, 16, 32, 0, 4, 2, 0.0, 15)
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    out = H.run_gpu(cfg, dev, "vote")
+    H.check_against_oracle(cfg, layer, out, "vote", label="small_core")
+    idx = out.topk_idx.cpu().numpy()[0, 0]
+    assert (idx[:2] >= 0).all() and (idx[2:] == -1).all()
+    assert out.topk_w.cpu().numpy()[0, 0, 2:].tolist() == [0.0, 0.0]
+
+
+# ----------------------------------------------------- full-size configurations
+def _sample_tokens(cfg, n, seed):
+    rng = np.random.default_rng(seed)
+    all_t = [(b, t) for b in range(cfg.n_seqs) for t in range(cfg.n_tokens)]
+    pick = rng.choice(len(all_t), size=min(n, len(all_t)), replace=False)
+    return [all_t[i] for i in sorted(pick)]
+
+
+def test_m128_zipf_full_size():
+    """128 experts, D=2048, F=768, K=8, N=32, Zipf-skewed router: DES-Vote C=32
+    against vanilla, in the launch configuration the benchmark times."""
+    cfg = W.CONFIGS["m128_zipf"]
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    packed = tuple(B.des_pack_expert_weights(dev[k]) for k in ("w_gate", "w_up", "w_down"))
+    res = {}
+    for mode in ("vote", "vanilla", "seq"):
+        _say(f"m128_zipf {mode}")
+        out = H.run_gpu(cfg, dev, mode)
+        res[mode] = H.check_against_oracle(cfg, layer, out, mode, label=f"m128 {mode}")
+        _say(f"  {res[mode]}")
+        out_p = H.run_gpu(cfg, dev, mode, layout=B.DES_LAYOUT_PACKED, packed_weights=(*packed, None))
+        assert torch.equal(out.y, out_p.y)
+    assert res["vote"]["n_unique"] <= 32 < res["vanilla"]["n_unique"]
+
+
+def test_m256_shared_full_size():
+    """256 experts + always-on shared expert, softmax router, no bias:
+    DES-Seq and DES-Vote at C in {16, 32, 64}."""
+    cfg = W.CONFIGS["m256_shared"]
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    for mode in ("vote", "seq"):
+        for C in (16, 32, 64):
+            _say(f"m256_shared {mode} C={C}")
+            out = H.run_gpu(cfg, dev, mode, C=C)
+            toks = None if C == 32 else _sample_tokens(cfg, 6, C)
+            r = H.check_against_oracle(cfg, layer, out, mode, C=C, only_tokens=toks,
+                                       label=f"m256 {mode} C={C}")
+            _say(f"  {r}")
+            assert r["n_unique"] <= C
+
+
+def test_m128_block_size_sweep():
+    """N in {4..128} on the 128-expert layer: unique experts flat under
+    DES-Vote, growing under vanilla; outputs checked on sampled tokens."""
+    base = W.CONFIGS["m128_sweep"]
+    layer = W.make_layer(base, with_x=False)
+    dev_w = None
+    uniq = {}
+    for N in (4, 8, 16, 32, 64, 128):
+        cfg = base.with_(n_tokens=N)
+        rng = np.random.default_rng([base.seed, N])
+        layer["x"] = W._normal(rng, (1, N, cfg.hidden), 1.0, cfg.dtype)
+        if dev_w is None:
+            dev_w = H.layer_to_device(layer)
+        dev_w["x"] = H.dev_tensor(layer["x"])
+        for mode in ("vote", "vanilla"):
+            _say(f"sweep N={N} {mode}")
+            out = H.run_gpu(cfg, dev_w, mode)
+            r = H.check_against_oracle(cfg, layer, out, mode, only_tokens=_sample_tokens(cfg, 8, N),
+                                       label=f"sweep N={N} {mode}")
+            uniq[(N, mode)] = r["n_unique"]
+            _say(f"  {r}")
+    assert all(uniq[(N, "vote")] <= 32 for N in (4, 8, 16, 32, 64, 128))
+    assert uniq[(128, "vanilla")] > uniq[(32, "vanilla")] > uniq[(4, "vanilla")]
