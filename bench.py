@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the DES MoE-layer hot path on one MI355X.
+
+A "step" is one pass of the whole path - router, coreset election,
+constrained re-routing, permutation, grouped SwiGLU expert FFN, combine - over
+one block of synthetic tokens, through the C ABI (des_moe_forward).  The
+workload is the 128-expert bf16 layer (D=2048, F=768, K=8, N=32, Zipf-skewed
+router bias) under DES-Vote with a coreset of 32; inputs are resident in HBM
+before the timed region.  To keep the 256 MB last-level cache from serving the
+expert weights, successive steps rotate over several replicas of the layer's
+weights at different addresses.
+
+Prints one JSON line: metric = microseconds per block (lower is better), plus
+  roofline     - the dominant kernel (gate/up projection) against the 8 TB/s
+                 HBM peak, its duration measured with HIP events in this run;
+  cpu_baseline - the CPU oracle timed on this host on the same block.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM traffic of the dominant kernel from rocprofv3 counters, in bytes per
+# launch (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size); the
+# summaries are under profiles/.  None until measured for a workload/layout.
+MEASURED_TRAFFIC = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="m128_zipf",
+                    choices=["m128_zipf", "m256_shared", "tiny_f32"])
+    ap.add_argument("--mode", default="vote", choices=["vanilla", "seq", "vote"])
+    ap.add_argument("--coreset", type=int, default=None)
+    ap.add_argument("--n-tokens", type=int, default=None)
+    ap.add_argument("--layout", default="packed", choices=["packed", "rowmajor"])
+    ap.add_argument("--replicas", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true", help="also time the steps replayed from a HIP graph")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2602_00879_amd import binding as B
+    from paper_2602_00879_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.lib()  # fails loudly if the HIP library has not been built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = W.CONFIGS[args.workload]
+    if args.n_tokens:
+        cfg = cfg.with_(n_tokens=args.n_tokens)
+    C = args.coreset if args.coreset else cfg.coreset
+    layer = W.make_layer(cfg)
+
+    def dev_t(a):
+        if a is None:
+            return None
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    packed = args.layout == "packed" and cfg.dtype == "bf16"
+    layout = B.DES_LAYOUT_PACKED if packed else B.DES_LAYOUT_ROWMAJOR
+    shape = B.make_shape(cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k, C,
+                         args.mode, cfg.dtype, ffn_shared=cfg.ffn_shared, weight_layout=layout)
+    x = dev_t(layer["x"])
+    w_router, bias = dev_t(layer["w_router"]), dev_t(layer["bias"])
+
+    def prep(a):
+        t = dev_t(a)
+        return B.des_pack_expert_weights(t) if packed else t
+
+    base = [prep(layer[k]) for k in ("w_gate", "w_up", "w_down")]
+    shared = tuple(prep(m) for m in layer["shared"]) if layer["shared"] else None
+    torch.cuda.synchronize()
+    # replicas: same values at different addresses, so that a step never finds
+    # its expert weights in the last-level cache
+    replicas = [base] + [[t.clone() for t in base] for _ in range(max(1, args.replicas) - 1)]
+    bufs = B.MoeBuffers(shape, dev, x.dtype)
+
+    def step(i):
+        wg, wu, wd = replicas[i % len(replicas)]
+        B.des_moe_forward(shape, x, w_router, bias, wg, wu, wd, shared=shared, buffers=bufs)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    n_unique = int(bufs.n_unique.cpu()[0])
+
+    # per-kernel durations: the same steps again with an event pair around
+    # every kernel on the launch stream
+    B.des_kernel_timing_enable(True)
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    kt = B.des_kernel_timing_read()
+    B.des_kernel_timing_enable(False)
+    kernels_us = {k: (v[0] * 1e3 / v[1]) for k, v in kt.items() if v[1] > 0}
+
+    graph_us = None
+    if args.graph:
+        g = torch.cuda.CUDAGraph()
+        n_rep = len(replicas)
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            for i in range(3):
+                step(i)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(g, stream=s):
+                for i in range(n_rep):
+                    step(i)
+        torch.cuda.synchronize()
+        reps = max(1, args.steps // n_rep)
+        g.replay()
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - tg0) * 1e6 / (reps * n_rep)
+
+    el = 2 if cfg.dtype == "bf16" else 4
+    per_expert = 3 * cfg.hidden * cfg.ffn * el
+    unique_bytes = n_unique * per_expert + (3 * cfg.hidden * cfg.ffn_shared * el)
+    gateup_bytes = n_unique * 2 * cfg.hidden * cfg.ffn * el + 2 * cfg.hidden * cfg.ffn_shared * el
+    dom_us = kernels_us.get("gateup")
+    achieved = gateup_bytes / (dom_us * 1e-6) / 1e9 if dom_us else None
+    roofline = {
+        "bound": "hbm", "kernel": "gateup", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
+        "traffic": MEASURED_TRAFFIC.get((args.workload, args.mode, args.layout)),
+        "algorithmic_bytes_per_launch": gateup_bytes, "avg_launch_us": dom_us,
+    }
+    ffn_us = sum(kernels_us.get(k, 0.0) for k in ("gateup", "down"))
+    expert_gbs_step = unique_bytes / (ms_per_step * 1e-3) / 1e9
+    expert_gbs_ffn = unique_bytes / (ffn_us * 1e-6) / 1e9 if ffn_us else None
+
+    out = {
+        "metric": "MoE-layer us per N-token block (DES-Vote, whole hot path)",
+        "value": ms_per_step * 1e3, "unit": "us/block", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload}: M={cfg.n_experts} D={cfg.hidden} F={cfg.ffn} "
+                               f"Fs={cfg.ffn_shared} K={cfg.top_k} N={cfg.n_tokens} B={cfg.n_seqs} "
+                               f"mode={args.mode} C={C} zipf_s={cfg.zipf_s}",
+                   "weight_layout": args.layout, "weight_replicas": len(replicas)},
+        "n_unique_experts": n_unique,
+        "unique_expert_bytes": unique_bytes,
+        "expert_weight_GBps_whole_step": expert_gbs_step,
+        "expert_weight_GBps_ffn_kernels": expert_gbs_ffn,
+        "pct_of_hbm_peak_whole_step": 100.0 * expert_gbs_step / HBM_PEAK_GBS,
+        "pct_of_hbm_peak_ffn_kernels": (100.0 * expert_gbs_ffn / HBM_PEAK_GBS) if expert_gbs_ffn else None,
+        "kernel_us": kernels_us,
+        "graph_replay_us_per_block": graph_us,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, layer, args.mode, C)
+    print(json.dumps(out))
+
+
+def cpu_baseline(cfg, layer, mode, C):
+    """The CPU oracle, as it stands, on the same block (bounded sample: the
+    router + election + routing for the whole block and the expert FFN for as
+    many of its tokens as fit in about 20 s), scaled to one block."""
+    from oracle import des_oracle as O
+    from paper_2602_00879_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:  # pragma: no cover
+        threads = 1
+    f64 = {k: W.to_f64(layer[k]) for k in ("x", "w_router")}
+    bias = None if layer["bias"] is None else layer["bias"].astype(np.float64)
+    wg, wu, wd = layer["w_gate"], layer["w_up"], layer["w_down"]
+
+    class Lazy:  # widen one expert at a time (exact), as the oracle's cache asks for it
+        def __init__(self, a):
+            self.a = a
+
+        def __getitem__(self, e):
+            return W.to_f64(self.a[e])
+
+    shared = tuple(W.to_f64(m) for m in layer["shared"]) if layer["shared"] else None
+    B_, N = cfg.n_seqs, cfg.n_tokens
+    n_sample = min(N, 8)
+    toks = [(0, n) for n in range(n_sample)]
+    t0 = time.perf_counter()
+    O.moe_forward(f64["x"], f64["w_router"], bias, Lazy(wg), Lazy(wu), Lazy(wd), cfg.top_k, C, mode,
+                  shared=shared, only_tokens=toks)
+    dt = time.perf_counter() - t0
+    # routing cost is counted once; the FFN part scales with the tokens
+    t1 = time.perf_counter()
+    O.moe_forward(f64["x"], f64["w_router"], bias, Lazy(wg), Lazy(wu), Lazy(wd), cfg.top_k, C, mode,
+                  shared=shared, compute_y=False)
+    dt_route = time.perf_counter() - t1
+    per_block = dt_route + (dt - dt_route) * (B_ * N) / n_sample
+    return {"value": per_block * 1e6, "unit": "us/block", "cores": threads, "kind": "oracle",
+            "sample": f"routing of the whole block + expert FFN of {n_sample} of {B_ * N} tokens "
+                      f"({dt:.1f} s measured), FFN part scaled to the block",
+            "host_cpus": len(os.sched_getaffinity(0))}
+
+
+if __name__ == "__main__":
+    main()

@@ -142,7 +142,10 @@ int des_select_coreset(const des_shape_t* shape, const float* logits, int32_t* c
  * topk_idx [B][N][K] int32 in rank order, unused slots -1; topk_w [B][N][K]
  * fp32, unused slots 0; expert_counts [M] int32 = pairs routed to each expert
  * summed over sequences (cnt_i of Eq. 2); n_unique [1] int32 = experts with a
- * non-zero count (|union S_n|); coreset_idx / coreset_size as above.
+ * non-zero count (|union S_n|), or -1 if an internal bounded wait between the
+ * routing stages expired (a fault of the device or of a concurrent misuse of
+ * the workspace; the other outputs are then undefined); coreset_idx /
+ * coreset_size as above.
  * ws_gate / ws_up / ws_down: the shared expert ([Fs][D], [Fs][D], [D][Fs], same
  * dtype and layout rule), required iff ffn_shared > 0.
  * y must not alias x.  workspace: >= des_workspace_bytes(shape), 256-byte
@@ -183,6 +186,21 @@ int des_moe_stack_forward(const des_shape_t* shape, int32_t n_layers, const void
  */
 int des_pack_expert_weights(const void* src, void* dst, int64_t n_mats, int32_t rows,
                             int32_t cols, void* hip_stream);
+
+/*
+ * Measurement aid, off by default and not part of the hot path: while enabled,
+ * every kernel launch of this library is bracketed by a pair of HIP events on
+ * the launch stream (the events are created on the host at launch time, so do
+ * not enable it under graph capture).  des_kernel_timing_read() waits for the
+ * recorded events and returns the accumulated duration and launch count of one
+ * kernel id in [0, des_kernel_timing_count()); des_kernel_timing_name() names
+ * it (router, softmax, select, permute, gateup, down, combine, pack).
+ * des_kernel_timing_enable() also clears the accumulators.  Not thread-safe.
+ */
+int des_kernel_timing_enable(int enable);
+int des_kernel_timing_count(void);
+const char* des_kernel_timing_name(int kernel_id);
+int des_kernel_timing_read(int kernel_id, double* total_ms, int64_t* launches);
 
 const char* des_strerror(int code);
 /* Text of the last HIP error seen by this thread's DES_ERR_HIP ("" if none). */

@@ -24,6 +24,8 @@ EXPORTS = (
     "des_coreset_capacity", "des_workspace_bytes", "des_route", "des_select_coreset",
     "des_moe_forward", "des_stack_workspace_bytes", "des_moe_stack_forward",
     "des_pack_expert_weights", "des_strerror", "des_last_hip_error",
+    "des_kernel_timing_enable", "des_kernel_timing_count", "des_kernel_timing_name",
+    "des_kernel_timing_read",
 )
 
 
@@ -73,6 +75,15 @@ def lib() -> ctypes.CDLL:
         L.des_strerror.argtypes = [ctypes.c_int]
         L.des_last_hip_error.restype = ctypes.c_char_p
         L.des_last_hip_error.argtypes = []
+        L.des_kernel_timing_enable.restype = ctypes.c_int
+        L.des_kernel_timing_enable.argtypes = [ctypes.c_int]
+        L.des_kernel_timing_count.restype = ctypes.c_int
+        L.des_kernel_timing_count.argtypes = []
+        L.des_kernel_timing_name.restype = ctypes.c_char_p
+        L.des_kernel_timing_name.argtypes = [ctypes.c_int]
+        L.des_kernel_timing_read.restype = ctypes.c_int
+        L.des_kernel_timing_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                             ctypes.POINTER(ctypes.c_int64)]
         _lib = L
     return _lib
 
@@ -217,3 +228,17 @@ def des_pack_expert_weights(src: torch.Tensor) -> torch.Tensor:
     dst = torch.empty_like(src)
     _check(lib().des_pack_expert_weights(_ptr(src), _ptr(dst), n_mats, rows, cols, _stream()))
     return dst
+
+
+def des_kernel_timing_enable(enable: bool) -> None:
+    _check(lib().des_kernel_timing_enable(1 if enable else 0))
+
+
+def des_kernel_timing_read() -> Dict[str, Tuple[float, int]]:
+    """{kernel name: (total ms, launches)} accumulated since timing was enabled."""
+    out = {}
+    for k in range(lib().des_kernel_timing_count()):
+        ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+        _check(lib().des_kernel_timing_read(k, ctypes.byref(ms), ctypes.byref(n)))
+        out[lib().des_kernel_timing_name(k).decode()] = (ms.value, n.value)
+    return out

@@ -3,6 +3,9 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+#include <vector>
+
 #include "des_common.h"
 
 namespace des {
@@ -13,6 +16,45 @@ int hip_fail(hipError_t e, const char* what) {
   snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
   return DES_ERR_HIP;
 }
+
+// ---- optional per-kernel timing (a measurement aid, never on by default) ----
+bool g_timing_on = false;
+namespace {
+struct TimedLaunch { int id; hipEvent_t start, stop; };
+std::vector<TimedLaunch> g_timed;
+double g_ms[kKCount];
+long long g_launches[kKCount];
+}  // namespace
+
+void timing_mark(int kernel_id, hipStream_t st, bool begin) {
+  if (begin) {
+    TimedLaunch t;
+    t.id = kernel_id;
+    if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) return;
+    (void)hipEventRecord(t.start, st);
+    g_timed.push_back(t);
+  } else if (!g_timed.empty() && g_timed.back().id == kernel_id) {
+    (void)hipEventRecord(g_timed.back().stop, st);
+  }
+}
+
+static void timing_collect() {
+  for (TimedLaunch& t : g_timed) {
+    float ms = 0.f;
+    if (hipEventSynchronize(t.stop) == hipSuccess &&
+        hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
+      g_ms[t.id] += ms;
+      g_launches[t.id] += 1;
+    }
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
+  }
+  g_timed.clear();
+}
+
+// Epoch of the routing launch's flags: never zero, never repeated in a process.
+static std::atomic<unsigned long long> g_epoch{0x5eed000000000001ull};
+static unsigned long long next_epoch() { return g_epoch.fetch_add(1, std::memory_order_relaxed); }
 
 // Shape checks shared by all entry points.  `need_ffn` adds the checks that
 // only the expert FFN needs (alignment of F, Fs).
@@ -81,7 +123,7 @@ int des_select_coreset(const des_shape_t* s, const float* logits, int32_t* cores
   int rc = check_shape(s, false);
   if (rc != DES_OK) return rc;
   if (!logits || !coreset_idx || !coreset_size) return DES_ERR_NULL;
-  return launch_select(*s, logits, coreset_idx, coreset_size, votes, k_seq_used, nullptr, nullptr,
+  return launch_select(*s, logits, coreset_idx, coreset_size, votes, k_seq_used,
                        static_cast<hipStream_t>(hip_stream));
 }
 
@@ -103,11 +145,8 @@ int des_moe_forward(const des_shape_t* s, const void* x, const void* w_router,
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return DES_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  rc = launch_router(*s, x, w_router, router_bias, logits, st);
-  if (rc != DES_OK) return rc;
-  rc = launch_select(*s, logits, coreset_idx, coreset_size, nullptr, nullptr, topk_idx, topk_w, st);
-  if (rc != DES_OK) return rc;
-  rc = launch_permute(*s, topk_idx, expert_counts, n_unique, ws, st);
+  rc = launch_routing(*s, x, w_router, router_bias, logits, coreset_idx, coreset_size, topk_idx,
+                      topk_w, expert_counts, n_unique, ws, next_epoch(), st);
   if (rc != DES_OK) return rc;
   return launch_ffn(*s, x, w_gate, w_up, w_down, ws_gate, ws_up, ws_down, topk_idx, topk_w, y, ws,
                     st);
@@ -180,12 +219,9 @@ int des_moe_stack_forward(const des_shape_t* s_in, int32_t n_layers, const void*
     int32_t* tidx = reinterpret_cast<int32_t*>(ws + l.topk_idx);
     float* tw = reinterpret_cast<float*>(ws + l.topk_w);
     char* lws = ws + l.layer_ws;
-    rc = launch_router(s, cur, wr, rb, logits, st);
-    if (rc != DES_OK) return rc;
-    rc = launch_select(s, logits, reinterpret_cast<int32_t*>(ws + l.core_idx),
-                       reinterpret_cast<int32_t*>(ws + l.core_size), nullptr, nullptr, tidx, tw, st);
-    if (rc != DES_OK) return rc;
-    rc = launch_permute(s, tidx, expert_counts + li * M, n_unique + li, lws, st);
+    rc = launch_routing(s, cur, wr, rb, logits, reinterpret_cast<int32_t*>(ws + l.core_idx),
+                        reinterpret_cast<int32_t*>(ws + l.core_size), tidx, tw,
+                        expert_counts + li * M, n_unique + li, lws, next_epoch(), st);
     if (rc != DES_OK) return rc;
     rc = launch_ffn(s, cur, wg, wu, wd, sg, su, sd, tidx, tw, out, lws, st);
     if (rc != DES_OK) return rc;
@@ -217,5 +253,29 @@ const char* des_strerror(int code) {
 }
 
 const char* des_last_hip_error(void) { return g_hip_error; }
+
+int des_kernel_timing_enable(int enable) {
+  timing_collect();
+  for (int i = 0; i < kKCount; ++i) { g_ms[i] = 0.0; g_launches[i] = 0; }
+  g_timing_on = enable != 0;
+  return DES_OK;
+}
+
+int des_kernel_timing_count(void) { return kKCount; }
+
+const char* des_kernel_timing_name(int kernel_id) {
+  static const char* names[kKCount] = {"router", "softmax", "select", "permute", "gateup",
+                                       "down", "combine", "pack", "routing"};
+  return (kernel_id >= 0 && kernel_id < kKCount) ? names[kernel_id] : "";
+}
+
+int des_kernel_timing_read(int kernel_id, double* total_ms, int64_t* launches) {
+  if (!total_ms || !launches) return DES_ERR_NULL;
+  if (kernel_id < 0 || kernel_id >= kKCount) return DES_ERR_SHAPE;
+  timing_collect();
+  *total_ms = g_ms[kernel_id];
+  *launches = g_launches[kernel_id];
+  return DES_OK;
+}
 
 }  // extern "C"

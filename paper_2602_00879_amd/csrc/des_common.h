@@ -75,39 +75,6 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 }
 
 // ------------------------------------------------------------ workspace layout
-// All offsets in bytes from the (256-byte aligned) workspace base.
-struct WsLayout {
-  size_t offsets;   // int32 [M + 1]   exclusive scan of expert_counts
-  size_t live;      // int32 [M]       expert ids with a non-zero count, ascending
-  size_t meta;      // int32 [8]       [0] = number of live experts, [1] = routed pairs
-  size_t perm;      // int32 [T*K]     pair ids (t*K + j) sorted by (expert, token)
-  size_t pos;       // int32 [T*K]     inverse of perm; -1 for unused slots
-  size_t h;         // act   [(T*K + Ts) * max(F, Fs)]   SwiGLU activations
-  size_t o;         // f32   [(T*K + Ts) * D]            per-pair expert outputs
-  size_t total;
-};
-
-inline size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
-
-inline WsLayout ws_layout(const des_shape_t& s) {
-  const size_t T = static_cast<size_t>(s.n_seqs) * s.n_tokens;
-  const size_t TK = T * s.top_k;
-  const size_t Ts = s.ffn_shared > 0 ? T : 0;
-  const size_t act = s.dtype == DES_BF16 ? 2 : 4;
-  const size_t Fm = s.ffn > s.ffn_shared ? s.ffn : s.ffn_shared;
-  WsLayout w;
-  size_t p = 0;
-  w.offsets = p; p = align256(p + 4 * (static_cast<size_t>(s.n_experts) + 1));
-  w.live = p;    p = align256(p + 4 * static_cast<size_t>(s.n_experts));
-  w.meta = p;    p = align256(p + 4 * 8);
-  w.perm = p;    p = align256(p + 4 * TK);
-  w.pos = p;     p = align256(p + 4 * TK);
-  w.h = p;       p = align256(p + act * (TK + Ts) * Fm);
-  w.o = p;       p = align256(p + 4 * (TK + Ts) * static_cast<size_t>(s.hidden));
-  w.total = p;
-  return w;
-}
-
 // Worst-case number of live experts the FFN launches must cover.
 inline int max_live_experts(const des_shape_t& s) {
   const long long TK = static_cast<long long>(s.n_seqs) * s.n_tokens * s.top_k;
@@ -121,20 +88,75 @@ inline int max_live_experts(const des_shape_t& s) {
   return static_cast<int>(m);
 }
 
+// The fused routing launch is used when all of its workgroups (router tiles +
+// one per sequence + one) are resident at once; the chip holds 512 of them.
+constexpr int kMaxFusedRoutingBlocks = 256;
+
+// All offsets in bytes from the (256-byte aligned) workspace base.
+struct WsLayout {
+  size_t flags;     // u64   [router tiles + B]  epoch flags of the routing launch
+  size_t offsets;   // int32 [M + 1]   exclusive scan of expert_counts
+  size_t slots;     // int4  [n_slots] {expert, first sorted pair, pairs, 0}; expert -1 = unused
+  size_t meta;      // int32 [64]      [0] live experts, [1] routed pairs
+  size_t pair_tok;  // int32 [T*K]     token of each pair, pairs sorted by (expert, token)
+  size_t pos;       // int32 [T*K]     sorted position of pair t*K+j; -1 for unused slots
+  size_t h;         // act   [(T*K + Ts) * max(F, Fs)]   SwiGLU activations
+  size_t o;         // f32   [(T*K + Ts) * D]            per-pair expert outputs
+  size_t total;
+};
+
+inline size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+inline WsLayout ws_layout(const des_shape_t& s) {
+  const size_t T = static_cast<size_t>(s.n_seqs) * s.n_tokens;
+  const size_t TK = T * s.top_k;
+  const size_t Ts = s.ffn_shared > 0 ? T : 0;
+  const size_t act = s.dtype == DES_BF16 ? 2 : 4;
+  const size_t Fm = s.ffn > s.ffn_shared ? s.ffn : s.ffn_shared;
+  const size_t tiles = static_cast<size_t>((s.n_experts + 15) / 16) * ((T + 15) / 16);
+  WsLayout w;
+  size_t p = 0;
+  w.flags = p;    p = align256(p + 8 * (tiles + s.n_seqs));
+  w.offsets = p;  p = align256(p + 4 * (static_cast<size_t>(s.n_experts) + 1));
+  w.slots = p;    p = align256(p + 16 * static_cast<size_t>(max_live_experts(s)));
+  w.meta = p;     p = align256(p + 4 * 64);
+  w.pair_tok = p; p = align256(p + 4 * TK);
+  w.pos = p;      p = align256(p + 4 * TK);
+  w.h = p;        p = align256(p + act * (TK + Ts) * Fm);
+  w.o = p;        p = align256(p + 4 * (TK + Ts) * static_cast<size_t>(s.hidden));
+  w.total = p;
+  return w;
+}
+
 // Launchers implemented in the .hip files (host functions).
 int launch_router(const des_shape_t& s, const void* x, const void* w_router, const float* bias,
                   float* logits, hipStream_t st);
 int launch_softmax(const des_shape_t& s, const float* logits, float* probs, hipStream_t st);
 int launch_select(const des_shape_t& s, const float* logits, int32_t* coreset_idx,
-                  int32_t* coreset_size, float* votes, int32_t* k_seq_used, int32_t* topk_idx,
-                  float* topk_w, hipStream_t st);
-int launch_permute(const des_shape_t& s, const int32_t* topk_idx, int32_t* expert_counts,
-                   int32_t* n_unique, char* ws, hipStream_t st);
+                  int32_t* coreset_size, float* votes, int32_t* k_seq_used, hipStream_t st);
+// router + election + re-routing + permutation (one launch when it fits)
+int launch_routing(const des_shape_t& s, const void* x, const void* w_router, const float* bias,
+                   float* logits, int32_t* coreset_idx, int32_t* coreset_size, int32_t* topk_idx,
+                   float* topk_w, int32_t* expert_counts, int32_t* n_unique, char* ws,
+                   unsigned long long epoch, hipStream_t st);
 int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const void* w_up,
                const void* w_down, const void* ws_gate, const void* ws_up, const void* ws_down,
                const int32_t* topk_idx, const float* topk_w, void* y, char* ws, hipStream_t st);
 int launch_pack(const void* src, void* dst, int64_t n_mats, int rows, int cols, hipStream_t st);
 
 int hip_fail(hipError_t e, const char* what);  // records text, returns DES_ERR_HIP
+
+// Kernel ids for the optional per-kernel event timing (des_kernel_timing_*).
+enum KernelId { kKRouter = 0, kKSoftmax, kKSelect, kKPermute, kKGateUp, kKDown, kKCombine, kKPack,
+                kKRouting, kKCount };
+void timing_mark(int kernel_id, hipStream_t st, bool begin);
+extern bool g_timing_on;
+// Brackets the launches issued in its scope with a pair of events when timing
+// is enabled; costs one predictable branch otherwise.
+struct TimedScope {
+  int id; hipStream_t st;
+  TimedScope(int kernel_id, hipStream_t s) : id(kernel_id), st(s) { if (g_timing_on) timing_mark(id, st, true); }
+  ~TimedScope() { if (g_timing_on) timing_mark(id, st, false); }
+};
 
 }  // namespace des

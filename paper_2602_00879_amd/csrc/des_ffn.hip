@@ -33,7 +33,8 @@ struct FfnArgs {
   const void *sg, *su, *sd;     // shared expert (or null)
   const int32_t* topk_idx;      // [T][K]
   const float* topk_w;          // [T][K]
-  const int32_t *offsets, *live, *meta, *perm, *pos;
+  const int4* slots;            // [n_slots] {expert, first sorted pair, pairs, 0}
+  const int32_t *meta, *pair_tok, *pos;
   void* h;                      // [(TK) x F] then [T x Fs]
   float* o;                     // [(TK + T) x D]
   void* y;                      // [T][D]
@@ -71,6 +72,11 @@ __device__ __forceinline__ constexpr int frag_step() { return PACKED ? 512 : 32;
 __device__ __forceinline__ bf16x8 ld8(const uint16_t* p) {
   return *reinterpret_cast<const bf16x8*>(p);
 }
+// Weights are read once and never again: a non-temporal load keeps them from
+// displacing the activations in L2 / the last-level cache.
+__device__ __forceinline__ bf16x8 ld8_stream(const uint16_t* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(p));
+}
 __device__ __forceinline__ bf16x8 zero8() {
   bf16x8 z;
 #pragma unroll
@@ -78,42 +84,56 @@ __device__ __forceinline__ bf16x8 zero8() {
   return z;
 }
 
-// gate/up for pairs [g0, g0 + 16*NT) of the task, intermediate rows ft*16..+15
-template <int NT, int U, bool PACKED>
-__device__ __forceinline__ void gateup_group(const FfnArgs& a, const Task& t, int ft, int g0,
+// gate/up for pairs [g0, g0 + 16*NT) of the task, intermediate rows
+// (ft0 .. ft0+FT-1)*16..+15.  The FT row tiles share every token fragment.
+template <int FT, int NT, int U, bool PACKED>
+__device__ __forceinline__ void gateup_group(const FfnArgs& a, const Task& t, int ft0, int g0,
                                              int lane) {
   const int D = a.D;
   const int nks = D / 32;
   const uint16_t* x = static_cast<const uint16_t*>(a.x);
-  const uint16_t* gp = frag_ptr<PACKED>(t.w0, ft, D, lane);
-  const uint16_t* up = frag_ptr<PACKED>(t.w1, ft, D, lane);
+  const uint16_t* gp[FT];
+  const uint16_t* up[FT];
+#pragma unroll
+  for (int f = 0; f < FT; ++f) {
+    gp[f] = frag_ptr<PACKED>(t.w0, ft0 + f, D, lane);
+    up[f] = frag_ptr<PACKED>(t.w1, ft0 + f, D, lane);
+  }
   const uint16_t* xp[NT];
 #pragma unroll
   for (int i = 0; i < NT; ++i) {
     int pi = min(g0 + i * 16 + (lane & 15), t.count - 1);  // clamped rows are dropped at the store
-    const int tok = t.shared ? pi : a.perm[t.pair0 + pi] / a.K;
+    const int tok = t.shared ? pi : a.pair_tok[t.pair0 + pi];
     xp[i] = x + static_cast<size_t>(tok) * D + (lane >> 4) * 8;
   }
-  f32x4 accg[NT], accu[NT];
+  f32x4 accg[FT][NT], accu[FT][NT];
 #pragma unroll
-  for (int i = 0; i < NT; ++i) {
-    accg[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    accu[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-  bf16x8 ag[2][U], au[2][U], bx[2][U][NT];
+  for (int f = 0; f < FT; ++f)
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+      accg[f][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      accu[f][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  bf16x8 ag[2][U][FT], au[2][U][FT], bx[2][U][NT];
 
   auto load = [&](int ks, auto stage) {
     constexpr int s = decltype(stage)::value;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (ks + u < nks) {
-        ag[s][u] = ld8(gp + static_cast<size_t>(ks + u) * frag_step<PACKED>());
-        au[s][u] = ld8(up + static_cast<size_t>(ks + u) * frag_step<PACKED>());
+#pragma unroll
+        for (int f = 0; f < FT; ++f) {
+          ag[s][u][f] = ld8_stream(gp[f] + static_cast<size_t>(ks + u) * frag_step<PACKED>());
+          au[s][u][f] = ld8_stream(up[f] + static_cast<size_t>(ks + u) * frag_step<PACKED>());
+        }
 #pragma unroll
         for (int i = 0; i < NT; ++i) bx[s][u][i] = ld8(xp[i] + (ks + u) * 32);
       } else {
-        ag[s][u] = zero8();
-        au[s][u] = zero8();
+#pragma unroll
+        for (int f = 0; f < FT; ++f) {
+          ag[s][u][f] = zero8();
+          au[s][u][f] = zero8();
+        }
 #pragma unroll
         for (int i = 0; i < NT; ++i) bx[s][u][i] = zero8();
       }
@@ -124,10 +144,12 @@ __device__ __forceinline__ void gateup_group(const FfnArgs& a, const Task& t, in
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int i = 0; i < NT; ++i) {
-        accg[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag[s][u], bx[s][u][i], accg[i], 0, 0, 0);
-        accu[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au[s][u], bx[s][u][i], accu[i], 0, 0, 0);
-      }
+      for (int f = 0; f < FT; ++f)
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+          accg[f][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag[s][u][f], bx[s][u][i], accg[f][i], 0, 0, 0);
+          accu[f][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au[s][u][f], bx[s][u][i], accu[f][i], 0, 0, 0);
+        }
   };
   load(0, S0{});
   for (int ks = 0; ks < nks; ks += 2 * U) {
@@ -141,11 +163,14 @@ __device__ __forceinline__ void gateup_group(const FfnArgs& a, const Task& t, in
   for (int i = 0; i < NT; ++i) {
     const int pi = g0 + i * 16 + (lane & 15);
     if (pi < t.count) {
-      u16x4 v;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) v[q] = f32_to_bf16_bits(silu_f(accg[i][q]) * accu[i][q]);
-      uint16_t* dst = h + (t.row_base + pi) * t.fdim + ft * 16 + 4 * (lane >> 4);
-      *reinterpret_cast<u16x4*>(dst) = v;
+      for (int f = 0; f < FT; ++f) {
+        u16x4 v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = f32_to_bf16_bits(silu_f(accg[f][i][q]) * accu[f][i][q]);
+        uint16_t* dst = h + (t.row_base + pi) * t.fdim + (ft0 + f) * 16 + 4 * (lane >> 4);
+        *reinterpret_cast<u16x4*>(dst) = v;
+      }
     }
   }
 }
@@ -154,10 +179,11 @@ __device__ __forceinline__ bool make_task(const FfnArgs& a, int slot_or_shared, 
                                           bool down, Task& t) {
   const size_t TK = static_cast<size_t>(a.T) * a.K;
   if (!shared) {
-    if (slot_or_shared >= a.meta[0]) return false;
-    const int e = a.live[slot_or_shared];
-    const int off = a.offsets[e];
-    t.count = a.offsets[e + 1] - off;
+    const int4 sl = a.slots[slot_or_shared];  // one 16-byte load names the whole task
+    if (sl.x < 0) return false;
+    const int e = sl.x;
+    const int off = sl.y;
+    t.count = sl.z;
     t.pair0 = off;
     t.shared = false;
     t.row_base = static_cast<size_t>(off);
@@ -193,7 +219,8 @@ __device__ __forceinline__ FfnArgs shared_view(const FfnArgs& a, Task& t, size_t
   return v;
 }
 
-constexpr int kFfnWaves = 2;  // wavefronts per workgroup; each is an independent task
+constexpr int kFfnWaves = 1;  // wavefronts per workgroup; each is an independent task
+constexpr int kGuTiles = 2;   // gate/up row tiles per task (F % 32 == 0, so F/16 is even)
 
 // MAXNT bounds the token tiles a task can have (the host knows T >= any expert's
 // count), so that small blocks get a kernel with few registers and high
@@ -202,47 +229,50 @@ template <int MAXNT, bool PACKED>
 __global__ __launch_bounds__(kFfnWaves* kWave) void gateup_bf16_kernel(FfnArgs a) {
   const int lane = threadIdx.x & 63;
   const int task = blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
-  const int tiles_r = a.F / 16;
+  const int tiles_r = a.F / (16 * kGuTiles);
   const int routed = a.n_slots * tiles_r;
-  const int tiles_s = a.Fs / 16;
+  const int tiles_s = a.Fs / (16 * kGuTiles);
   Task t;
   int ft;
   FfnArgs v = a;
   if (task < routed) {
     if (!make_task(a, task / tiles_r, false, false, t)) return;
-    ft = task % tiles_r;
+    ft = (task % tiles_r) * kGuTiles;
   } else if (task < routed + tiles_s) {
     make_task(a, 0, true, false, t);
     v = shared_view(a, t, 2);
-    ft = task - routed;
+    ft = (task - routed) * kGuTiles;
   } else {
     return;
   }
   const int nt = (t.count + 15) / 16;
   if (MAXNT == 1 || nt <= 1) {
-    gateup_group<1, 4, PACKED>(v, t, ft, 0, lane);
+    gateup_group<kGuTiles, 1, 4, PACKED>(v, t, ft, 0, lane);
     return;
   }
   if constexpr (MAXNT >= 2) {
     if (MAXNT == 2 || nt <= 2) {
-      gateup_group<2, 4, PACKED>(v, t, ft, 0, lane);
+      gateup_group<kGuTiles, 2, 2, PACKED>(v, t, ft, 0, lane);
       return;
     }
   }
   if constexpr (MAXNT >= 4) {
     if (MAXNT == 4 || nt <= 4) {
-      gateup_group<4, 2, PACKED>(v, t, ft, 0, lane);
+      gateup_group<kGuTiles, 4, 2, PACKED>(v, t, ft, 0, lane);
       return;
     }
   }
   if constexpr (MAXNT >= 8) {
     if (MAXNT == 8 || nt <= 8) {
-      gateup_group<8, 1, PACKED>(v, t, ft, 0, lane);
+      gateup_group<kGuTiles, 8, 1, PACKED>(v, t, ft, 0, lane);
       return;
     }
   }
   if constexpr (MAXNT >= 16) {
-    for (int g0 = 0; g0 < t.count; g0 += 256) gateup_group<16, 1, PACKED>(v, t, ft, g0, lane);
+    for (int g0 = 0; g0 < t.count; g0 += 256) {
+      gateup_group<1, 16, 1, PACKED>(v, t, ft, g0, lane);
+      gateup_group<1, 16, 1, PACKED>(v, t, ft + 1, g0, lane);
+    }
   }
 }
 
@@ -275,7 +305,7 @@ __device__ __forceinline__ void down_group(const FfnArgs& a, const Task& t, int 
       if (ks + u < nks) {
 #pragma unroll
         for (int r = 0; r < RT; ++r)
-          aw[s][u][r] = ld8(ap[r] + static_cast<size_t>(ks + u) * frag_step<PACKED>());
+          aw[s][u][r] = ld8_stream(ap[r] + static_cast<size_t>(ks + u) * frag_step<PACKED>());
 #pragma unroll
         for (int i = 0; i < NT; ++i) bh[s][u][i] = ld8(hp[i] + (ks + u) * 32);
       } else {
@@ -400,9 +430,10 @@ __device__ __forceinline__ bool f32_row(const FfnArgs& a, int r, int& e, int& to
   const int TK = a.T * a.K;
   if (r < TK) {
     if (r >= a.meta[1]) return false;  // fewer routed pairs than slots (k_eff < K)
-    const int p = a.perm[r];
-    e = a.topk_idx[p];
-    tok = p / a.K;
+    tok = a.pair_tok[r];
+    e = -1;
+    for (int j = 0; j < a.K; ++j)  // the slot of this token that sits at sorted position r
+      if (a.pos[tok * a.K + j] == r) e = a.topk_idx[tok * a.K + j];
     shared = false;
     return true;
   }
@@ -521,6 +552,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
 int launch_pack(const void* src, void* dst, int64_t n_mats, int rows, int cols, hipStream_t st) {
   const long long groups = n_mats * rows * static_cast<long long>(cols) / 8;
   const long long blocks = (groups + 255) / 256;
+  TimedScope ts(kKPack, st);
   hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
                      static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), rows, cols,
                      groups);
@@ -539,10 +571,9 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
   a.sg = ws_gate; a.su = ws_up; a.sd = ws_down;
   a.topk_idx = topk_idx;
   a.topk_w = topk_w;
-  a.offsets = reinterpret_cast<const int32_t*>(ws + w.offsets);
-  a.live = reinterpret_cast<const int32_t*>(ws + w.live);
+  a.slots = reinterpret_cast<const int4*>(ws + w.slots);
   a.meta = reinterpret_cast<const int32_t*>(ws + w.meta);
-  a.perm = reinterpret_cast<const int32_t*>(ws + w.perm);
+  a.pair_tok = reinterpret_cast<const int32_t*>(ws + w.pair_tok);
   a.pos = reinterpret_cast<const int32_t*>(ws + w.pos);
   a.h = ws + w.h;
   a.o = reinterpret_cast<float*>(ws + w.o);
@@ -555,7 +586,7 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
 
   if (s.dtype == DES_BF16) {
     const bool packed = s.weight_layout == DES_LAYOUT_PACKED;
-    const int gu_tasks = a.n_slots * (a.F / 16) + a.Fs / 16;
+    const int gu_tasks = a.n_slots * (a.F / (16 * kGuTiles)) + a.Fs / (16 * kGuTiles);
     const int gu_blocks = (gu_tasks + kFfnWaves - 1) / kFfnWaves;
     const int groups = (a.D / 16 + 3) / 4;
     const int dn_tasks = a.n_slots * groups + (a.Fs > 0 ? groups : 0);
@@ -565,8 +596,14 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     const dim3 blk(kFfnWaves * kWave);
 #define DES_LAUNCH_FFN(NTV, PK)                                                             \
   do {                                                                                      \
-    hipLaunchKernelGGL((gateup_bf16_kernel<NTV, PK>), dim3(gu_blocks), blk, 0, st, a);      \
-    hipLaunchKernelGGL((down_bf16_kernel<NTV, PK>), dim3(dn_blocks), blk, 0, st, a);        \
+    {                                                                                       \
+      TimedScope ts(kKGateUp, st);                                                          \
+      hipLaunchKernelGGL((gateup_bf16_kernel<NTV, PK>), dim3(gu_blocks), blk, 0, st, a);    \
+    }                                                                                       \
+    {                                                                                       \
+      TimedScope ts(kKDown, st);                                                            \
+      hipLaunchKernelGGL((down_bf16_kernel<NTV, PK>), dim3(dn_blocks), blk, 0, st, a);      \
+    }                                                                                       \
   } while (0)
 #define DES_LAUNCH_BY_NT(PK)                                                                \
   do {                                                                                      \
@@ -581,15 +618,23 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
 #undef DES_LAUNCH_BY_NT
 #undef DES_LAUNCH_FFN
     dim3 cg(a.T, (a.D / 4 + 255) / 256);
+    TimedScope ts(kKCombine, st);
     hipLaunchKernelGGL(combine_kernel<true>, cg, dim3(256), 0, st, a);
   } else {
     const int rows = TK + (a.Fs > 0 ? a.T : 0);
     const int Fm = a.F > a.Fs ? a.F : a.Fs;
-    hipLaunchKernelGGL(gateup_f32_kernel, dim3(rows, (Fm + 3) / 4 > 64 ? 64 : (Fm + 3) / 4),
-                       dim3(256), 0, st, a);
-    hipLaunchKernelGGL(down_f32_kernel, dim3(rows, (a.D + 3) / 4 > 64 ? 64 : (a.D + 3) / 4),
-                       dim3(256), 0, st, a);
+    {
+      TimedScope ts(kKGateUp, st);
+      hipLaunchKernelGGL(gateup_f32_kernel, dim3(rows, (Fm + 3) / 4 > 64 ? 64 : (Fm + 3) / 4),
+                         dim3(256), 0, st, a);
+    }
+    {
+      TimedScope ts(kKDown, st);
+      hipLaunchKernelGGL(down_f32_kernel, dim3(rows, (a.D + 3) / 4 > 64 ? 64 : (a.D + 3) / 4),
+                         dim3(256), 0, st, a);
+    }
     dim3 cg(a.T, (a.D / 4 + 255) / 256);
+    TimedScope ts(kKCombine, st);
     hipLaunchKernelGGL(combine_kernel<false>, cg, dim3(256), 0, st, a);
   }
   hipError_t e = hipGetLastError();

@@ -1,0 +1,724 @@
+// Routing half of the DES layer for gfx950, in ONE launch:
+//   router scores G(x)                      (Background, definition of G)
+//   coreset election  Phi                   (Alg. 1 stage 1; Eq. 5 / Alg. 2, Eq. 6 / Alg. 3)
+//   constrained re-routing + gates          (Alg. 1 stage 2)
+//   token permutation by expert, cnt_i      (Eq. 2)
+//
+// The paper fuses its selection into two kernels that add votes into a global
+// vector with float atomics (Sec. 4.3).  Here the whole routing step is one
+// kernel whose workgroups take one of three roles, chained through per-producer
+// flags in device memory instead of kernel boundaries:
+//   role R (one per 16x16 logits tile)  router GEMM tile, then flag[tile] = epoch
+//   role S (one per sequence)           waits for the R flags, elects the coreset,
+//                                       re-routes, then flag[seq] = epoch
+//   role P (one, merged into S if B==1) waits for the S flags, builds counts,
+//                                       offsets, the slot table and the permutation
+// A flag is a 64-bit word that a producer sets to the call's epoch (a host
+// counter that never repeats), so the workspace needs no clearing, stale
+// contents can never satisfy a wait, and no two workgroups ever write the same
+// word (no atomic read-modify-write at all).  Waiting is safe because the launch
+// is only used in this fused form when every workgroup fits on the chip at once
+// (at most 256 workgroups of 1024 threads; the chip holds 512), so a producer
+// can always run; every wait is also bounded and gives up into an error flag.
+// Larger problems run the same three roles as three launches.
+//
+// Votes are accumulated without floating-point atomics: a 16-lane row of a
+// wavefront owns one token, each lane owns a contiguous slice of the experts,
+// votes stay in the owning lane's registers, and rows / waves are combined in a
+// fixed order.  Every ranking compares order-preserving integer keys of the
+// fp32 logits with ties to the lowest expert index.
+#include "des_common.h"
+
+namespace des {
+
+constexpr int kRtWaves = 16;
+constexpr int kRtThreads = kRtWaves * kWave;  // 1024
+constexpr int kMaxWaitIters = 1 << 22;        // bounded waits (~ seconds), then give up
+
+#ifdef DES_ROUTING_TIMESTAMPS  // development aid: 100 MHz timestamps into meta[16..]
+#define DES_STAMP(a, i) do { if (threadIdx.x == 0 && (a).meta != nullptr) reinterpret_cast<long long*>((a).meta + 16)[i] = wall_clock64(); } while (0)
+#else
+#define DES_STAMP(a, i) do { } while (0)
+#endif
+
+struct RoutingArgs {
+  // router
+  const void* x;
+  const void* w_router;
+  const float* bias;
+  float* logits;          // [B][N][M]
+  // selection
+  int32_t* coreset_idx;   // [B][cap]
+  int32_t* coreset_size;  // [B]
+  float* votes;           // [B][M] or null
+  int32_t* k_seq_used;    // [B] or null
+  int32_t* topk_idx;      // [B][N][K] or null (then stage 2 and permutation are skipped)
+  float* topk_w;
+  // permutation
+  int32_t* expert_counts; // [M]
+  int32_t* n_unique;      // [1]
+  int32_t* offsets;       // [M+1]
+  int4* slots;            // [n_slots] {expert, first sorted pair, pairs, 0}; expert -1 = unused
+  int32_t* meta;          // [8]: [0] live experts, [1] routed pairs
+  int32_t* pair_tok;      // [T*K] token of each sorted pair
+  int32_t* pos;           // [T*K] sorted position of pair (t*K+j), -1 = unused slot
+  unsigned long long* flags;  // [n_tiles + B] epoch flags
+  unsigned long long epoch;
+  int B, N, M, K, C, k_seq, mode, cap, D, n_slots;
+  int tiles_m, tiles_t;   // router tiles along experts / tokens
+  int do_router, do_select, do_permute, use_flags, bf16;
+};
+
+// ------------------------------------------------------------------ flags
+__device__ __forceinline__ void flag_publish(unsigned long long* f, unsigned long long epoch) {
+  // all threads of the workgroup have passed a barrier; one thread publishes
+  __threadfence();
+  __hip_atomic_store(f, epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Every thread polls a subset of the flags; returns false if a wait ran out.
+__device__ __forceinline__ bool flags_wait(const unsigned long long* f, int n,
+                                           unsigned long long epoch) {
+  bool ok = true;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    int it = 0;
+    while (__hip_atomic_load(f + i, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+      __builtin_amdgcn_s_sleep(4);
+      if (++it > kMaxWaitIters) { ok = false; break; }
+    }
+  }
+  const int all = __syncthreads_and(ok ? 1 : 0);
+  __threadfence();
+  return all != 0;
+}
+
+// ------------------------------------------------------------ role R: router
+// experts [i0, i0+16) x tokens [t0, t0+16); wave w takes k-steps w, w+16, ...
+// MFMA 16x16x32: lane l supplies row (l%16), reduction elements 8*(l/16)..+7;
+// the accumulator of lane l holds column (l%16), rows 4*(l/16)..+3.
+__device__ __forceinline__ void router_tile_bf16(const RoutingArgs& a, int tile_m, int tile_t,
+                                                 float* part /* [16][256] LDS */) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int T = a.B * a.N, D = a.D, M = a.M;
+  const int i0 = tile_m * 16, t0 = tile_t * 16;
+  const int r = lane & 15, kq = (lane >> 4) * 8;
+  const int ei = min(i0 + r, M - 1);  // clamped rows are computed and dropped
+  const int ti = min(t0 + r, T - 1);
+  const uint16_t* ap = static_cast<const uint16_t*>(a.w_router) + static_cast<size_t>(ei) * D + kq;
+  const uint16_t* bp = static_cast<const uint16_t*>(a.x) + static_cast<size_t>(ti) * D + kq;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  const int nks = D / 32;
+  // four k-steps per trip, all eight loads in flight before the first MFMA
+  for (int ks = wave; ks < nks; ks += 4 * kRtWaves) {
+    bf16x8 av[4], bv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int k = min(ks + u * kRtWaves, nks - 1);  // clamped steps are skipped below
+      av[u] = *reinterpret_cast<const bf16x8*>(ap + k * 32);
+      bv[u] = *reinterpret_cast<const bf16x8*>(bp + k * 32);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (ks + u * kRtWaves < nks)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[u], bv[u], acc, 0, 0, 0);
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) part[wave * 256 + (4 * (lane >> 4) + q) * 16 + r] = acc[q];
+  __syncthreads();
+  if (threadIdx.x < 256) {
+    const int er = threadIdx.x & 15, tc = threadIdx.x >> 4;
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < kRtWaves; ++w) s += part[w * 256 + er * 16 + tc];  // fixed order
+    const int e = i0 + er, t = t0 + tc;
+    if (e < M && t < T) a.logits[static_cast<size_t>(t) * M + e] = s + (a.bias ? a.bias[e] : 0.f);
+  }
+}
+
+// fp32 inputs: each wavefront takes (expert, token) dot products of the tile in
+// turn, lanes stride the reduction dimension with 16-byte loads.
+__device__ __forceinline__ void router_tile_f32(const RoutingArgs& a, int tile_m, int tile_t) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int T = a.B * a.N, D = a.D, M = a.M;
+  const float* x = static_cast<const float*>(a.x);
+  const float* wr = static_cast<const float*>(a.w_router);
+  for (int p = wave; p < 256; p += kRtWaves) {
+    const int e = tile_m * 16 + (p & 15), t = tile_t * 16 + (p >> 4);
+    if (e >= M || t >= T) continue;  // uniform per wave
+    const float4* xp = reinterpret_cast<const float4*>(x + static_cast<size_t>(t) * D);
+    const float4* wp = reinterpret_cast<const float4*>(wr + static_cast<size_t>(e) * D);
+    float s = 0.f;
+    for (int v = lane; v < D / 4; v += 64) {
+      const float4 p4 = xp[v], q4 = wp[v];
+      s = fmaf(p4.x, q4.x, s);
+      s = fmaf(p4.y, q4.y, s);
+      s = fmaf(p4.z, q4.z, s);
+      s = fmaf(p4.w, q4.w, s);
+    }
+    s = wave_sum_f32(s);
+    if (lane == 0) a.logits[static_cast<size_t>(t) * M + e] = s + (a.bias ? a.bias[e] : 0.f);
+  }
+}
+
+// ------------------------------------------------- 16-lane row primitives
+// all-reduce inside each 16-lane row: quad swaps, then rotations by 4 and 8
+__device__ __forceinline__ uint32_t row_max_u32(uint32_t v) {
+  v = max(v, dpp_u32<0xB1>(0u, v));
+  v = max(v, dpp_u32<0x4E>(0u, v));
+  v = max(v, dpp_u32<0x124>(0u, v));  // row_ror:4
+  v = max(v, dpp_u32<0x128>(0u, v));  // row_ror:8
+  return v;
+}
+__device__ __forceinline__ float row_sum_f32(float x) {
+  uint32_t v = __float_as_uint(x);
+#define DES_STEP(ctrl) v = __float_as_uint(__uint_as_float(v) + __uint_as_float(dpp_u32<ctrl>(0u, v)))
+  DES_STEP(0xB1);
+  DES_STEP(0x4E);
+  DES_STEP(0x124);
+  DES_STEP(0x128);
+#undef DES_STEP
+  return __uint_as_float(v);
+}
+// exp(x) for x <= 0 through the hardware exp2: the product x*log2(e) is split
+// into a rounded part and its residual, so the result is good to ~2 ulp
+// (a plain exp2(x*log2e) loses |x| ulp).  Underflows to 0 below about -87.
+__device__ __forceinline__ float exp_neg(float x) {
+  const float kL2eHi = 1.44269502162933349609375f, kL2eLo = 1.925963033500011e-8f;
+  const float t = x * kL2eHi;
+  float r = fmaf(x, kL2eHi, -t);
+  r = fmaf(x, kL2eLo, r);
+  return __builtin_amdgcn_exp2f(t) * fmaf(r, 0.693147180559945f, 1.0f);
+}
+__device__ __forceinline__ float key_to_f32(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+// Best remaining candidate of each row.  Returns the row's best key (0 = none);
+// `mine` is true in the one lane that owns it, `lj` its slot in that lane.
+template <int E16>
+__device__ __forceinline__ uint32_t row_argmax(const uint32_t (&key)[E16], int& lj, bool& mine) {
+  uint32_t lk = key[0];
+  lj = 0;
+#pragma unroll
+  for (int j = 1; j < E16; ++j)
+    if (key[j] > lk) { lk = key[j]; lj = j; }
+  const uint32_t m = row_max_u32(lk);
+  const unsigned long long hit = __ballot(lk == m && m != 0u);
+  const int lane = threadIdx.x & 63;
+  const uint32_t rowhits = static_cast<uint32_t>(hit >> (lane & 48)) & 0xFFFFu;
+  mine = rowhits != 0u && (lane & 15) == __builtin_ctz(rowhits);  // lowest lane = lowest index
+  return m;
+}
+
+// LDS carve-up of the routing kernel (bytes).  MP = padded expert count.
+template <int E16>
+struct SelLds {
+  static constexpr int MP = E16 * 16;
+  static constexpr int vpart = 0;                                // float [16 waves][MP]
+  static constexpr int level = vpart + 4 * kRtWaves * MP;        // int [MP]
+  static constexpr int cnt1 = level + 4 * MP;                    // int [MP]
+  static constexpr int key = cnt1 + 4 * MP;                      // u32 [MP]
+  static constexpr int rank = key + 4 * MP;                      // int [MP]
+  static constexpr int core = rank + 4 * MP;                     // int [MP]
+  static constexpr int hist = core + 4 * MP;                     // int [36]
+  static constexpr int sel_idx = hist + 4 * 36;                  // int [64 slots][32]
+  static constexpr int sel_val = sel_idx + 4 * 64 * 32;          // float [64][32]
+  static constexpr int total = sel_val + 4 * 64 * 32;
+};
+
+// ------------------------------------------------------- role S: selection
+template <int E16>
+__device__ void select_sequence(const RoutingArgs& a, int b, char* smem) {
+  using L = SelLds<E16>;
+  constexpr int MP = L::MP;
+  float* s_vpart = reinterpret_cast<float*>(smem + L::vpart);
+  int* s_level = reinterpret_cast<int*>(smem + L::level);
+  int* s_cnt1 = reinterpret_cast<int*>(smem + L::cnt1);
+  uint32_t* s_key = reinterpret_cast<uint32_t*>(smem + L::key);
+  int* s_rank = reinterpret_cast<int*>(smem + L::rank);
+  int* s_core = reinterpret_cast<int*>(smem + L::core);
+  int* s_hist = reinterpret_cast<int*>(smem + L::hist);  // [0..32] histogram, [33] k used, [34] size
+  int* s_sel_idx = reinterpret_cast<int*>(smem + L::sel_idx);
+  float* s_sel_val = reinterpret_cast<float*>(smem + L::sel_val);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = lane >> 4, rl = lane & 15;   // 4 rows of 16 lanes; a row owns one token
+  const int slot = wave * 4 + row;             // token slot 0..63: fill a wave's 4 rows first,
+                                               // so idle waves issue nothing (16 waves share 4 SIMDs)
+  const int N = a.N, M = a.M, K = a.K;
+  const float* Lg = a.logits + static_cast<size_t>(b) * N * M;
+
+  for (int e = threadIdx.x; e < MP; e += kRtThreads) {
+    s_level[e] = K;
+    s_cnt1[e] = 0;
+    s_rank[e] = 0;
+    s_key[e] = 0u;
+    s_core[e] = (a.mode == DES_VANILLA && e < M) ? 1 : 0;
+  }
+  if (threadIdx.x < 36) s_hist[threadIdx.x] = 0;
+  __syncthreads();
+
+  // ---------------------------------------------------------- stage 1: Phi
+  if (a.mode != DES_VANILLA) {
+    const bool vote = a.mode == DES_VOTE;
+    const int kk = (!vote && a.k_seq > 0) ? a.k_seq : K;
+    float vacc[E16];
+#pragma unroll
+    for (int j = 0; j < E16; ++j) vacc[j] = 0.f;
+
+    for (int n0 = 0; n0 + wave * 4 < N; n0 += 64) {  // fixed token order per row
+      const int n = n0 + slot;
+      const bool live = n < N;
+      const float* rowp = Lg + static_cast<size_t>(live ? n : 0) * M;
+      float val[E16], p[E16];
+      uint32_t key[E16];
+#pragma unroll
+      for (int j = 0; j < E16; ++j) {
+        const int idx = rl * E16 + j;
+        const bool ok = live && idx < M;
+        val[j] = ok ? rowp[idx] : 0.f;
+        key[j] = ok ? order_key(val[j]) : 0u;
+        p[j] = 0.f;
+      }
+      if (vote) {  // softmax over all M experts (Sec. 4.3), fp32
+        uint32_t lk = key[0];
+#pragma unroll
+        for (int j = 1; j < E16; ++j) lk = max(lk, key[j]);
+        const float mx = key_to_f32(row_max_u32(lk));
+        float se = 0.f;
+#pragma unroll
+        for (int j = 0; j < E16; ++j) {
+          p[j] = key[j] ? exp_neg(val[j] - mx) : 0.f;
+          se += p[j];
+        }
+        const float den = row_sum_f32(se);
+        const float inv = den > 0.f ? 1.0f / den : 0.f;
+#pragma unroll
+        for (int j = 0; j < E16; ++j) p[j] *= inv;
+      }
+      for (int it = 0; it < kk; ++it) {  // Mask(I, K): the token's own top-K
+        int lj;
+        bool mine;
+        row_argmax<E16>(key, lj, mine);
+#pragma unroll
+        for (int j = 0; j < E16; ++j) {
+          const bool hit = mine && j == lj;
+          key[j] = hit ? 0u : key[j];
+          vacc[j] += hit ? p[j] : 0.f;  // V_i += masked weight (Eq. 6)
+        }
+        if (mine) {
+          if (vote) {
+            s_level[rl * E16 + lj] = 0;  // "nominated": only < K matters for votes
+          } else {
+            atomicMin(&s_level[rl * E16 + lj], it);
+            if (it == 0) atomicAdd(&s_cnt1[rl * E16 + lj], 1);
+          }
+        }
+      }
+    }
+    DES_STAMP(a, 2);
+    if (vote) {
+      // rows of a wave in the fixed order (r0 + r1) + (r2 + r3), then waves in order
+#pragma unroll
+      for (int j = 0; j < E16; ++j) {
+        float v = vacc[j];
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        if (row == 0) s_vpart[wave * MP + rl * E16 + j] = v;
+      }
+    }
+    __syncthreads();
+    DES_STAMP(a, 11);
+
+    if (vote) {
+      for (int e = threadIdx.x; e < MP; e += kRtThreads) {
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < kRtWaves; ++w) v += s_vpart[w * MP + e];
+        const bool nominated = e < M && s_level[e] < K;
+        s_key[e] = nominated ? order_key(v) : 0u;
+        if (a.votes && e < M) a.votes[static_cast<size_t>(b) * M + e] = v;
+      }
+      if (threadIdx.x == 0) s_hist[33] = 0;
+    } else if (a.k_seq > 0) {  // Eq. 5 with the caller's k
+      for (int e = threadIdx.x; e < MP; e += kRtThreads) s_core[e] = s_level[e] < a.k_seq;
+      if (threadIdx.x == 0) s_hist[33] = a.k_seq;
+    } else {  // largest k' whose union fits in C
+      for (int e = threadIdx.x; e < M; e += kRtThreads)
+        if (s_level[e] < K) atomicAdd(&s_hist[s_level[e]], 1);
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        int size = 0, ku = 0;
+        for (int k1 = 1; k1 <= K; ++k1) {
+          size += s_hist[k1 - 1];
+          if (size <= a.C) ku = k1; else break;
+        }
+        s_hist[33] = ku;
+      }
+      __syncthreads();
+      const int ku = s_hist[33];
+      for (int e = threadIdx.x; e < MP; e += kRtThreads) {
+        if (ku > 0) s_core[e] = s_level[e] < ku;
+        else s_key[e] = (s_level[e] == 0) ? static_cast<uint32_t>(s_cnt1[e]) : 0u;
+      }
+    }
+    __syncthreads();
+    DES_STAMP(a, 12);
+
+    if (vote || s_hist[33] == 0) {  // top-C by key, ties to the lowest index
+      // rank[e] = #{j : key[j] beats key[e]}; the j range is split over the
+      // threads that share an expert, partial counts meet in an integer LDS add
+      constexpr int P = kRtThreads / MP >= 1 ? kRtThreads / MP : 1;
+      for (int t = threadIdx.x; t < MP * P; t += kRtThreads) {
+        const int e = t % MP, part = t / MP;
+        const uint32_t ke = s_key[e];
+        if (ke == 0u) continue;
+        const int j0 = (M * part) / P, j1 = (M * (part + 1)) / P;
+        int rank = 0;
+        for (int j = j0; j < j1; ++j) {
+          const uint32_t kj = s_key[j];
+          rank += (kj > ke || (kj == ke && j < e)) ? 1 : 0;
+        }
+        if (rank) atomicAdd(&s_rank[e], rank);
+      }
+      __syncthreads();
+      DES_STAMP(a, 13);
+      for (int e = threadIdx.x; e < MP; e += kRtThreads)
+        s_core[e] = (s_key[e] != 0u && s_rank[e] < a.C) ? 1 : 0;
+    }
+    __syncthreads();
+  }
+
+  DES_STAMP(a, 3);
+  // ------------------------------------- coreset as an ascending index list
+  if (wave == 0) {
+    int base = 0;
+    int32_t* out = a.coreset_idx + static_cast<size_t>(b) * a.cap;
+    for (int c = 0; c < MP; c += 64) {
+      const int e = c + lane;
+      const bool f = e < MP && s_core[e] != 0;
+      const unsigned long long bal = __ballot(f);
+      const int pre = __popcll(bal & ((1ull << lane) - 1ull));
+      if (f && base + pre < a.cap) out[base + pre] = e;
+      base += __popcll(bal);
+    }
+    for (int i = base + lane; i < a.cap; i += 64) out[i] = -1;
+    if (lane == 0) {
+      a.coreset_size[b] = base;
+      s_hist[34] = base;
+      if (a.k_seq_used) a.k_seq_used[b] = (a.mode == DES_SEQ) ? s_hist[33] : 0;
+    }
+  }
+  __syncthreads();
+  if (a.topk_idx == nullptr) return;
+
+  DES_STAMP(a, 4);
+  // ------------------------------ stage 2: constrained local routing + gates
+  const int keff = min(K, s_hist[34]);
+  bool cm[E16];
+#pragma unroll
+  for (int j = 0; j < E16; ++j) cm[j] = (rl * E16 + j < M) && s_core[rl * E16 + j] != 0;
+  int* my_idx = s_sel_idx + (wave * 4 + row) * 32;
+  float* my_val = s_sel_val + (wave * 4 + row) * 32;
+
+  for (int n0 = 0; n0 + wave * 4 < N; n0 += 64) {
+    const int n = n0 + slot;
+    const bool live = n < N;
+    const float* rowp = Lg + static_cast<size_t>(live ? n : 0) * M;
+    float val[E16];
+    uint32_t key[E16];
+#pragma unroll
+    for (int j = 0; j < E16; ++j) {
+      const bool ok = live && cm[j];
+      val[j] = ok ? rowp[rl * E16 + j] : 0.f;
+      key[j] = ok ? order_key(val[j]) : 0u;
+    }
+    for (int it = 0; it < keff; ++it) {  // S_n = TopK(I_n restricted to C, K)
+      int lj;
+      bool mine;
+      row_argmax<E16>(key, lj, mine);
+      float lv = val[0];
+#pragma unroll
+      for (int j = 0; j < E16; ++j) {
+        const bool hit = j == lj;
+        lv = hit ? val[j] : lv;
+        key[j] = (mine && hit) ? 0u : key[j];
+      }
+      if (mine) {
+        my_idx[it] = rl * E16 + lj;
+        my_val[it] = lv;
+      }
+    }
+    // g_n = softmax of the selected logits; slot 0 holds the largest.  A row
+    // has 16 lanes and K <= 32, so each lane covers slots rl and rl + 16.
+    const float mx = keff > 0 ? my_val[0] : 0.f;
+    const float e0 = rl < keff ? exp_neg(my_val[rl] - mx) : 0.f;
+    const float e1 = rl + 16 < keff ? exp_neg(my_val[rl + 16] - mx) : 0.f;
+    const float den = row_sum_f32(e0 + e1);
+    if (live) {
+      const size_t o = (static_cast<size_t>(b) * N + n) * K;
+      if (rl < K) {
+        a.topk_idx[o + rl] = rl < keff ? my_idx[rl] : -1;
+        a.topk_w[o + rl] = rl < keff ? e0 / den : 0.f;
+      }
+      if (rl + 16 < K) {
+        a.topk_idx[o + rl + 16] = rl + 16 < keff ? my_idx[rl + 16] : -1;
+        a.topk_w[o + rl + 16] = rl + 16 < keff ? e1 / den : 0.f;
+      }
+    }
+  }
+}
+
+// ----------------------------------------------------- role P: permutation
+// Because a token names an expert at most once, the pairs of expert e ordered
+// by (token, slot) are ordered by token alone, so a per-expert bitmap over the
+// tokens gives every pair's sorted position with popcounts: no sort, no float,
+// integer LDS atomics only (their result does not depend on arrival order).
+__device__ void permute_all(const RoutingArgs& a, char* smem) {
+  const int T = a.B * a.N, K = a.K, M = a.M;
+  const int words = (T + 31) / 32;
+  uint32_t* member = reinterpret_cast<uint32_t*>(smem);           // [M][words]
+  int* s_cnt = reinterpret_cast<int*>(member + static_cast<size_t>(M) * words);  // [M]
+  int* s_off = s_cnt + M;                                          // [M+1]
+  int* s_liv = s_off + M + 1;                                      // [M+1]
+  const int tid = threadIdx.x;
+  const int TK = T * K;
+
+  for (int i = tid; i < M * words; i += kRtThreads) member[i] = 0u;
+  __syncthreads();
+  for (int p = tid; p < TK; p += kRtThreads) {
+    const int e = a.topk_idx[p];
+    if (e >= 0) {
+      const int t = p / K;
+      atomicOr(&member[static_cast<size_t>(e) * words + (t >> 5)], 1u << (t & 31));
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < M; e += kRtThreads) {
+    int c = 0;
+    for (int w = 0; w < words; ++w) c += __popc(member[static_cast<size_t>(e) * words + w]);
+    s_cnt[e] = c;
+    a.expert_counts[e] = c;
+  }
+  __syncthreads();
+  if (tid < 64) {  // exclusive scans of counts and of (count > 0), 64 experts at a time
+    int base_c = 0, base_l = 0;
+    for (int c0 = 0; c0 < M; c0 += 64) {
+      const int e = c0 + tid;
+      const int c = e < M ? s_cnt[e] : 0;
+      int inc = c;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(inc, d);
+        if (tid >= d) inc += o;
+      }
+      const unsigned long long bal = __ballot(c > 0);
+      const int lpre = __popcll(bal & ((1ull << tid) - 1ull));
+      if (e < M) {
+        s_off[e] = base_c + inc - c;
+        s_liv[e] = base_l + lpre;
+      }
+      base_c += __shfl(inc, 63);
+      base_l += __popcll(bal);
+    }
+    if (tid == 0) {
+      s_off[M] = base_c;
+      s_liv[M] = base_l;
+      a.meta[0] = base_l;
+      a.meta[1] = base_c;
+      a.n_unique[0] = base_l;
+    }
+  }
+  __syncthreads();
+  const int n_live = s_liv[M];
+  for (int e = tid; e <= M; e += kRtThreads) a.offsets[e] = s_off[e];
+  for (int e = tid; e < M; e += kRtThreads)
+    if (s_cnt[e] > 0 && s_liv[e] < a.n_slots) a.slots[s_liv[e]] = make_int4(e, s_off[e], s_cnt[e], 0);
+  for (int s = n_live + tid; s < a.n_slots; s += kRtThreads) a.slots[s] = make_int4(-1, 0, 0, 0);
+  for (int p = tid; p < TK; p += kRtThreads) {
+    const int e = a.topk_idx[p];
+    if (e < 0) { a.pos[p] = -1; continue; }
+    const int t = p / K;
+    const uint32_t* mrow = member + static_cast<size_t>(e) * words;
+    int r = s_off[e];
+    for (int w = 0; w < (t >> 5); ++w) r += __popc(mrow[w]);
+    r += __popc(mrow[t >> 5] & ((1u << (t & 31)) - 1u));
+    a.pair_tok[r] = t;
+    a.pos[p] = r;
+  }
+}
+
+// ---------------------------------------------------------------- the kernel
+constexpr int kRoutingLds = 64 * 1024;
+
+template <int E16>
+__global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
+  __shared__ __align__(16) char smem[kRoutingLds];
+  static_assert(SelLds<E16>::total <= kRoutingLds, "selection scratch exceeds LDS budget");
+  const int n_tiles = a.do_router ? a.tiles_m * a.tiles_t : 0;
+  int blk = blockIdx.x;
+  if (blk < n_tiles) {  // ---- role R
+    if (blk == 0) DES_STAMP(a, 8);
+    if (a.bf16) router_tile_bf16(a, blk % a.tiles_m, blk / a.tiles_m, reinterpret_cast<float*>(smem));
+    else router_tile_f32(a, blk % a.tiles_m, blk / a.tiles_m);
+    if (blk == 0) DES_STAMP(a, 9);
+    if (a.use_flags) {
+      __syncthreads();
+      if (threadIdx.x == 0) flag_publish(a.flags + blk, a.epoch);
+    }
+    if (blk == 0) DES_STAMP(a, 10);
+    return;
+  }
+  blk -= n_tiles;
+  const int n_sel = a.do_select ? a.B : 0;
+  const int all_tiles = a.tiles_m * a.tiles_t;
+  if (blk < n_sel) {  // ---- role S
+    DES_STAMP(a, 0);
+    if (a.use_flags && a.do_router && !flags_wait(a.flags, all_tiles, a.epoch)) {
+      if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
+      return;
+    }
+    DES_STAMP(a, 1);
+    select_sequence<E16>(a, blk, smem);
+    DES_STAMP(a, 5);
+    if (a.topk_idx == nullptr) return;
+    if (a.B == 1 && a.do_permute) {  // single sequence: permute right here
+      // same workgroup, same compute unit: the barrier orders the topk_idx
+      // stores before the loads below, no device-scope fence needed
+      __syncthreads();
+      DES_STAMP(a, 6);
+      permute_all(a, smem);
+      DES_STAMP(a, 7);
+      // every flag of this call has been consumed: clear them, so that a replay
+      // of a captured launch (same epoch) cannot be satisfied by stale flags
+      if (a.use_flags)
+        for (int i = threadIdx.x; i < all_tiles + a.B; i += kRtThreads) a.flags[i] = 0ull;
+      return;
+    }
+    if (a.use_flags) {
+      __syncthreads();
+      if (threadIdx.x == 0) flag_publish(a.flags + all_tiles + blk, a.epoch);
+    }
+    return;
+  }
+  blk -= n_sel;
+  if (blk == 0 && a.do_permute && a.B > 1) {  // ---- role P
+    if (a.use_flags && a.do_select && !flags_wait(a.flags + all_tiles, a.B, a.epoch)) {
+      if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
+      return;
+    }
+    permute_all(a, smem);
+    if (a.use_flags)  // all selectors have consumed the router flags and published theirs
+      for (int i = threadIdx.x; i < all_tiles + a.B; i += kRtThreads) a.flags[i] = 0ull;
+  }
+}
+
+// probs[t][:] = softmax(logits[t][:]); one wavefront per token (des_route only).
+__global__ __launch_bounds__(64) void softmax_kernel(const float* __restrict__ logits,
+                                                     float* __restrict__ probs, int M) {
+  const int lane = threadIdx.x;
+  const float* row = logits + static_cast<size_t>(blockIdx.x) * M;
+  float* out = probs + static_cast<size_t>(blockIdx.x) * M;
+  uint32_t mk = 0;
+  for (int i = lane; i < M; i += 64) mk = max(mk, order_key(row[i]));
+  const float mx = key_to_f32(wave_max_u32(mk));
+  float s = 0.f;
+  for (int i = lane; i < M; i += 64) s += expf(row[i] - mx);
+  s = wave_sum_f32(s);
+  const float inv = 1.0f / s;
+  for (int i = lane; i < M; i += 64) out[i] = expf(row[i] - mx) * inv;
+}
+
+// ------------------------------------------------------------------ launchers
+static int launch_routing_grid(const RoutingArgs& a, int grid, int kernel_id, hipStream_t st) {
+  const int e16 = (a.M + 15) / 16;
+  TimedScope ts(kernel_id, st);
+  const dim3 g(grid), b(kRtThreads);
+  if (e16 <= 1) hipLaunchKernelGGL(routing_kernel<1>, g, b, 0, st, a);
+  else if (e16 <= 2) hipLaunchKernelGGL(routing_kernel<2>, g, b, 0, st, a);
+  else if (e16 <= 4) hipLaunchKernelGGL(routing_kernel<4>, g, b, 0, st, a);
+  else if (e16 <= 8) hipLaunchKernelGGL(routing_kernel<8>, g, b, 0, st, a);
+  else if (e16 <= 16) hipLaunchKernelGGL(routing_kernel<16>, g, b, 0, st, a);
+  else hipLaunchKernelGGL(routing_kernel<32>, g, b, 0, st, a);
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? DES_OK : hip_fail(e, "routing launch");
+}
+
+static void fill_common(RoutingArgs& a, const des_shape_t& s) {
+  a = RoutingArgs{};
+  a.B = s.n_seqs; a.N = s.n_tokens; a.M = s.n_experts; a.K = s.top_k; a.C = s.coreset;
+  a.k_seq = s.k_seq; a.mode = s.mode; a.cap = des_coreset_capacity(&s); a.D = s.hidden;
+  a.n_slots = max_live_experts(s);
+  a.tiles_m = (s.n_experts + 15) / 16;
+  a.tiles_t = (s.n_seqs * s.n_tokens + 15) / 16;
+  a.bf16 = s.dtype == DES_BF16;
+}
+
+int launch_router(const des_shape_t& s, const void* x, const void* w_router, const float* bias,
+                  float* logits, hipStream_t st) {
+  RoutingArgs a;
+  fill_common(a, s);
+  a.x = x; a.w_router = w_router; a.bias = bias; a.logits = logits;
+  a.do_router = 1;
+  return launch_routing_grid(a, a.tiles_m * a.tiles_t, kKRouter, st);
+}
+
+int launch_softmax(const des_shape_t& s, const float* logits, float* probs, hipStream_t st) {
+  const int T = s.n_seqs * s.n_tokens;
+  TimedScope ts(kKSoftmax, st);
+  hipLaunchKernelGGL(softmax_kernel, dim3(T), dim3(64), 0, st, logits, probs, s.n_experts);
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? DES_OK : hip_fail(e, "softmax launch");
+}
+
+int launch_select(const des_shape_t& s, const float* logits, int32_t* coreset_idx,
+                  int32_t* coreset_size, float* votes, int32_t* k_seq_used, hipStream_t st) {
+  RoutingArgs a;
+  fill_common(a, s);
+  a.logits = const_cast<float*>(logits);
+  a.coreset_idx = coreset_idx; a.coreset_size = coreset_size; a.votes = votes;
+  a.k_seq_used = k_seq_used;
+  a.do_select = 1;
+  return launch_routing_grid(a, a.B, kKSelect, st);
+}
+
+int launch_routing(const des_shape_t& s, const void* x, const void* w_router, const float* bias,
+                   float* logits, int32_t* coreset_idx, int32_t* coreset_size, int32_t* topk_idx,
+                   float* topk_w, int32_t* expert_counts, int32_t* n_unique, char* ws,
+                   unsigned long long epoch, hipStream_t st) {
+  const WsLayout w = ws_layout(s);
+  RoutingArgs a;
+  fill_common(a, s);
+  a.x = x; a.w_router = w_router; a.bias = bias; a.logits = logits;
+  a.coreset_idx = coreset_idx; a.coreset_size = coreset_size;
+  a.topk_idx = topk_idx; a.topk_w = topk_w;
+  a.expert_counts = expert_counts; a.n_unique = n_unique;
+  a.offsets = reinterpret_cast<int32_t*>(ws + w.offsets);
+  a.slots = reinterpret_cast<int4*>(ws + w.slots);
+  a.meta = reinterpret_cast<int32_t*>(ws + w.meta);
+  a.pair_tok = reinterpret_cast<int32_t*>(ws + w.pair_tok);
+  a.pos = reinterpret_cast<int32_t*>(ws + w.pos);
+  a.flags = reinterpret_cast<unsigned long long*>(ws + w.flags);
+  a.epoch = epoch;
+  const int n_tiles = a.tiles_m * a.tiles_t;
+  const int roles = n_tiles + a.B + (a.B > 1 ? 1 : 0);
+  if (roles <= kMaxFusedRoutingBlocks) {  // all workgroups resident at once: one launch
+    a.do_router = a.do_select = a.do_permute = 1;
+    a.use_flags = 1;
+    return launch_routing_grid(a, roles, kKRouting, st);
+  }
+  // too large to wait inside one launch: the same roles as three launches
+  RoutingArgs r = a;
+  r.do_router = 1;
+  int rc = launch_routing_grid(r, n_tiles, kKRouter, st);
+  if (rc != DES_OK) return rc;
+  RoutingArgs sel = a;
+  sel.do_select = 1;
+  sel.do_permute = a.B == 1 ? 1 : 0;
+  rc = launch_routing_grid(sel, a.B, kKSelect, st);
+  if (rc != DES_OK || a.B == 1) return rc;
+  RoutingArgs p = a;
+  p.do_permute = 1;
+  return launch_routing_grid(p, 1, kKPermute, st);
+}
+
+}  // namespace des
