@@ -88,8 +88,9 @@ inline int max_live_experts(const des_shape_t& s) {
   return static_cast<int>(m);
 }
 
-// The fused routing launch is used when all of its workgroups (router tiles +
-// one per sequence + one) are resident at once; the chip holds 512 of them.
+// The fused routing launch is used only when all of its workgroups (router
+// tiles + one per sequence + one) can be resident at once: one per compute
+// unit, and never more than this.
 constexpr int kMaxFusedRoutingBlocks = 256;
 
 // All offsets in bytes from the (256-byte aligned) workspace base.

@@ -18,8 +18,8 @@
 // contents can never satisfy a wait, and no two workgroups ever write the same
 // word (no atomic read-modify-write at all).  Waiting is safe because the launch
 // is only used in this fused form when every workgroup fits on the chip at once
-// (at most 256 workgroups of 1024 threads; the chip holds 512), so a producer
-// can always run; every wait is also bounded and gives up into an error flag.
+// (one 1024-thread workgroup per compute unit), so a producer can always run;
+// every wait is also bounded and gives up, reporting n_unique = -1.
 // Larger problems run the same three roles as three launches.
 //
 // Votes are accumulated without floating-point atomics: a 16-lane row of a
@@ -159,24 +159,33 @@ __device__ __forceinline__ void router_tile_f32(const RoutingArgs& a, int tile_m
   }
 }
 
-// ------------------------------------------------- 16-lane row primitives
-// all-reduce inside each 16-lane row: quad swaps, then rotations by 4 and 8
+// ------------------------------------------------------- row primitives
+// A "row" is the group of LPT adjacent lanes that owns one token; each lane
+// owns 8 consecutive experts.  All-reduce inside every row: quad swaps, the
+// half-row and row mirrors (DPP), then lane exchanges across 16-lane rows.
+template <int LPT>
 __device__ __forceinline__ uint32_t row_max_u32(uint32_t v) {
-  v = max(v, dpp_u32<0xB1>(0u, v));
-  v = max(v, dpp_u32<0x4E>(0u, v));
-  v = max(v, dpp_u32<0x124>(0u, v));  // row_ror:4
-  v = max(v, dpp_u32<0x128>(0u, v));  // row_ror:8
+  if (LPT >= 2) v = max(v, dpp_u32<0xB1>(0u, v));   // quad_perm [1,0,3,2]
+  if (LPT >= 4) v = max(v, dpp_u32<0x4E>(0u, v));   // quad_perm [2,3,0,1]
+  if (LPT >= 8) v = max(v, dpp_u32<0x141>(0u, v));  // row_half_mirror
+  if (LPT >= 16) v = max(v, dpp_u32<0x140>(0u, v)); // row_mirror
+  if (LPT >= 32) v = max(v, static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), 16)));
+  if (LPT >= 64) v = max(v, static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), 32)));
   return v;
 }
+template <int LPT>
 __device__ __forceinline__ float row_sum_f32(float x) {
   uint32_t v = __float_as_uint(x);
 #define DES_STEP(ctrl) v = __float_as_uint(__uint_as_float(v) + __uint_as_float(dpp_u32<ctrl>(0u, v)))
-  DES_STEP(0xB1);
-  DES_STEP(0x4E);
-  DES_STEP(0x124);
-  DES_STEP(0x128);
+  if (LPT >= 2) DES_STEP(0xB1);
+  if (LPT >= 4) DES_STEP(0x4E);
+  if (LPT >= 8) DES_STEP(0x141);
+  if (LPT >= 16) DES_STEP(0x140);
 #undef DES_STEP
-  return __uint_as_float(v);
+  float r = __uint_as_float(v);
+  if (LPT >= 32) r += __shfl_xor(r, 16);
+  if (LPT >= 64) r += __shfl_xor(r, 32);
+  return r;
 }
 // exp(x) for x <= 0 through the hardware exp2: the product x*log2(e) is split
 // into a rounded part and its residual, so the result is good to ~2 ulp
@@ -192,44 +201,85 @@ __device__ __forceinline__ float key_to_f32(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
 }
 
-// Best remaining candidate of each row.  Returns the row's best key (0 = none);
-// `mine` is true in the one lane that owns it, `lj` its slot in that lane.
-template <int E16>
-__device__ __forceinline__ uint32_t row_argmax(const uint32_t (&key)[E16], int& lj, bool& mine) {
-  uint32_t lk = key[0];
-  lj = 0;
+constexpr int kEpl = 8;  // experts per lane
+
+// A lane's 8 (key, slot) pairs sorted once, best first.  Odd-even transposition
+// with strict comparisons is stable, so equal keys keep ascending expert order;
+// every later "best remaining candidate" is then a head pointer, not a rescan.
+// `idx` packs the original slot of sorted position s in bits [3s, 3s+3).
+__device__ __forceinline__ void sort8_desc(uint32_t (&k)[kEpl], uint32_t& idx) {
+  uint32_t id[kEpl];
 #pragma unroll
-  for (int j = 1; j < E16; ++j)
-    if (key[j] > lk) { lk = key[j]; lj = j; }
-  const uint32_t m = row_max_u32(lk);
-  const unsigned long long hit = __ballot(lk == m && m != 0u);
-  const int lane = threadIdx.x & 63;
-  const uint32_t rowhits = static_cast<uint32_t>(hit >> (lane & 48)) & 0xFFFFu;
-  mine = rowhits != 0u && (lane & 15) == __builtin_ctz(rowhits);  // lowest lane = lowest index
-  return m;
+  for (int j = 0; j < kEpl; ++j) id[j] = j;
+#pragma unroll
+  for (int round = 0; round < kEpl; ++round) {
+#pragma unroll
+    for (int i = round & 1; i + 1 < kEpl; i += 2) {
+      const bool sw = k[i] < k[i + 1];
+      const uint32_t hi = max(k[i], k[i + 1]), lo = min(k[i], k[i + 1]);
+      const uint32_t ia = sw ? id[i + 1] : id[i], ib = sw ? id[i] : id[i + 1];
+      k[i] = hi; k[i + 1] = lo; id[i] = ia; id[i + 1] = ib;
+    }
+  }
+  idx = 0;
+#pragma unroll
+  for (int j = 0; j < kEpl; ++j) idx |= id[j] << (3 * j);
 }
 
-// LDS carve-up of the routing kernel (bytes).  MP = padded expert count.
-template <int E16>
+// LDS carve-up of the selection (bytes).  MP = padded expert count = 8 * LPT.
+template <int LPT>
 struct SelLds {
-  static constexpr int MP = E16 * 16;
-  static constexpr int vpart = 0;                                // float [16 waves][MP]
+  static constexpr int MP = kEpl * LPT;
+  static constexpr int sorted = 0;                               // u32 [16 waves][8][64 lanes]
+  static constexpr int vpart = sorted + 4 * kRtWaves * kEpl * 64; // float [16 waves][MP]
   static constexpr int level = vpart + 4 * kRtWaves * MP;        // int [MP]
   static constexpr int cnt1 = level + 4 * MP;                    // int [MP]
   static constexpr int key = cnt1 + 4 * MP;                      // u32 [MP]
   static constexpr int rank = key + 4 * MP;                      // int [MP]
   static constexpr int core = rank + 4 * MP;                     // int [MP]
   static constexpr int hist = core + 4 * MP;                     // int [36]
-  static constexpr int sel_idx = hist + 4 * 36;                  // int [64 slots][32]
-  static constexpr int sel_val = sel_idx + 4 * 64 * 32;          // float [64][32]
-  static constexpr int total = sel_val + 4 * 64 * 32;
+  static constexpr int total = hist + 4 * 36;
 };
 
+// Per-token state of one lane while candidates are drawn best-first.
+struct Head {
+  uint32_t mask;  // sorted positions still in play
+  uint32_t key;   // key at the head (0 = none)
+  int h;          // head position
+};
+__device__ __forceinline__ void head_set(Head& hd, uint32_t mask, const uint32_t* my_sorted) {
+  hd.mask = mask;
+  hd.h = mask ? __builtin_ctz(mask) : 0;
+  hd.key = mask ? my_sorted[hd.h * 64] : 0u;
+}
+
+// One draw: the best head of every row.  Returns the row's best key (0 = the
+// row has no candidate); `mine` is set in the one lane that owns it.
+template <int LPT>
+__device__ __forceinline__ uint32_t row_draw(const Head& hd, bool& mine) {
+  const uint32_t m = row_max_u32<LPT>(hd.key);
+  const unsigned long long hit = __ballot(hd.key == m && m != 0u);
+  const int lane = threadIdx.x & 63;
+  const unsigned long long rowbits =
+      LPT == 64 ? hit : ((hit >> (lane & (64 - LPT))) & ((1ull << (LPT & 63)) - 1ull));
+  // lowest lane with the best key = lowest expert index among equals
+  mine = rowbits != 0ull && (lane & (LPT - 1)) == __builtin_ctzll(rowbits);
+  return m;
+}
+
 // ------------------------------------------------------- role S: selection
-template <int E16>
-__device__ void select_sequence(const RoutingArgs& a, int b, char* smem) {
-  using L = SelLds<E16>;
+// `dry` runs the same instructions on whatever the logits buffer holds and
+// stores nothing to global memory: the selector workgroup uses it to pull its
+// code into the instruction cache while it waits for the router tiles (every
+// index below derives from lane and slot numbers, never from the data read).
+template <int LPT>
+__device__ void select_sequence(const RoutingArgs& a, int b, char* smem, bool dry) {
+  using L = SelLds<LPT>;
   constexpr int MP = L::MP;
+  constexpr int RPW = 64 / LPT;          // rows (tokens) per wave
+  constexpr int TPP = kRtWaves * RPW;    // tokens per pass
+  constexpr int NW = (32 + LPT - 1) / LPT;  // gate slots a lane keeps (K <= 32)
+  uint32_t* s_sorted = reinterpret_cast<uint32_t*>(smem + L::sorted);
   float* s_vpart = reinterpret_cast<float*>(smem + L::vpart);
   int* s_level = reinterpret_cast<int*>(smem + L::level);
   int* s_cnt1 = reinterpret_cast<int*>(smem + L::cnt1);
@@ -237,15 +287,14 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem) {
   int* s_rank = reinterpret_cast<int*>(smem + L::rank);
   int* s_core = reinterpret_cast<int*>(smem + L::core);
   int* s_hist = reinterpret_cast<int*>(smem + L::hist);  // [0..32] histogram, [33] k used, [34] size
-  int* s_sel_idx = reinterpret_cast<int*>(smem + L::sel_idx);
-  float* s_sel_val = reinterpret_cast<float*>(smem + L::sel_val);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int row = lane >> 4, rl = lane & 15;   // 4 rows of 16 lanes; a row owns one token
-  const int slot = wave * 4 + row;             // token slot 0..63: fill a wave's 4 rows first,
-                                               // so idle waves issue nothing (16 waves share 4 SIMDs)
+  const int row = lane / LPT, rl = lane % LPT;
+  const int slot = wave * RPW + row;  // fill a wave's rows first: idle waves issue nothing
   const int N = a.N, M = a.M, K = a.K;
   const float* Lg = a.logits + static_cast<size_t>(b) * N * M;
+  uint32_t* my_sorted = s_sorted + wave * (kEpl * 64) + lane;  // [s * 64]
+  const bool single_pass = N <= TPP;
 
   for (int e = threadIdx.x; e < MP; e += kRtThreads) {
     s_level[e] = K;
@@ -256,74 +305,95 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem) {
   }
   if (threadIdx.x < 36) s_hist[threadIdx.x] = 0;
   __syncthreads();
+  DES_STAMP(a, 14);
+
+  uint32_t sidx = 0;     // packed original slots of the sorted positions
+  uint32_t nvalid = 0;   // sorted positions [0, nvalid) hold real experts
+
+  // Loads token n's logits, sorts this lane's 8 keys into LDS, returns the
+  // unsorted values (for the softmax).
+  auto load_sort = [&](int n, float (&val)[kEpl], uint32_t (&key)[kEpl]) {
+    const bool live = n < N;
+    const float* rowp = Lg + static_cast<size_t>(live ? n : 0) * M;
+    nvalid = 0;
+#pragma unroll
+    for (int j = 0; j < kEpl; ++j) {
+      const int idx = rl * kEpl + j;
+      const bool ok = live && idx < M;
+      val[j] = ok ? rowp[idx] : 0.f;
+      key[j] = ok ? order_key(val[j]) : 0u;
+      nvalid += ok ? 1u : 0u;
+    }
+    uint32_t sk[kEpl];
+#pragma unroll
+    for (int j = 0; j < kEpl; ++j) sk[j] = key[j];
+    sort8_desc(sk, sidx);
+#pragma unroll
+    for (int j = 0; j < kEpl; ++j) my_sorted[j * 64] = sk[j];
+  };
 
   // ---------------------------------------------------------- stage 1: Phi
   if (a.mode != DES_VANILLA) {
     const bool vote = a.mode == DES_VOTE;
     const int kk = (!vote && a.k_seq > 0) ? a.k_seq : K;
-    float vacc[E16];
+    float vacc[kEpl];
 #pragma unroll
-    for (int j = 0; j < E16; ++j) vacc[j] = 0.f;
+    for (int j = 0; j < kEpl; ++j) vacc[j] = 0.f;
 
-    for (int n0 = 0; n0 + wave * 4 < N; n0 += 64) {  // fixed token order per row
-      const int n = n0 + slot;
-      const bool live = n < N;
-      const float* rowp = Lg + static_cast<size_t>(live ? n : 0) * M;
-      float val[E16], p[E16];
-      uint32_t key[E16];
-#pragma unroll
-      for (int j = 0; j < E16; ++j) {
-        const int idx = rl * E16 + j;
-        const bool ok = live && idx < M;
-        val[j] = ok ? rowp[idx] : 0.f;
-        key[j] = ok ? order_key(val[j]) : 0u;
-        p[j] = 0.f;
-      }
+    for (int n0 = 0; n0 + wave * RPW < N; n0 += TPP) {  // fixed token order per row
+      float val[kEpl], p[kEpl];
+      uint32_t key[kEpl];
+      load_sort(n0 + slot, val, key);
+      DES_STAMP(a, 15);
       if (vote) {  // softmax over all M experts (Sec. 4.3), fp32
-        uint32_t lk = key[0];
-#pragma unroll
-        for (int j = 1; j < E16; ++j) lk = max(lk, key[j]);
-        const float mx = key_to_f32(row_max_u32(lk));
+        const float mx = key_to_f32(row_max_u32<LPT>(my_sorted[0]));
         float se = 0.f;
 #pragma unroll
-        for (int j = 0; j < E16; ++j) {
+        for (int j = 0; j < kEpl; ++j) {
           p[j] = key[j] ? exp_neg(val[j] - mx) : 0.f;
           se += p[j];
         }
-        const float den = row_sum_f32(se);
+        const float den = row_sum_f32<LPT>(se);
         const float inv = den > 0.f ? 1.0f / den : 0.f;
 #pragma unroll
-        for (int j = 0; j < E16; ++j) p[j] *= inv;
+        for (int j = 0; j < kEpl; ++j) p[j] *= inv;
       }
+      DES_STAMP(a, 16);
+      Head hd;
+      head_set(hd, (1u << nvalid) - 1u, my_sorted);
+      uint32_t taken = 0;  // original slots this token nominated
       for (int it = 0; it < kk; ++it) {  // Mask(I, K): the token's own top-K
-        int lj;
         bool mine;
-        row_argmax<E16>(key, lj, mine);
-#pragma unroll
-        for (int j = 0; j < E16; ++j) {
-          const bool hit = mine && j == lj;
-          key[j] = hit ? 0u : key[j];
-          vacc[j] += hit ? p[j] : 0.f;  // V_i += masked weight (Eq. 6)
-        }
+        row_draw<LPT>(hd, mine);
         if (mine) {
+          const uint32_t j = (sidx >> (3 * hd.h)) & 7u;
+          taken |= 1u << j;
+          const int e = rl * kEpl + static_cast<int>(j);
           if (vote) {
-            s_level[rl * E16 + lj] = 0;  // "nominated": only < K matters for votes
+            s_level[e] = 0;  // "nominated": only < K matters for votes
           } else {
-            atomicMin(&s_level[rl * E16 + lj], it);
-            if (it == 0) atomicAdd(&s_cnt1[rl * E16 + lj], 1);
+            atomicMin(&s_level[e], it);
+            if (it == 0) atomicAdd(&s_cnt1[e], 1);
           }
+          head_set(hd, hd.mask & (hd.mask - 1u), my_sorted);
         }
+      }
+      if (vote) {
+#pragma unroll
+        for (int j = 0; j < kEpl; ++j) vacc[j] += ((taken >> j) & 1u) ? p[j] : 0.f;  // Eq. 6
       }
     }
     DES_STAMP(a, 2);
     if (vote) {
-      // rows of a wave in the fixed order (r0 + r1) + (r2 + r3), then waves in order
+      // rows of a wave in a fixed pairwise order, then waves in order
 #pragma unroll
-      for (int j = 0; j < E16; ++j) {
+      for (int j = 0; j < kEpl; ++j) {
         float v = vacc[j];
-        v += __shfl_xor(v, 16);
-        v += __shfl_xor(v, 32);
-        if (row == 0) s_vpart[wave * MP + rl * E16 + j] = v;
+        if (RPW >= 2) v += __shfl_xor(v, LPT);
+        if (RPW >= 4) v += __shfl_xor(v, 2 * LPT);
+        if (RPW >= 8) v += __shfl_xor(v, 4 * LPT);
+        if (RPW >= 16) v += __shfl_xor(v, 8 * LPT);
+        if (row == 0) s_vpart[wave * MP + rl * kEpl + j] = v;
       }
     }
     __syncthreads();
@@ -336,7 +406,7 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem) {
         for (int w = 0; w < kRtWaves; ++w) v += s_vpart[w * MP + e];
         const bool nominated = e < M && s_level[e] < K;
         s_key[e] = nominated ? order_key(v) : 0u;
-        if (a.votes && e < M) a.votes[static_cast<size_t>(b) * M + e] = v;
+        if (a.votes && e < M && !dry) a.votes[static_cast<size_t>(b) * M + e] = v;
       }
       if (threadIdx.x == 0) s_hist[33] = 0;
     } else if (a.k_seq > 0) {  // Eq. 5 with the caller's k
@@ -367,7 +437,7 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem) {
     if (vote || s_hist[33] == 0) {  // top-C by key, ties to the lowest index
       // rank[e] = #{j : key[j] beats key[e]}; the j range is split over the
       // threads that share an expert, partial counts meet in an integer LDS add
-      constexpr int P = kRtThreads / MP >= 1 ? kRtThreads / MP : 1;
+      constexpr int P = kRtThreads / MP;
       for (int t = threadIdx.x; t < MP * P; t += kRtThreads) {
         const int e = t % MP, part = t / MP;
         const uint32_t ke = s_key[e];
@@ -398,14 +468,17 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem) {
       const bool f = e < MP && s_core[e] != 0;
       const unsigned long long bal = __ballot(f);
       const int pre = __popcll(bal & ((1ull << lane) - 1ull));
-      if (f && base + pre < a.cap) out[base + pre] = e;
+      if (f && base + pre < a.cap && !dry) out[base + pre] = e;
       base += __popcll(bal);
     }
-    for (int i = base + lane; i < a.cap; i += 64) out[i] = -1;
+    if (!dry)
+      for (int i = base + lane; i < a.cap; i += 64) out[i] = -1;
     if (lane == 0) {
-      a.coreset_size[b] = base;
       s_hist[34] = base;
-      if (a.k_seq_used) a.k_seq_used[b] = (a.mode == DES_SEQ) ? s_hist[33] : 0;
+      if (!dry) {
+        a.coreset_size[b] = base;
+        if (a.k_seq_used) a.k_seq_used[b] = (a.mode == DES_SEQ) ? s_hist[33] : 0;
+      }
     }
   }
   __syncthreads();
@@ -414,55 +487,55 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem) {
   DES_STAMP(a, 4);
   // ------------------------------ stage 2: constrained local routing + gates
   const int keff = min(K, s_hist[34]);
-  bool cm[E16];
-#pragma unroll
-  for (int j = 0; j < E16; ++j) cm[j] = (rl * E16 + j < M) && s_core[rl * E16 + j] != 0;
-  int* my_idx = s_sel_idx + (wave * 4 + row) * 32;
-  float* my_val = s_sel_val + (wave * 4 + row) * 32;
+  const bool reuse_sort = single_pass && a.mode != DES_VANILLA;  // stage 1 sorted this token
 
-  for (int n0 = 0; n0 + wave * 4 < N; n0 += 64) {
+  for (int n0 = 0; n0 + wave * RPW < N; n0 += TPP) {
     const int n = n0 + slot;
-    const bool live = n < N;
-    const float* rowp = Lg + static_cast<size_t>(live ? n : 0) * M;
-    float val[E16];
-    uint32_t key[E16];
-#pragma unroll
-    for (int j = 0; j < E16; ++j) {
-      const bool ok = live && cm[j];
-      val[j] = ok ? rowp[rl * E16 + j] : 0.f;
-      key[j] = ok ? order_key(val[j]) : 0u;
+    const bool live = n < N && !dry;
+    if (!reuse_sort) {
+      float val[kEpl];
+      uint32_t key[kEpl];
+      load_sort(n, val, key);
     }
-    for (int it = 0; it < keff; ++it) {  // S_n = TopK(I_n restricted to C, K)
-      int lj;
+    // candidates: sorted positions whose expert sits in the coreset
+    uint32_t cmask = 0;
+#pragma unroll
+    for (int sp = 0; sp < kEpl; ++sp) {
+      const int e = rl * kEpl + static_cast<int>((sidx >> (3 * sp)) & 7u);
+      cmask |= (static_cast<uint32_t>(sp) < nvalid && s_core[e] != 0) ? (1u << sp) : 0u;
+    }
+    Head hd;
+    head_set(hd, cmask, my_sorted);
+    const size_t o = (static_cast<size_t>(b) * N + (live ? n : 0)) * K;
+    float mx = 0.f, den = 0.f, mye[NW];
+#pragma unroll
+    for (int q = 0; q < NW; ++q) mye[q] = 0.f;
+    for (int it = 0; it < keff; ++it) {  // S_n = TopK(I_n restricted to C, K), best first
       bool mine;
-      row_argmax<E16>(key, lj, mine);
-      float lv = val[0];
+      const uint32_t m = row_draw<LPT>(hd, mine);
+      // every lane of the row sees the drawn logit: gate numerators in draw order
+      const float v = key_to_f32(m);
+      if (it == 0) mx = v;
+      const float ex = m ? exp_neg(v - mx) : 0.f;
+      den += ex;  // fixed order it = 0, 1, ...
 #pragma unroll
-      for (int j = 0; j < E16; ++j) {
-        const bool hit = j == lj;
-        lv = hit ? val[j] : lv;
-        key[j] = (mine && hit) ? 0u : key[j];
-      }
+      for (int q = 0; q < NW; ++q)
+        if (it == q * LPT + rl) mye[q] = ex;
       if (mine) {
-        my_idx[it] = rl * E16 + lj;
-        my_val[it] = lv;
+        if (live) a.topk_idx[o + it] = rl * kEpl + static_cast<int>((sidx >> (3 * hd.h)) & 7u);
+        head_set(hd, hd.mask & (hd.mask - 1u), my_sorted);
       }
     }
-    // g_n = softmax of the selected logits; slot 0 holds the largest.  A row
-    // has 16 lanes and K <= 32, so each lane covers slots rl and rl + 16.
-    const float mx = keff > 0 ? my_val[0] : 0.f;
-    const float e0 = rl < keff ? exp_neg(my_val[rl] - mx) : 0.f;
-    const float e1 = rl + 16 < keff ? exp_neg(my_val[rl + 16] - mx) : 0.f;
-    const float den = row_sum_f32(e0 + e1);
+    DES_STAMP(a, 17);
+    // g_n = softmax of the selected logits (Alg. 1 stage 2); unused slots -1 / 0
     if (live) {
-      const size_t o = (static_cast<size_t>(b) * N + n) * K;
-      if (rl < K) {
-        a.topk_idx[o + rl] = rl < keff ? my_idx[rl] : -1;
-        a.topk_w[o + rl] = rl < keff ? e0 / den : 0.f;
-      }
-      if (rl + 16 < K) {
-        a.topk_idx[o + rl + 16] = rl + 16 < keff ? my_idx[rl + 16] : -1;
-        a.topk_w[o + rl + 16] = rl + 16 < keff ? e1 / den : 0.f;
+#pragma unroll
+      for (int q = 0; q < NW; ++q) {
+        const int it = q * LPT + rl;
+        if (it < K) {
+          a.topk_w[o + it] = it < keff ? mye[q] / den : 0.f;
+          if (it >= keff) a.topk_idx[o + it] = -1;
+        }
       }
     }
   }
@@ -548,12 +621,15 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
 }
 
 // ---------------------------------------------------------------- the kernel
-constexpr int kRoutingLds = 64 * 1024;
+// LDS of the routing kernel: the selection's carve-up, but at least what the
+// router tile (16 KB) and the permutation (bitmap of at most 8192 words plus
+// 3M+2 counters, under 40 KB for every shape the library accepts) need.
+constexpr int kMinRoutingLds = 40 * 1024;
 
-template <int E16>
+template <int LPT>
 __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
-  __shared__ __align__(16) char smem[kRoutingLds];
-  static_assert(SelLds<E16>::total <= kRoutingLds, "selection scratch exceeds LDS budget");
+  constexpr int kLds = SelLds<LPT>::total > kMinRoutingLds ? SelLds<LPT>::total : kMinRoutingLds;
+  __shared__ __align__(16) char smem[kLds];
   const int n_tiles = a.do_router ? a.tiles_m * a.tiles_t : 0;
   int blk = blockIdx.x;
   if (blk < n_tiles) {  // ---- role R
@@ -578,7 +654,7 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
       return;
     }
     DES_STAMP(a, 1);
-    select_sequence<E16>(a, blk, smem);
+    select_sequence<LPT>(a, blk, smem, false);
     DES_STAMP(a, 5);
     if (a.topk_idx == nullptr) return;
     if (a.B == 1 && a.do_permute) {  // single sequence: permute right here
@@ -630,17 +706,32 @@ __global__ __launch_bounds__(64) void softmax_kernel(const float* __restrict__ l
 
 // ------------------------------------------------------------------ launchers
 static int launch_routing_grid(const RoutingArgs& a, int grid, int kernel_id, hipStream_t st) {
-  const int e16 = (a.M + 15) / 16;
+  const int lanes = (a.M + kEpl - 1) / kEpl;  // lanes a token's experts need, 8 experts each
   TimedScope ts(kernel_id, st);
   const dim3 g(grid), b(kRtThreads);
-  if (e16 <= 1) hipLaunchKernelGGL(routing_kernel<1>, g, b, 0, st, a);
-  else if (e16 <= 2) hipLaunchKernelGGL(routing_kernel<2>, g, b, 0, st, a);
-  else if (e16 <= 4) hipLaunchKernelGGL(routing_kernel<4>, g, b, 0, st, a);
-  else if (e16 <= 8) hipLaunchKernelGGL(routing_kernel<8>, g, b, 0, st, a);
-  else if (e16 <= 16) hipLaunchKernelGGL(routing_kernel<16>, g, b, 0, st, a);
-  else hipLaunchKernelGGL(routing_kernel<32>, g, b, 0, st, a);
+  if (lanes <= 4) hipLaunchKernelGGL(routing_kernel<4>, g, b, 0, st, a);
+  else if (lanes <= 8) hipLaunchKernelGGL(routing_kernel<8>, g, b, 0, st, a);
+  else if (lanes <= 16) hipLaunchKernelGGL(routing_kernel<16>, g, b, 0, st, a);
+  else if (lanes <= 32) hipLaunchKernelGGL(routing_kernel<32>, g, b, 0, st, a);
+  else hipLaunchKernelGGL(routing_kernel<64>, g, b, 0, st, a);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? DES_OK : hip_fail(e, "routing launch");
+}
+
+// Compute units of the current device (cached).  A routing workgroup fills a
+// whole compute unit (16 wavefronts at up to 128 registers), so the fused
+// launch may use at most this many workgroups if all are to be resident.
+static int device_compute_units() {
+  static int cached_dev = -1, cached_cus = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (dev != cached_dev) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+    cached_dev = dev;
+    cached_cus = n;
+  }
+  return cached_cus;
 }
 
 static void fill_common(RoutingArgs& a, const des_shape_t& s) {
@@ -701,7 +792,9 @@ int launch_routing(const des_shape_t& s, const void* x, const void* w_router, co
   a.epoch = epoch;
   const int n_tiles = a.tiles_m * a.tiles_t;
   const int roles = n_tiles + a.B + (a.B > 1 ? 1 : 0);
-  if (roles <= kMaxFusedRoutingBlocks) {  // all workgroups resident at once: one launch
+  int fused_limit = device_compute_units();
+  if (fused_limit > kMaxFusedRoutingBlocks) fused_limit = kMaxFusedRoutingBlocks;
+  if (roles <= fused_limit) {  // all workgroups resident at once: one launch
     a.do_router = a.do_select = a.do_permute = 1;
     a.use_flags = 1;
     return launch_routing_grid(a, roles, kKRouting, st);
