@@ -1,0 +1,107 @@
+"""The 48-layer residual stack (batch of 8 sequences x 32 tokens, each sequence
+electing its own DES-Vote coreset per layer, about 58 GB of expert weights):
+des_moe_stack_forward against a loop of des_moe_forward calls (bit-exact), and
+that loop against the CPU oracle, teacher-forced per layer - routing of every
+layer and sequence, layer outputs on sampled tokens of a few layers."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import des_oracle as O
+from paper_2602_00879_amd import binding as B
+from paper_2602_00879_amd import device_workloads as DW
+from paper_2602_00879_amd import workloads as W
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(m):
+    print(m, flush=True)
+
+
+def _run_stack_case(cfg, oracle_layers, n_tok_samples):
+    st = DW.make_stack(cfg)
+    torch.cuda.synchronize()
+    L, Bq, N, M, K = cfg.n_layers, cfg.n_seqs, cfg.n_tokens, cfg.n_experts, cfg.top_k
+    shape = B.make_shape(Bq, N, cfg.hidden, M, cfg.ffn, K, cfg.coreset, "vote", "bf16", residual=1)
+    _say(f"stack {cfg.name}: L={L} B={Bq} weights={sum(st[k].numel() for k in ('w_gate','w_up','w_down'))*2/1e9:.1f} GB")
+    out = B.des_moe_stack_forward(shape, L, st["x"], st["w_router"], st["bias"], st["w_gate"],
+                                  st["w_up"], st["w_down"])
+    torch.cuda.synchronize()
+    # the same stack as a loop over layers
+    cur = st["x"]
+    uniq = []
+    rng = np.random.default_rng(cfg.seed)
+    for l in range(L):
+        bias_l = None if st["bias"] is None else st["bias"][l]
+        r = B.des_moe_forward(shape, cur, st["w_router"][l], bias_l, st["w_gate"][l], st["w_up"][l],
+                              st["w_down"][l])
+        torch.cuda.synchronize()
+        assert torch.equal(r.expert_counts, out.expert_counts[l]), f"layer {l}: counts differ"
+        assert int(r.n_unique[0]) == int(out.n_unique[l])
+        uniq.append(int(r.n_unique[0]))
+        # routing of every layer and sequence against the oracle, teacher-forced
+        g_logits = r.logits.cpu().numpy()
+        want_y = l in oracle_layers
+        toks = None
+        if want_y:
+            pick = rng.choice(Bq * N, size=n_tok_samples, replace=False)
+            toks = [(int(p) // N, int(p) % N) for p in sorted(pick)]
+        x64 = cur.float().cpu().numpy().astype(np.float64)
+
+        class Lazy:  # one expert at a time, device -> host, exact widening
+            def __init__(self, t):
+                self.t = t
+
+            def __getitem__(self, e):
+                return self.t[e].float().cpu().numpy().astype(np.float64)
+
+        ref = O.moe_forward(x64, st["w_router"][l].float().cpu().numpy().astype(np.float64),
+                            None if bias_l is None else bias_l.cpu().numpy().astype(np.float64),
+                            Lazy(st["w_gate"][l]), Lazy(st["w_up"][l]), Lazy(st["w_down"][l]),
+                            K, cfg.coreset, "vote", logits_override=g_logits, residual=True,
+                            compute_y=want_y, only_tokens=toks)
+        assert min(ref["margins"]) > H.VOTE_MARGIN_MIN, f"layer {l}: vote boundary too close"
+        assert np.array_equal(r.topk_idx.cpu().numpy(), ref["topk_idx"]), f"layer {l}: topk_idx"
+        np.testing.assert_allclose(r.topk_w.cpu().numpy(), ref["topk_w"], rtol=H.GATE_RTOL, atol=H.GATE_ATOL)
+        assert np.array_equal(r.expert_counts.cpu().numpy(), ref["counts"]), f"layer {l}: counts"
+        cs = r.coreset_size.cpu().numpy()
+        ci = r.coreset_idx.cpu().numpy()
+        for b in range(Bq):
+            assert ci[b, :cs[b]].tolist() == ref["coresets"][b]
+        if l == 0:  # router scores against the float64 definition
+            lg = O.router_logits(x64.reshape(Bq * N, -1), st["w_router"][l].float().cpu().numpy().astype(np.float64),
+                                 None if bias_l is None else bias_l.cpu().numpy().astype(np.float64))
+            assert np.abs(lg.reshape(Bq, N, M) - g_logits).max() <= H.LOGIT_ATOL
+        if want_y:
+            y = r.y.float().cpu().numpy().astype(np.float64)
+            sel = np.zeros((Bq, N), dtype=bool)
+            for (b, n) in toks:
+                sel[b, n] = True
+            d = y[sel] - ref["y"][sel]
+            max_abs = np.abs(d).max()
+            rel = np.sqrt((d ** 2).sum() / (ref["y"][sel] ** 2).sum())
+            # the residual stream is O(1) and rounded to bf16 once per layer: its half-ulp
+            # (2^-9 relative) dominates; the MoE increment itself obeys the 2e-2 bound
+            assert max_abs <= H.BF16_MAX_ABS + 2.0 ** -8 * np.abs(ref["y"][sel]).max() and rel <= H.BF16_REL_L2, \
+                f"layer {l}: max_abs {max_abs:.3e} rel_l2 {rel:.3e}"
+            _say(f"  layer {l}: unique={uniq[-1]} max_abs={max_abs:.2e} rel_l2={rel:.2e}")
+        cur = r.y.clone()
+    assert torch.equal(cur, out.y), "stack output differs from the per-layer loop"
+    _say(f"  unique experts per layer: min {min(uniq)} max {max(uniq)} mean {np.mean(uniq):.1f}")
+    return uniq
+
+
+def test_small_stack():
+    cfg = W.LayerConfig("stack_small", "bf16", 3, 20, 128, 24, 64, 0, 4, 6, 1.1, 21, n_layers=5)
+    _run_stack_case(cfg, oracle_layers={0, 2, 4}, n_tok_samples=12)
+
+
+def test_stack48_full_size():
+    free, _ = torch.cuda.mem_get_info()
+    if free < 70e9:
+        pytest.skip("needs about 60 GB of free HBM")
+    cfg = W.CONFIGS["stack48"]
+    uniq = _run_stack_case(cfg, oracle_layers={0, 24, 47}, n_tok_samples=6)
+    assert all(32 <= u <= 128 for u in uniq)
