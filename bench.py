@@ -33,7 +33,10 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of the dominant kernel from rocprofv3 counters, in bytes per
 # launch (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size); the
 # summaries are under profiles/.  None until measured for a workload/layout.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/hbm_traffic_m128_zipf_vote_c32_packed.txt: 202,582,016 B read + 393,216 B written
+    ("m128_zipf", "vote", "packed"): 202582016 + 393216,
+}
 
 
 def parse():
@@ -191,9 +194,9 @@ def main():
 
 
 def cpu_baseline(cfg, layer, mode, C):
-    """The CPU oracle, as it stands, on the same block (bounded sample: the
-    router + election + routing for the whole block and the expert FFN for as
-    many of its tokens as fit in about 20 s), scaled to one block."""
+    """The CPU oracle, as it stands, on the same block: whole blocks (router,
+    election, re-routing and every token's expert FFNs) repeated until about
+    12 s of CPU work have been timed."""
     from oracle import des_oracle as O
     from paper_2602_00879_amd import workloads as W
     try:
@@ -201,9 +204,9 @@ def cpu_baseline(cfg, layer, mode, C):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:  # pragma: no cover
         threads = 1
-    f64 = {k: W.to_f64(layer[k]) for k in ("x", "w_router")}
+    x = W.to_f64(layer["x"])
+    wr = W.to_f64(layer["w_router"])
     bias = None if layer["bias"] is None else layer["bias"].astype(np.float64)
-    wg, wu, wd = layer["w_gate"], layer["w_up"], layer["w_down"]
 
     class Lazy:  # widen one expert at a time (exact), as the oracle's cache asks for it
         def __init__(self, a):
@@ -212,23 +215,18 @@ def cpu_baseline(cfg, layer, mode, C):
         def __getitem__(self, e):
             return W.to_f64(self.a[e])
 
+    wg, wu, wd = Lazy(layer["w_gate"]), Lazy(layer["w_up"]), Lazy(layer["w_down"])
     shared = tuple(W.to_f64(m) for m in layer["shared"]) if layer["shared"] else None
-    B_, N = cfg.n_seqs, cfg.n_tokens
-    n_sample = min(N, 8)
-    toks = [(0, n) for n in range(n_sample)]
-    t0 = time.perf_counter()
-    O.moe_forward(f64["x"], f64["w_router"], bias, Lazy(wg), Lazy(wu), Lazy(wd), cfg.top_k, C, mode,
-                  shared=shared, only_tokens=toks)
-    dt = time.perf_counter() - t0
-    # routing cost is counted once; the FFN part scales with the tokens
-    t1 = time.perf_counter()
-    O.moe_forward(f64["x"], f64["w_router"], bias, Lazy(wg), Lazy(wu), Lazy(wd), cfg.top_k, C, mode,
-                  shared=shared, compute_y=False)
-    dt_route = time.perf_counter() - t1
-    per_block = dt_route + (dt - dt_route) * (B_ * N) / n_sample
-    return {"value": per_block * 1e6, "unit": "us/block", "cores": threads, "kind": "oracle",
-            "sample": f"routing of the whole block + expert FFN of {n_sample} of {B_ * N} tokens "
-                      f"({dt:.1f} s measured), FFN part scaled to the block",
+    blocks, t0 = 0, time.perf_counter()
+    while True:
+        O.moe_forward(x, wr, bias, wg, wu, wd, cfg.top_k, C, mode, shared=shared)
+        blocks += 1
+        dt = time.perf_counter() - t0
+        if dt >= 12.0 or blocks >= 200:
+            break
+    return {"value": dt / blocks * 1e6, "unit": "us/block", "cores": threads, "kind": "oracle",
+            "sample": f"{blocks} whole blocks of the same workload in {dt:.1f} s "
+                      f"(float64 numpy, BLAS threads = cores)",
             "host_cpus": len(os.sched_getaffinity(0))}
 
 

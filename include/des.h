@@ -189,9 +189,9 @@ int des_pack_expert_weights(const void* src, void* dst, int64_t n_mats, int32_t 
 
 /*
  * Measurement aid, off by default and not part of the hot path: while enabled,
- * every kernel launch of this library is bracketed by a pair of HIP events on
- * the launch stream (the events are created on the host at launch time, so do
- * not enable it under graph capture).  des_kernel_timing_read() waits for the
+ * every kernel launch of this library carries a pair of HIP events that take
+ * the dispatch's own begin and end timestamps (the events are created on the
+ * host at launch time, so do not enable it under graph capture).  des_kernel_timing_read() waits for the
  * recorded events and returns the accumulated duration and launch count of one
  * kernel id in [0, des_kernel_timing_count()); des_kernel_timing_name() names
  * it (router, softmax, select, permute, gateup, down, combine, pack).

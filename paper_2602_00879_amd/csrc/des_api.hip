@@ -26,16 +26,18 @@ double g_ms[kKCount];
 long long g_launches[kKCount];
 }  // namespace
 
-void timing_mark(int kernel_id, hipStream_t st, bool begin) {
-  if (begin) {
-    TimedLaunch t;
-    t.id = kernel_id;
-    if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) return;
-    (void)hipEventRecord(t.start, st);
-    g_timed.push_back(t);
-  } else if (!g_timed.empty() && g_timed.back().id == kernel_id) {
-    (void)hipEventRecord(g_timed.back().stop, st);
+bool timing_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop) {
+  TimedLaunch t;
+  t.id = kernel_id;
+  if (hipEventCreate(&t.start) != hipSuccess) return false;
+  if (hipEventCreate(&t.stop) != hipSuccess) {
+    (void)hipEventDestroy(t.start);
+    return false;
   }
+  g_timed.push_back(t);
+  *start = t.start;
+  *stop = t.stop;
+  return true;
 }
 
 static void timing_collect() {

@@ -2,6 +2,7 @@
 // gfx950 (CDNA4) only: 64-wide wavefronts, DPP row broadcasts, bf16 MFMA.
 #pragma once
 
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -150,14 +151,23 @@ int hip_fail(hipError_t e, const char* what);  // records text, returns DES_ERR_
 // Kernel ids for the optional per-kernel event timing (des_kernel_timing_*).
 enum KernelId { kKRouter = 0, kKSoftmax, kKSelect, kKPermute, kKGateUp, kKDown, kKCombine, kKPack,
                 kKRouting, kKCount };
-void timing_mark(int kernel_id, hipStream_t st, bool begin);
 extern bool g_timing_on;
-// Brackets the launches issued in its scope with a pair of events when timing
-// is enabled; costs one predictable branch otherwise.
-struct TimedScope {
-  int id; hipStream_t st;
-  TimedScope(int kernel_id, hipStream_t s) : id(kernel_id), st(s) { if (g_timing_on) timing_mark(id, st, true); }
-  ~TimedScope() { if (g_timing_on) timing_mark(id, st, false); }
-};
+// Creates the event pair of one timed launch and remembers it under kernel_id.
+bool timing_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop);
+
+// Every kernel of the library is launched through here.  With timing enabled
+// the launch carries its own start/stop events (hipExtLaunchKernelGGL), which
+// take the dispatch's begin and end timestamps - the kernel's execution time,
+// not the time between two stream markers.
+template <typename Kern, typename... Args>
+inline void launch(int kernel_id, Kern kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st,
+                   Args... args) {
+  hipEvent_t ev0, ev1;
+  if (g_timing_on && timing_events(kernel_id, &ev0, &ev1)) {
+    hipExtLaunchKernelGGL(kernel, grid, block, lds, st, ev0, ev1, 0, args...);
+  } else {
+    hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+  }
+}
 
 }  // namespace des

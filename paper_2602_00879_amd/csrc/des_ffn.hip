@@ -552,10 +552,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
 int launch_pack(const void* src, void* dst, int64_t n_mats, int rows, int cols, hipStream_t st) {
   const long long groups = n_mats * rows * static_cast<long long>(cols) / 8;
   const long long blocks = (groups + 255) / 256;
-  TimedScope ts(kKPack, st);
-  hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
-                     static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), rows, cols,
-                     groups);
+  launch(kKPack, pack_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
+         static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), rows, cols, groups);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DES_OK : hip_fail(e, "pack launch");
 }
@@ -596,14 +594,8 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     const dim3 blk(kFfnWaves * kWave);
 #define DES_LAUNCH_FFN(NTV, PK)                                                             \
   do {                                                                                      \
-    {                                                                                       \
-      TimedScope ts(kKGateUp, st);                                                          \
-      hipLaunchKernelGGL((gateup_bf16_kernel<NTV, PK>), dim3(gu_blocks), blk, 0, st, a);    \
-    }                                                                                       \
-    {                                                                                       \
-      TimedScope ts(kKDown, st);                                                            \
-      hipLaunchKernelGGL((down_bf16_kernel<NTV, PK>), dim3(dn_blocks), blk, 0, st, a);      \
-    }                                                                                       \
+    launch(kKGateUp, gateup_bf16_kernel<NTV, PK>, dim3(gu_blocks), blk, 0, st, a);          \
+    launch(kKDown, down_bf16_kernel<NTV, PK>, dim3(dn_blocks), blk, 0, st, a);              \
   } while (0)
 #define DES_LAUNCH_BY_NT(PK)                                                                \
   do {                                                                                      \
@@ -618,24 +610,16 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
 #undef DES_LAUNCH_BY_NT
 #undef DES_LAUNCH_FFN
     dim3 cg(a.T, (a.D / 4 + 255) / 256);
-    TimedScope ts(kKCombine, st);
-    hipLaunchKernelGGL(combine_kernel<true>, cg, dim3(256), 0, st, a);
+    launch(kKCombine, combine_kernel<true>, cg, dim3(256), 0, st, a);
   } else {
     const int rows = TK + (a.Fs > 0 ? a.T : 0);
     const int Fm = a.F > a.Fs ? a.F : a.Fs;
-    {
-      TimedScope ts(kKGateUp, st);
-      hipLaunchKernelGGL(gateup_f32_kernel, dim3(rows, (Fm + 3) / 4 > 64 ? 64 : (Fm + 3) / 4),
-                         dim3(256), 0, st, a);
-    }
-    {
-      TimedScope ts(kKDown, st);
-      hipLaunchKernelGGL(down_f32_kernel, dim3(rows, (a.D + 3) / 4 > 64 ? 64 : (a.D + 3) / 4),
-                         dim3(256), 0, st, a);
-    }
+    launch(kKGateUp, gateup_f32_kernel, dim3(rows, (Fm + 3) / 4 > 64 ? 64 : (Fm + 3) / 4),
+           dim3(256), 0, st, a);
+    launch(kKDown, down_f32_kernel, dim3(rows, (a.D + 3) / 4 > 64 ? 64 : (a.D + 3) / 4),
+           dim3(256), 0, st, a);
     dim3 cg(a.T, (a.D / 4 + 255) / 256);
-    TimedScope ts(kKCombine, st);
-    hipLaunchKernelGGL(combine_kernel<false>, cg, dim3(256), 0, st, a);
+    launch(kKCombine, combine_kernel<false>, cg, dim3(256), 0, st, a);
   }
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DES_OK : hip_fail(e, "ffn launch");

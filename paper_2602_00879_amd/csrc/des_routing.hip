@@ -707,13 +707,12 @@ __global__ __launch_bounds__(64) void softmax_kernel(const float* __restrict__ l
 // ------------------------------------------------------------------ launchers
 static int launch_routing_grid(const RoutingArgs& a, int grid, int kernel_id, hipStream_t st) {
   const int lanes = (a.M + kEpl - 1) / kEpl;  // lanes a token's experts need, 8 experts each
-  TimedScope ts(kernel_id, st);
   const dim3 g(grid), b(kRtThreads);
-  if (lanes <= 4) hipLaunchKernelGGL(routing_kernel<4>, g, b, 0, st, a);
-  else if (lanes <= 8) hipLaunchKernelGGL(routing_kernel<8>, g, b, 0, st, a);
-  else if (lanes <= 16) hipLaunchKernelGGL(routing_kernel<16>, g, b, 0, st, a);
-  else if (lanes <= 32) hipLaunchKernelGGL(routing_kernel<32>, g, b, 0, st, a);
-  else hipLaunchKernelGGL(routing_kernel<64>, g, b, 0, st, a);
+  if (lanes <= 4) launch(kernel_id, routing_kernel<4>, g, b, 0, st, a);
+  else if (lanes <= 8) launch(kernel_id, routing_kernel<8>, g, b, 0, st, a);
+  else if (lanes <= 16) launch(kernel_id, routing_kernel<16>, g, b, 0, st, a);
+  else if (lanes <= 32) launch(kernel_id, routing_kernel<32>, g, b, 0, st, a);
+  else launch(kernel_id, routing_kernel<64>, g, b, 0, st, a);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? DES_OK : hip_fail(e, "routing launch");
 }
@@ -755,8 +754,7 @@ int launch_router(const des_shape_t& s, const void* x, const void* w_router, con
 
 int launch_softmax(const des_shape_t& s, const float* logits, float* probs, hipStream_t st) {
   const int T = s.n_seqs * s.n_tokens;
-  TimedScope ts(kKSoftmax, st);
-  hipLaunchKernelGGL(softmax_kernel, dim3(T), dim3(64), 0, st, logits, probs, s.n_experts);
+  launch(kKSoftmax, softmax_kernel, dim3(T), dim3(64), 0, st, logits, probs, s.n_experts);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? DES_OK : hip_fail(e, "softmax launch");
 }
