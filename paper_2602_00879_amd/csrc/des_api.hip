@@ -147,11 +147,12 @@ int des_moe_forward(const des_shape_t* s, const void* x, const void* w_router,
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return DES_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
+  const unsigned long long epoch = next_epoch();
   rc = launch_routing(*s, x, w_router, router_bias, logits, coreset_idx, coreset_size, topk_idx,
-                      topk_w, expert_counts, n_unique, ws, next_epoch(), st);
+                      topk_w, expert_counts, n_unique, ws, epoch, st);
   if (rc != DES_OK) return rc;
-  return launch_ffn(*s, x, w_gate, w_up, w_down, ws_gate, ws_up, ws_down, topk_idx, topk_w, y, ws,
-                    st);
+  return launch_ffn(*s, x, w_gate, w_up, w_down, ws_gate, ws_up, ws_down, topk_idx, topk_w,
+                    n_unique, y, ws, epoch, st);
 }
 
 // Stack scratch: two activation ping-pong buffers, per-layer routing outputs
@@ -221,11 +222,12 @@ int des_moe_stack_forward(const des_shape_t* s_in, int32_t n_layers, const void*
     int32_t* tidx = reinterpret_cast<int32_t*>(ws + l.topk_idx);
     float* tw = reinterpret_cast<float*>(ws + l.topk_w);
     char* lws = ws + l.layer_ws;
+    const unsigned long long epoch = next_epoch();
     rc = launch_routing(s, cur, wr, rb, logits, reinterpret_cast<int32_t*>(ws + l.core_idx),
                         reinterpret_cast<int32_t*>(ws + l.core_size), tidx, tw,
-                        expert_counts + li * M, n_unique + li, lws, next_epoch(), st);
+                        expert_counts + li * M, n_unique + li, lws, epoch, st);
     if (rc != DES_OK) return rc;
-    rc = launch_ffn(s, cur, wg, wu, wd, sg, su, sd, tidx, tw, out, lws, st);
+    rc = launch_ffn(s, cur, wg, wu, wd, sg, su, sd, tidx, tw, n_unique + li, out, lws, epoch, st);
     if (rc != DES_OK) return rc;
     cur = out;
   }
@@ -267,7 +269,7 @@ int des_kernel_timing_count(void) { return kKCount; }
 
 const char* des_kernel_timing_name(int kernel_id) {
   static const char* names[kKCount] = {"router", "softmax", "select", "permute", "gateup",
-                                       "down", "combine", "pack", "routing"};
+                                       "down", "combine", "pack", "routing", "ffn"};
   return (kernel_id >= 0 && kernel_id < kKCount) ? names[kernel_id] : "";
 }
 

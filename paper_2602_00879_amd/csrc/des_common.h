@@ -94,9 +94,23 @@ inline int max_live_experts(const des_shape_t& s) {
 // unit, and never more than this.
 constexpr int kMaxFusedRoutingBlocks = 256;
 
+// Readiness flags of the single-launch FFN: one per gate/up task (2 row tiles
+// of 16 intermediate units) and one per down task (64 output rows).
+inline size_t ffn_h_flags(const des_shape_t& s) {
+  return static_cast<size_t>(max_live_experts(s)) * (s.ffn / 32) + s.ffn_shared / 32;
+}
+inline size_t ffn_o_flags(const des_shape_t& s) {
+  return (static_cast<size_t>(max_live_experts(s)) + 1) * ((s.hidden / 16 + 3) / 4);
+}
+
+constexpr int kSlotToks = 32;  // tokens per slot kept in the slot-major token table
+
 // All offsets in bytes from the (256-byte aligned) workspace base.
 struct WsLayout {
   size_t flags;     // u64   [router tiles + B]  epoch flags of the routing launch
+  size_t ffn_flags; // u64   [ffn_h_flags + ffn_o_flags]  cleared by the routing launch
+  size_t slot_of;   // int32 [M]       slot of each live expert
+  size_t slot_tok;  // u16   [n_slots][kSlotToks]  tokens of each slot's first pairs
   size_t offsets;   // int32 [M + 1]   exclusive scan of expert_counts
   size_t slots;     // int4  [n_slots] {expert, first sorted pair, pairs, 0}; expert -1 = unused
   size_t meta;      // int32 [64]      [0] live experts, [1] routed pairs
@@ -119,6 +133,9 @@ inline WsLayout ws_layout(const des_shape_t& s) {
   WsLayout w;
   size_t p = 0;
   w.flags = p;    p = align256(p + 8 * (tiles + s.n_seqs));
+  w.ffn_flags = p; p = align256(p + 8 * (ffn_h_flags(s) + ffn_o_flags(s)));
+  w.slot_of = p;  p = align256(p + 4 * static_cast<size_t>(s.n_experts));
+  w.slot_tok = p; p = align256(p + 2 * static_cast<size_t>(max_live_experts(s)) * kSlotToks);
   w.offsets = p;  p = align256(p + 4 * (static_cast<size_t>(s.n_experts) + 1));
   w.slots = p;    p = align256(p + 16 * static_cast<size_t>(max_live_experts(s)));
   w.meta = p;     p = align256(p + 4 * 64);
@@ -143,14 +160,15 @@ int launch_routing(const des_shape_t& s, const void* x, const void* w_router, co
                    unsigned long long epoch, hipStream_t st);
 int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const void* w_up,
                const void* w_down, const void* ws_gate, const void* ws_up, const void* ws_down,
-               const int32_t* topk_idx, const float* topk_w, void* y, char* ws, hipStream_t st);
+               const int32_t* topk_idx, const float* topk_w, int32_t* n_unique, void* y, char* ws,
+               unsigned long long epoch, hipStream_t st);
 int launch_pack(const void* src, void* dst, int64_t n_mats, int rows, int cols, hipStream_t st);
 
 int hip_fail(hipError_t e, const char* what);  // records text, returns DES_ERR_HIP
 
 // Kernel ids for the optional per-kernel event timing (des_kernel_timing_*).
 enum KernelId { kKRouter = 0, kKSoftmax, kKSelect, kKPermute, kKGateUp, kKDown, kKCombine, kKPack,
-                kKRouting, kKCount };
+                kKRouting, kKFfn, kKCount };
 extern bool g_timing_on;
 // Creates the event pair of one timed launch and remembers it under kernel_id.
 bool timing_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop);

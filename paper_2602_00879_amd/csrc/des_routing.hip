@@ -64,6 +64,10 @@ struct RoutingArgs {
   int32_t* pos;           // [T*K] sorted position of pair (t*K+j), -1 = unused slot
   unsigned long long* flags;  // [n_tiles + B] epoch flags
   unsigned long long epoch;
+  unsigned long long* ffn_flags;  // readiness flags of the FFN launch, cleared here
+  int n_ffn_flags;
+  int32_t* slot_of;       // [M] slot of each live expert, -1 otherwise
+  uint16_t* slot_tok;     // [n_slots][kSlotToks] tokens of each slot's first pairs
   int B, N, M, K, C, k_seq, mode, cap, D, n_slots;
   int tiles_m, tiles_t;   // router tiles along experts / tokens
   int do_router, do_select, do_permute, use_flags, bf16;
@@ -81,7 +85,8 @@ __device__ __forceinline__ bool flags_wait(const unsigned long long* f, int n,
   bool ok = true;
   for (int i = threadIdx.x; i < n; i += blockDim.x) {
     int it = 0;
-    while (__hip_atomic_load(f + i, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+    // relaxed polls; the fence after the barrier below is the acquire
+    while (__hip_atomic_load(f + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
       __builtin_amdgcn_s_sleep(4);
       if (++it > kMaxWaitIters) { ok = false; break; }
     }
@@ -604,9 +609,17 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
   __syncthreads();
   const int n_live = s_liv[M];
   for (int e = tid; e <= M; e += kRtThreads) a.offsets[e] = s_off[e];
-  for (int e = tid; e < M; e += kRtThreads)
-    if (s_cnt[e] > 0 && s_liv[e] < a.n_slots) a.slots[s_liv[e]] = make_int4(e, s_off[e], s_cnt[e], 0);
+  for (int e = tid; e < M; e += kRtThreads) {
+    const bool live = s_cnt[e] > 0 && s_liv[e] < a.n_slots;
+    if (live) a.slots[s_liv[e]] = make_int4(e, s_off[e], s_cnt[e], 0);
+    a.slot_of[e] = live ? s_liv[e] : -1;
+  }
+  for (int i = tid; i < a.n_ffn_flags; i += kRtThreads) a.ffn_flags[i] = 0ull;
   for (int s = n_live + tid; s < a.n_slots; s += kRtThreads) a.slots[s] = make_int4(-1, 0, 0, 0);
+  // entries of the slot-major token table past a slot's count must still name a
+  // valid token: clear the table, then (after the barrier) fill it
+  for (int i = tid; i < a.n_slots * kSlotToks; i += kRtThreads) a.slot_tok[i] = 0;
+  __syncthreads();
   for (int p = tid; p < TK; p += kRtThreads) {
     const int e = a.topk_idx[p];
     if (e < 0) { a.pos[p] = -1; continue; }
@@ -617,6 +630,9 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
     r += __popc(mrow[t >> 5] & ((1u << (t & 31)) - 1u));
     a.pair_tok[r] = t;
     a.pos[p] = r;
+    const int within = r - s_off[e];
+    if (within < kSlotToks && s_liv[e] < a.n_slots)
+      a.slot_tok[s_liv[e] * kSlotToks + within] = static_cast<uint16_t>(t);
   }
 }
 
@@ -788,6 +804,10 @@ int launch_routing(const des_shape_t& s, const void* x, const void* w_router, co
   a.pos = reinterpret_cast<int32_t*>(ws + w.pos);
   a.flags = reinterpret_cast<unsigned long long*>(ws + w.flags);
   a.epoch = epoch;
+  a.ffn_flags = reinterpret_cast<unsigned long long*>(ws + w.ffn_flags);
+  a.n_ffn_flags = static_cast<int>(ffn_h_flags(s) + ffn_o_flags(s));
+  a.slot_of = reinterpret_cast<int32_t*>(ws + w.slot_of);
+  a.slot_tok = reinterpret_cast<uint16_t*>(ws + w.slot_tok);
   const int n_tiles = a.tiles_m * a.tiles_t;
   const int roles = n_tiles + a.B + (a.B > 1 ? 1 : 0);
   int fused_limit = device_compute_units();
