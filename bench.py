@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="m128_zipf",
-                    choices=["m128_zipf", "m256_shared", "tiny_f32"])
+                    choices=["m128_zipf", "m256_shared", "tiny_f32", "stack48"])
     ap.add_argument("--mode", default="vote", choices=["vanilla", "seq", "vote"])
     ap.add_argument("--coreset", type=int, default=None)
     ap.add_argument("--n-tokens", type=int, default=None)
@@ -73,6 +73,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.workload == "stack48":
+        return bench_stack(args, torch, B, W, dev)
     cfg = W.CONFIGS[args.workload]
     if args.n_tokens:
         cfg = cfg.with_(n_tokens=args.n_tokens)
@@ -190,6 +192,63 @@ def main():
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, layer, args.mode, C)
+    print(json.dumps(out))
+
+
+def bench_stack(args, torch, B, W, dev):
+    """The 48-layer residual stack (8 sequences x 32 tokens, DES-Vote C=32 per
+    sequence and layer, ~58 GB of expert weights resident): us per decoding step.
+    A context figure: the headline metric is the single layer above."""
+    from paper_2602_00879_amd import device_workloads as DW
+    cfg = W.CONFIGS["stack48"]
+    st = DW.make_stack(cfg, dev)
+    packed = args.layout == "packed"
+    if packed:
+        for k in ("w_gate", "w_up", "w_down"):
+            for l in range(cfg.n_layers):  # layer by layer: bounds the temporary
+                st[k][l] = B.des_pack_expert_weights(st[k][l])
+    torch.cuda.synchronize()
+    layout = B.DES_LAYOUT_PACKED if packed else B.DES_LAYOUT_ROWMAJOR
+    shape = B.make_shape(cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k,
+                         args.coreset or cfg.coreset, args.mode, cfg.dtype, weight_layout=layout,
+                         residual=1)
+    bufs = B.StackBuffers(shape, cfg.n_layers, dev, torch.bfloat16)
+
+    def step():
+        B.des_moe_stack_forward(shape, cfg.n_layers, st["x"], st["w_router"], st["bias"],
+                                st["w_gate"], st["w_up"], st["w_down"], buffers=bufs)
+
+    steps = max(1, min(args.steps, 50))
+    for _ in range(min(args.warmup, 5)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    uniq = bufs.n_unique.cpu().numpy()
+    B.des_kernel_timing_enable(True)
+    step()
+    torch.cuda.synchronize()
+    kt = B.des_kernel_timing_read()
+    B.des_kernel_timing_enable(False)
+    per_expert = 3 * cfg.hidden * cfg.ffn * 2
+    unique_bytes = int(uniq.sum()) * per_expert
+    out = {
+        "metric": "48-layer MoE stack us per decoding step (DES-Vote per sequence and layer)",
+        "value": ms * 1e3, "unit": "us/step", "n_gpus": 1, "steps": steps, "warmup": min(args.warmup, 5),
+        "ms_per_step": ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"stack48: L={cfg.n_layers} B={cfg.n_seqs} N={cfg.n_tokens} M={cfg.n_experts} "
+                               f"D={cfg.hidden} F={cfg.ffn} K={cfg.top_k} mode={args.mode} C={args.coreset or cfg.coreset}",
+                   "weight_layout": args.layout},
+        "unique_experts_per_layer_mean": float(uniq.mean()),
+        "unique_expert_bytes_per_step": unique_bytes,
+        "expert_weight_GBps_whole_step": unique_bytes / (ms * 1e-3) / 1e9,
+        "pct_of_hbm_peak_whole_step": 100.0 * unique_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "kernel_us_per_layer": {k: v[0] * 1e3 / v[1] for k, v in kt.items() if v[1] > 0},
+    }
     print(json.dumps(out))
 
 

@@ -545,6 +545,226 @@ __global__ __launch_bounds__(kFfnWaves* kWave) void down_bf16_kernel(FfnArgs a) 
   if (task < tasks) down_task<MAXNT, PACKED, false>(a, task, lane);
 }
 
+// ------------------------------------------ larger blocks: activations via LDS
+// With more than two token tiles per expert the direct scheme above runs out
+// of registers for its prefetch (every token fragment is double-buffered in
+// registers) and re-reads the activations once per wavefront.  For T > 32 the
+// expert's activation rows are staged through LDS instead: a workgroup of four
+// wavefronts works on one expert, each wavefront streams its own weight rows
+// from HBM straight into MFMA operands as before, and all four read the token
+// fragments of the current 128-wide reduction chunk from LDS, which the
+// workgroup fills cooperatively one chunk ahead.  The weights are still read
+// once; the activations are read from L2 once per workgroup, not per wavefront.
+constexpr int kLW = 4;              // wavefronts per workgroup
+constexpr int kKC = 128;            // reduction elements per LDS chunk (4 k-steps)
+constexpr int kLRow = kKC + 8;      // padded LDS row: 272 B, spreads rows over banks
+constexpr int kLRows = 128;         // token rows per workgroup pass (8 token tiles)
+constexpr int kLPieces = kLRows / 16;  // 16-byte pieces a thread moves per chunk
+struct LdsGemm {
+  uint16_t buf[2][kLRows * kLRow];
+  const uint16_t* rowptr[kLRows];   // global row of each token row of this pass
+};
+
+// acc0/acc1 += A0/A1 (this wavefront's two 16-row weight tiles, reduction
+// length kd) x rows (the workgroup's token rows).  All four wavefronts call it.
+template <int NT, bool PACKED>
+__device__ __forceinline__ void lds_stream_gemm(const uint16_t* a0, const uint16_t* a1, bool active,
+                                                int kd, int rows_valid, LdsGemm& sm,
+                                                f32x4 (&acc0)[NT], f32x4 (&acc1)[NT]) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int nks = kd / 32;
+  const int nchunks = (kd + kKC - 1) / kKC;
+  const int c16 = tid & 15, r0 = tid >> 4;  // this thread's 16-byte column and first row
+  bf16x8 st[kLPieces];
+  bf16x8 aw0[2][4], aw1[2][4];
+  auto gload = [&](int chunk) {
+#pragma unroll
+    for (int i = 0; i < kLPieces; ++i) {
+      const int row = r0 + 16 * i;
+      const int k = chunk * kKC + c16 * 8;
+      st[i] = (row < rows_valid && k < kd) ? ld8(sm.rowptr[row] + k) : zero8();
+    }
+  };
+  auto lstore = [&](int b) {
+#pragma unroll
+    for (int i = 0; i < kLPieces; ++i)
+      *reinterpret_cast<bf16x8*>(&sm.buf[b][(r0 + 16 * i) * kLRow + c16 * 8]) = st[i];
+  };
+  auto loadw = [&](int chunk, auto stage) {
+    constexpr int s = decltype(stage)::value;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int ks = chunk * 4 + u;
+      const bool ok = active && ks < nks;
+      aw0[s][u] = ok ? ld8_stream(a0 + static_cast<size_t>(ks) * frag_step<PACKED>()) : zero8();
+      aw1[s][u] = ok ? ld8_stream(a1 + static_cast<size_t>(ks) * frag_step<PACKED>()) : zero8();
+    }
+  };
+  auto compute = [&](int b, auto stage) {
+    constexpr int s = decltype(stage)::value;
+    if (!active) return;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        const bf16x8 bv = *reinterpret_cast<const bf16x8*>(
+            &sm.buf[b][(i * 16 + (lane & 15)) * kLRow + u * 32 + (lane >> 4) * 8]);
+        acc0[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw0[s][u], bv, acc0[i], 0, 0, 0);
+        acc1[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw1[s][u], bv, acc1[i], 0, 0, 0);
+      }
+    }
+  };
+  gload(0);
+  loadw(0, S0{});
+  lstore(0);
+  __syncthreads();
+  for (int c = 0; c < nchunks; c += 2) {
+    // chunk c from buffer 0 / stage 0 while chunk c+1 is fetched
+    if (c + 1 < nchunks) { gload(c + 1); loadw(c + 1, S1{}); }
+    compute(0, S0{});
+    if (c + 1 < nchunks) lstore(1);
+    __syncthreads();
+    if (c + 1 >= nchunks) break;
+    if (c + 2 < nchunks) { gload(c + 2); loadw(c + 2, S0{}); }
+    compute(1, S1{});
+    if (c + 2 < nchunks) lstore(0);
+    __syncthreads();
+  }
+}
+
+// Which expert and which pairs a workgroup works on (as Task), shared by the two kernels.
+template <bool DOWN>
+__device__ __forceinline__ bool lds_task(const FfnArgs& a, int per_expert, int& group, Task& t,
+                                         FfnArgs& v, int lane) {
+  const int routed = a.n_slots * per_expert;
+  const int task = blockIdx.x;
+  v = a;
+  if (task < routed) {
+    if (!make_task(a, task / per_expert, false, DOWN, t, lane)) return false;
+    group = task % per_expert;
+  } else {
+    make_task(a, 0, true, DOWN, t, lane);
+    v = shared_view(a, t, 2);
+    group = task - routed;
+  }
+  return true;
+}
+
+template <bool PACKED>
+__global__ __launch_bounds__(kLW* kWave) void gateup_lds_kernel(FfnArgs a) {
+  __shared__ __align__(16) LdsGemm sm;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  Task t;
+  FfnArgs v;
+  int group;
+  const int per_r = (a.F / 16 + kLW - 1) / kLW;
+  const int per_s = (a.Fs / 16 + kLW - 1) / kLW;
+  if (static_cast<int>(blockIdx.x) >= a.n_slots * per_r + per_s) return;
+  if (!lds_task<false>(a, per_r, group, t, v, lane)) return;  // uniform per workgroup
+  // blockIdx.y picks 128 of the expert's pairs: an expert with more pairs than
+  // that is spread over two or more workgroups instead of looping in one (its
+  // weights are then read once per 128 pairs; measured faster than looping,
+  // while 64-pair groups were slower: the extra weight reads are real HBM reads)
+  const int tile = group * kLW + wave;
+  const bool active = tile < t.fdim / 16;
+  const uint16_t* gp = frag_ptr<PACKED>(t.w0, active ? tile : 0, a.D, lane);
+  const uint16_t* up = frag_ptr<PACKED>(t.w1, active ? tile : 0, a.D, lane);
+  const uint16_t* x = static_cast<const uint16_t*>(a.x);
+  uint16_t* h = static_cast<uint16_t*>(v.h);
+  for (int g0 = blockIdx.y * kLRows; g0 < t.count; g0 += gridDim.y * kLRows) {
+    const int rows = min(kLRows, t.count - g0);
+    if (tid < kLRows) {
+      const int pi = min(g0 + tid, t.count - 1);
+      const int tok = t.shared ? pi : a.pair_tok[t.pair0 + pi];
+      sm.rowptr[tid] = x + static_cast<size_t>(tok) * a.D;
+    }
+    __syncthreads();
+    const int nt = (rows + 15) / 16;
+    auto run = [&](auto ntc) {
+      constexpr int NT = decltype(ntc)::value;
+      f32x4 accg[NT], accu[NT];
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        accg[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        accu[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+      lds_stream_gemm<NT, PACKED>(gp, up, active, a.D, rows, sm, accg, accu);
+      if (!active) return;
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        const int pi = g0 + i * 16 + (lane & 15);
+        if (pi < t.count) {
+          u16x4 o;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) o[q] = f32_to_bf16_bits(silu_f(accg[i][q]) * accu[i][q]);
+          *reinterpret_cast<u16x4*>(h + (t.row_base + pi) * t.fdim + tile * 16 + 4 * (lane >> 4)) = o;
+        }
+      }
+    };
+    if (nt <= 1) run(std::integral_constant<int, 1>{});
+    else if (nt <= 2) run(std::integral_constant<int, 2>{});
+    else if (nt <= 4) run(std::integral_constant<int, 4>{});
+    else if (nt <= 6) run(std::integral_constant<int, 6>{});
+    else run(std::integral_constant<int, 8>{});
+    __syncthreads();  // the next pass rewrites rowptr and the buffers
+  }
+}
+
+template <bool PACKED>
+__global__ __launch_bounds__(kLW* kWave) void down_lds_kernel(FfnArgs a) {
+  __shared__ __align__(16) LdsGemm sm;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  Task t;
+  FfnArgs v;
+  int group;
+  const int dtiles = a.D / 16;                       // even: D is a multiple of 32
+  const int per = (dtiles / 2 + kLW - 1) / kLW;      // a wavefront owns two row tiles
+  if (static_cast<int>(blockIdx.x) >= a.n_slots * per + (a.Fs > 0 ? per : 0)) return;
+  if (!lds_task<true>(a, per, group, t, v, lane)) return;
+  const int dt0 = (group * kLW + wave) * 2;
+  const bool active = dt0 < dtiles;
+  const int F = t.fdim;
+  const uint16_t* p0 = frag_ptr<PACKED>(t.w0, active ? dt0 : 0, F, lane);
+  const uint16_t* p1 = frag_ptr<PACKED>(t.w0, active ? dt0 + 1 : 0, F, lane);
+  const uint16_t* h = static_cast<const uint16_t*>(v.h);
+  const size_t orow0 = t.shared ? static_cast<size_t>(a.T) * a.K : static_cast<size_t>(t.pair0);
+  for (int g0 = blockIdx.y * kLRows; g0 < t.count; g0 += gridDim.y * kLRows) {
+    const int rows = min(kLRows, t.count - g0);
+    if (tid < kLRows) {
+      const int pi = min(g0 + tid, t.count - 1);
+      sm.rowptr[tid] = h + (t.row_base + pi) * F;
+    }
+    __syncthreads();
+    const int nt = (rows + 15) / 16;
+    auto run = [&](auto ntc) {
+      constexpr int NT = decltype(ntc)::value;
+      f32x4 acc0[NT], acc1[NT];
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        acc0[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc1[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+      lds_stream_gemm<NT, PACKED>(p0, p1, active, F, rows, sm, acc0, acc1);
+      if (!active) return;
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        const int pi = g0 + i * 16 + (lane & 15);
+        if (pi < t.count) {
+          float* dst = a.o + (orow0 + pi) * a.D + dt0 * 16 + 4 * (lane >> 4);
+          *reinterpret_cast<f32x4*>(dst) = acc0[i];
+          *reinterpret_cast<f32x4*>(dst + 16) = acc1[i];
+        }
+      }
+    };
+    if (nt <= 1) run(std::integral_constant<int, 1>{});
+    else if (nt <= 2) run(std::integral_constant<int, 2>{});
+    else if (nt <= 4) run(std::integral_constant<int, 4>{});
+    else if (nt <= 6) run(std::integral_constant<int, 6>{});
+    else run(std::integral_constant<int, 8>{});
+    __syncthreads();
+  }
+}
+
 // ------------------------------------------------------------------ fp32 path
 // Plain fused-multiply-add kernels for the small fp32 configuration: one
 // wavefront per output element row-chunk, lanes stride the reduction
@@ -887,8 +1107,25 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     else if (maxnt <= 8) DES_LAUNCH_FFN(8, PK);                                             \
     else DES_LAUNCH_FFN(16, PK);                                                            \
   } while (0)
-    if (packed) DES_LAUNCH_BY_NT(true);
-    else DES_LAUNCH_BY_NT(false);
+    if (a.T > 32 && !fused_requested) {
+      // larger blocks: activations staged through LDS, four wavefronts per expert group
+      const int gu_lds = a.n_slots * ((a.F / 16 + kLW - 1) / kLW) + (a.Fs / 16 + kLW - 1) / kLW;
+      const int per_dn = (a.D / 32 + kLW - 1) / kLW;
+      const int dn_lds = a.n_slots * per_dn + (a.Fs > 0 ? per_dn : 0);
+      int splits = (a.T + kLRows - 1) / kLRows;  // token groups of 128 (grid.y), at most 8
+      if (splits > 8) splits = 8;
+      if (packed) {
+        launch(kKGateUp, gateup_lds_kernel<true>, dim3(gu_lds, splits), dim3(kLW * kWave), 0, st, a);
+        launch(kKDown, down_lds_kernel<true>, dim3(dn_lds, splits), dim3(kLW * kWave), 0, st, a);
+      } else {
+        launch(kKGateUp, gateup_lds_kernel<false>, dim3(gu_lds, splits), dim3(kLW * kWave), 0, st, a);
+        launch(kKDown, down_lds_kernel<false>, dim3(dn_lds, splits), dim3(kLW * kWave), 0, st, a);
+      }
+    } else if (packed) {
+      DES_LAUNCH_BY_NT(true);
+    } else {
+      DES_LAUNCH_BY_NT(false);
+    }
 #undef DES_LAUNCH_BY_NT
 #undef DES_LAUNCH_FFN
 #undef DES_TRY_FUSED
