@@ -304,11 +304,13 @@ constexpr int kFfnWaves = 1;  // wavefronts per workgroup; each is an independen
 constexpr int kGuTiles = 2;   // gate/up row tiles per task (F % 32 == 0, so F/16 is even)
 
 // MAXNT bounds the token tiles a task can have (the host knows T >= any expert's
-// count), so that small blocks get a kernel with few registers and high
-// occupancy.
+// count), so that small blocks get a kernel with few registers.  U1 / U2 are
+// the k-steps per prefetch stage of the one- and two-token-tile paths; two
+// stages of two k-steps measured best on the 128-expert layer (34.3 us against
+// 36.2 us for four and 34.5 us for one).
 // One gate/up task (see the kernel comment): returns false if the slot is unused.
 // `fused`: publish the task's readiness flag when its H rows are stored.
-template <int MAXNT, bool PACKED, bool FUSED>
+template <int MAXNT, bool PACKED, bool FUSED, int U1 = 2, int U2 = 2>
 __device__ __forceinline__ bool gateup_task(const FfnArgs& a, int task, int lane) {
   const int tiles_r = a.F / (16 * kGuTiles);
   const int routed = a.n_slots * tiles_r;
@@ -326,12 +328,12 @@ __device__ __forceinline__ bool gateup_task(const FfnArgs& a, int task, int lane
   const int nt = (t.count + 15) / 16;
   bool done = false;
   if (MAXNT == 1 || nt <= 1) {
-    gateup_group<kGuTiles, 1, 4, PACKED, FUSED>(v, t, ft, 0, lane);
+    gateup_group<kGuTiles, 1, U1, PACKED, FUSED>(v, t, ft, 0, lane);
     done = true;
   }
   if constexpr (MAXNT >= 2) {
     if (!done && (MAXNT == 2 || nt <= 2)) {
-      gateup_group<kGuTiles, 2, 2, PACKED, FUSED>(v, t, ft, 0, lane);
+      gateup_group<kGuTiles, 2, U2, PACKED, FUSED>(v, t, ft, 0, lane);
       done = true;
     }
   }
@@ -359,14 +361,16 @@ __device__ __forceinline__ bool gateup_task(const FfnArgs& a, int task, int lane
 }
 
 // MAXNT bounds the token tiles a task can have (the host knows T >= any expert's
-// count), so that small blocks get a kernel with few registers and high
-// occupancy.
-template <int MAXNT, bool PACKED>
+// count), so that small blocks get a kernel with few registers.  U1 / U2 are
+// the k-steps per prefetch stage of the one- and two-token-tile paths; two
+// stages of two k-steps measured best on the 128-expert layer (34.3 us against
+// 36.2 us for four and 34.5 us for one).
+template <int MAXNT, bool PACKED, int U1 = 2, int U2 = 2>
 __global__ __launch_bounds__(kFfnWaves* kWave) void gateup_bf16_kernel(FfnArgs a) {
   const int lane = threadIdx.x & 63;
   const int task = blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
   const int tasks = a.n_slots * (a.F / (16 * kGuTiles)) + a.Fs / (16 * kGuTiles);
-  if (task < tasks) gateup_task<MAXNT, PACKED, false>(a, task, lane);
+  if (task < tasks) gateup_task<MAXNT, PACKED, false, U1, U2>(a, task, lane);
 }
 
 // down for pairs [g0, g0+16*NT), output rows (dt0 .. dt0+RT-1)*16
@@ -462,7 +466,7 @@ __device__ __forceinline__ void down_group(const FfnArgs& a, const Task& t, int 
 }
 
 // One down task: 64 output rows of one expert for all of its pairs.
-template <int MAXNT, bool PACKED, bool FUSED>
+template <int MAXNT, bool PACKED, bool FUSED, int U1 = 2, int U2 = 2>
 __device__ __forceinline__ bool down_task(const FfnArgs& a, int task, int lane) {
   const int dtiles = a.D / 16;
   const int groups = (dtiles + 3) / 4;  // 64 output rows per task
@@ -493,12 +497,12 @@ __device__ __forceinline__ bool down_task(const FfnArgs& a, int task, int lane) 
   bool done = false;
   if (dt_end - dt_begin == 4) {
     if (MAXNT == 1 || nt <= 1) {
-      down_group<4, 1, 4, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
+      down_group<4, 1, U1, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
       done = true;
     }
     if constexpr (MAXNT >= 2) {
       if (!done && (MAXNT == 2 || nt <= 2)) {
-        down_group<4, 2, 2, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
+        down_group<4, 2, U2, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
         done = true;
       }
     }
@@ -536,13 +540,13 @@ __device__ __forceinline__ bool down_task(const FfnArgs& a, int task, int lane) 
   return true;
 }
 
-template <int MAXNT, bool PACKED>
+template <int MAXNT, bool PACKED, int U1 = 2, int U2 = 2>
 __global__ __launch_bounds__(kFfnWaves* kWave) void down_bf16_kernel(FfnArgs a) {
   const int lane = threadIdx.x & 63;
   const int task = blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
   const int groups = (a.D / 16 + 3) / 4;
   const int tasks = a.n_slots * groups + (a.Fs > 0 ? groups : 0);
-  if (task < tasks) down_task<MAXNT, PACKED, false>(a, task, lane);
+  if (task < tasks) down_task<MAXNT, PACKED, false, U1, U2>(a, task, lane);
 }
 
 // ------------------------------------------ larger blocks: activations via LDS
