@@ -208,27 +208,38 @@ __device__ __forceinline__ float key_to_f32(uint32_t k) {
 
 constexpr int kEpl = 8;  // experts per lane
 
-// A lane's 8 (key, slot) pairs sorted once, best first.  Odd-even transposition
-// with strict comparisons is stable, so equal keys keep ascending expert order;
-// every later "best remaining candidate" is then a head pointer, not a rescan.
-// `idx` packs the original slot of sorted position s in bits [3s, 3s+3).
+// A lane's 8 (key, slot) pairs sorted once, best first; every later "best
+// remaining candidate" is then a head pointer, not a rescan.  The pair is one
+// 64-bit word, key << 3 | (7 - slot), so that equal keys order by ascending
+// slot (= ascending expert index) and a plain 19-comparator network does the
+// job.  `idx` packs the original slot of sorted position s in bits [3s, 3s+3).
 __device__ __forceinline__ void sort8_desc(uint32_t (&k)[kEpl], uint32_t& idx) {
-  uint32_t id[kEpl];
+  unsigned long long c[kEpl];
 #pragma unroll
-  for (int j = 0; j < kEpl; ++j) id[j] = j;
-#pragma unroll
-  for (int round = 0; round < kEpl; ++round) {
-#pragma unroll
-    for (int i = round & 1; i + 1 < kEpl; i += 2) {
-      const bool sw = k[i] < k[i + 1];
-      const uint32_t hi = max(k[i], k[i + 1]), lo = min(k[i], k[i + 1]);
-      const uint32_t ia = sw ? id[i + 1] : id[i], ib = sw ? id[i] : id[i + 1];
-      k[i] = hi; k[i + 1] = lo; id[i] = ia; id[i + 1] = ib;
-    }
-  }
+  for (int j = 0; j < kEpl; ++j)
+    c[j] = (static_cast<unsigned long long>(k[j]) << 3) | static_cast<unsigned>(7 - j);
+#define DES_CE(i, j)                              \
+  do {                                            \
+    const bool sw = c[i] < c[j];                  \
+    const unsigned long long hi = sw ? c[j] : c[i]; \
+    const unsigned long long lo = sw ? c[i] : c[j]; \
+    c[i] = hi;                                    \
+    c[j] = lo;                                    \
+  } while (0)
+  DES_CE(0, 1); DES_CE(2, 3); DES_CE(4, 5); DES_CE(6, 7);
+  DES_CE(0, 2); DES_CE(1, 3); DES_CE(4, 6); DES_CE(5, 7);
+  DES_CE(1, 2); DES_CE(5, 6); DES_CE(0, 4); DES_CE(3, 7);
+  DES_CE(1, 5); DES_CE(2, 6);
+  DES_CE(1, 4); DES_CE(3, 6);
+  DES_CE(2, 4); DES_CE(3, 5);
+  DES_CE(3, 4);
+#undef DES_CE
   idx = 0;
 #pragma unroll
-  for (int j = 0; j < kEpl; ++j) idx |= id[j] << (3 * j);
+  for (int j = 0; j < kEpl; ++j) {
+    k[j] = static_cast<uint32_t>(c[j] >> 3);
+    idx |= (7u - (static_cast<uint32_t>(c[j]) & 7u)) << (3 * j);
+  }
 }
 
 // LDS carve-up of the selection (bytes).  MP = padded expert count = 8 * LPT.
@@ -443,15 +454,18 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem, bool dr
       // rank[e] = #{j : key[j] beats key[e]}; the j range is split over the
       // threads that share an expert, partial counts meet in an integer LDS add
       constexpr int P = kRtThreads / MP;
+      constexpr int CH = MP / P;  // keys per thread: a compile-time count (padding keys are 0
+                                  // and never beat a candidate), so the reads batch up
       for (int t = threadIdx.x; t < MP * P; t += kRtThreads) {
         const int e = t % MP, part = t / MP;
         const uint32_t ke = s_key[e];
         if (ke == 0u) continue;
-        const int j0 = (M * part) / P, j1 = (M * (part + 1)) / P;
+        const int j0 = part * CH;
         int rank = 0;
-        for (int j = j0; j < j1; ++j) {
-          const uint32_t kj = s_key[j];
-          rank += (kj > ke || (kj == ke && j < e)) ? 1 : 0;
+#pragma unroll
+        for (int jj = 0; jj < CH; ++jj) {
+          const uint32_t kj = s_key[j0 + jj];
+          rank += (kj > ke || (kj == ke && j0 + jj < e)) ? 1 : 0;
         }
         if (rank) atomicAdd(&s_rank[e], rank);
       }
@@ -512,25 +526,30 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem, bool dr
     Head hd;
     head_set(hd, cmask, my_sorted);
     const size_t o = (static_cast<size_t>(b) * N + (live ? n : 0)) * K;
-    float mx = 0.f, den = 0.f, mye[NW];
+    uint32_t mkey[NW], m0 = 0u;  // keys drawn at iterations rl, rl + LPT, ...; the first key
 #pragma unroll
-    for (int q = 0; q < NW; ++q) mye[q] = 0.f;
+    for (int q = 0; q < NW; ++q) mkey[q] = 0u;
     for (int it = 0; it < keff; ++it) {  // S_n = TopK(I_n restricted to C, K), best first
       bool mine;
-      const uint32_t m = row_draw<LPT>(hd, mine);
-      // every lane of the row sees the drawn logit: gate numerators in draw order
-      const float v = key_to_f32(m);
-      if (it == 0) mx = v;
-      const float ex = m ? exp_neg(v - mx) : 0.f;
-      den += ex;  // fixed order it = 0, 1, ...
+      const uint32_t m = row_draw<LPT>(hd, mine);  // every lane of the row sees the drawn key
+      if (it == 0) m0 = m;
 #pragma unroll
       for (int q = 0; q < NW; ++q)
-        if (it == q * LPT + rl) mye[q] = ex;
+        if (it == q * LPT + rl) mkey[q] = m;
       if (mine) {
         if (live) a.topk_idx[o + it] = rl * kEpl + static_cast<int>((sidx >> (3 * hd.h)) & 7u);
         head_set(hd, hd.mask & (hd.mask - 1u), my_sorted);
       }
     }
+    // gate numerators of this lane's slots, then the row's sum in a fixed order
+    const float mx = key_to_f32(m0);
+    float mye[NW], part = 0.f;
+#pragma unroll
+    for (int q = 0; q < NW; ++q) {
+      mye[q] = mkey[q] ? exp_neg(key_to_f32(mkey[q]) - mx) : 0.f;
+      part += mye[q];
+    }
+    const float den = row_sum_f32<LPT>(part);
     DES_STAMP(a, 17);
     // g_n = softmax of the selected logits (Alg. 1 stage 2); unused slots -1 / 0
     if (live) {
