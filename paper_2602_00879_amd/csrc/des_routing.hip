@@ -74,14 +74,21 @@ struct RoutingArgs {
 };
 
 // ------------------------------------------------------------------ flags
-__device__ __forceinline__ void flag_publish(unsigned long long* f, unsigned long long epoch) {
-  // all threads of the workgroup have passed a barrier; one thread publishes
-  __threadfence();
-  __hip_atomic_store(f, epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+// Two hand-off styles.  `fenced`: the data was written with ordinary stores, so
+// a device-scope fence (an L2 write-back on this chip, ~1 us) precedes the flag
+// and the waiter ends with one too.  Unfenced: the data itself is written and
+// read with device-scope accesses (the logits), which reach the level all
+// compute units share on their own, so the flag only has to follow them.
+__device__ __forceinline__ void flag_publish(unsigned long long* f, unsigned long long epoch,
+                                             bool fenced) {
+  // all threads of the workgroup have passed a barrier (their stores have
+  // completed); one thread publishes
+  if (fenced) __threadfence();
+  __hip_atomic_store(f, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // Every thread polls a subset of the flags; returns false if a wait ran out.
 __device__ __forceinline__ bool flags_wait(const unsigned long long* f, int n,
-                                           unsigned long long epoch) {
+                                           unsigned long long epoch, bool fenced) {
   bool ok = true;
   for (int i = threadIdx.x; i < n; i += blockDim.x) {
     int it = 0;
@@ -92,7 +99,7 @@ __device__ __forceinline__ bool flags_wait(const unsigned long long* f, int n,
     }
   }
   const int all = __syncthreads_and(ok ? 1 : 0);
-  __threadfence();
+  if (fenced) __threadfence();
   return all != 0;
 }
 
@@ -132,10 +139,13 @@ __device__ __forceinline__ void router_tile_bf16(const RoutingArgs& a, int tile_
   if (threadIdx.x < 256) {
     const int er = threadIdx.x & 15, tc = threadIdx.x >> 4;
     float s = 0.f;
+    const float bias_e = (a.bias && i0 + er < M) ? a.bias[i0 + er] : 0.f;
 #pragma unroll
     for (int w = 0; w < kRtWaves; ++w) s += part[w * 256 + er * 16 + tc];  // fixed order
     const int e = i0 + er, t = t0 + tc;
-    if (e < M && t < T) a.logits[static_cast<size_t>(t) * M + e] = s + (a.bias ? a.bias[e] : 0.f);
+    if (e < M && t < T)  // device-scope store: the selector reads it without a fence
+      __hip_atomic_store(a.logits + static_cast<size_t>(t) * M + e, s + bias_e, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
@@ -160,7 +170,9 @@ __device__ __forceinline__ void router_tile_f32(const RoutingArgs& a, int tile_m
       s = fmaf(p4.w, q4.w, s);
     }
     s = wave_sum_f32(s);
-    if (lane == 0) a.logits[static_cast<size_t>(t) * M + e] = s + (a.bias ? a.bias[e] : 0.f);
+    if (lane == 0)
+      __hip_atomic_store(a.logits + static_cast<size_t>(t) * M + e, s + (a.bias ? a.bias[e] : 0.f),
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
@@ -336,7 +348,7 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem, bool dr
     for (int j = 0; j < kEpl; ++j) {
       const int idx = rl * kEpl + j;
       const bool ok = live && idx < M;
-      val[j] = ok ? rowp[idx] : 0.f;
+      val[j] = ok ? __hip_atomic_load(rowp + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
       key[j] = ok ? order_key(val[j]) : 0u;
       nvalid += ok ? 1u : 0u;
     }
@@ -674,7 +686,7 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
     if (blk == 0) DES_STAMP(a, 9);
     if (a.use_flags) {
       __syncthreads();
-      if (threadIdx.x == 0) flag_publish(a.flags + blk, a.epoch);
+      if (threadIdx.x == 0) flag_publish(a.flags + blk, a.epoch, false);
     }
     if (blk == 0) DES_STAMP(a, 10);
     return;
@@ -684,7 +696,7 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
   const int all_tiles = a.tiles_m * a.tiles_t;
   if (blk < n_sel) {  // ---- role S
     DES_STAMP(a, 0);
-    if (a.use_flags && a.do_router && !flags_wait(a.flags, all_tiles, a.epoch)) {
+    if (a.use_flags && a.do_router && !flags_wait(a.flags, all_tiles, a.epoch, false)) {
       if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
       return;
     }
@@ -707,13 +719,13 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
     }
     if (a.use_flags) {
       __syncthreads();
-      if (threadIdx.x == 0) flag_publish(a.flags + all_tiles + blk, a.epoch);
+      if (threadIdx.x == 0) flag_publish(a.flags + all_tiles + blk, a.epoch, true);
     }
     return;
   }
   blk -= n_sel;
   if (blk == 0 && a.do_permute && a.B > 1) {  // ---- role P
-    if (a.use_flags && a.do_select && !flags_wait(a.flags + all_tiles, a.B, a.epoch)) {
+    if (a.use_flags && a.do_select && !flags_wait(a.flags + all_tiles, a.B, a.epoch, true)) {
       if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
       return;
     }
