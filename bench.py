@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--replicas", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="also time the steps replayed from a HIP graph")
+    ap.add_argument("--selection-only", action="store_true",
+                    help="time coreset selection alone (one fused HIP launch) beside the same "
+                         "selection written with torch ops (Sec. 4.3 / Fig. 6 of the paper)")
     return ap.parse_args()
 
 
@@ -73,6 +76,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.selection_only:
+        return bench_selection(args, torch, B, W, dev)
     if args.workload == "stack48":
         return bench_stack(args, torch, B, W, dev)
     cfg = W.CONFIGS[args.workload]
@@ -193,6 +198,62 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, layer, args.mode, C)
     print(json.dumps(out))
+
+
+def bench_selection(args, torch, B, W, dev):
+    """DES-Vote coreset selection alone: des_select_coreset (one launch) against
+    the same selection composed from torch ops on the same GPU (softmax, top-k,
+    gather, scatter-add, top-k, sort) - the comparison of Sec. 4.3 / Fig. 6."""
+    cfg = W.CONFIGS["m128_zipf" if args.workload == "stack48" else args.workload]
+    N = args.n_tokens or cfg.n_tokens
+    M, K = cfg.n_experts, cfg.top_k
+    C = args.coreset or cfg.coreset
+    logits = torch.from_numpy(W.make_logits(N, M, cfg.seed, zipf_s=cfg.zipf_s)).to(dev).reshape(1, N, M)
+    shape = B.make_shape(1, N, 32, M, 32, K, C, "vote", "f32")
+
+    def torch_select(L):
+        P = torch.softmax(L, dim=-1)
+        idx = torch.topk(L, K, dim=-1).indices            # ranking on the logits
+        w = torch.gather(P, -1, idx)
+        V = torch.zeros(M, device=L.device, dtype=L.dtype).scatter_add_(0, idx.reshape(-1), w.reshape(-1))
+        nominated = torch.zeros(M, device=L.device, dtype=torch.bool).index_fill_(0, idx.reshape(-1), True)
+        score = torch.where(nominated, V, torch.full_like(V, -1.0))
+        core = torch.topk(score, min(C, M)).indices
+        return torch.sort(core).values
+
+    def timed(fn, iters):
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e6 / iters
+
+    iters = max(args.steps, 200)
+    outs = B.des_select_coreset(shape, logits)  # outputs allocated once, as a serving loop would
+    hip_us = timed(lambda: B.des_select_coreset(shape, logits, out=outs), iters)
+    torch_us = timed(lambda: torch_select(logits[0]), iters)
+    # same coreset (the torch version breaks exact ties arbitrarily; none occur here)
+    ours = B.des_select_coreset(shape, logits)
+    n = int(ours["coreset_size"][0])
+    same = ours["coreset_idx"][0, :n].tolist() == torch_select(logits[0]).tolist()[:n]
+    B.des_kernel_timing_enable(True)
+    for _ in range(50):
+        B.des_select_coreset(shape, logits)
+    torch.cuda.synchronize()
+    kt = B.des_kernel_timing_read()
+    B.des_kernel_timing_enable(False)
+    print(json.dumps({
+        "metric": "DES-Vote coreset selection us per block (host wall-clock per call)",
+        "value": hip_us, "unit": "us/block", "n_gpus": 1, "steps": iters, "higher_is_better": False,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"selection only: N={N} M={M} K={K} C={C} zipf_s={cfg.zipf_s}"},
+        "hip_launches": 1, "hip_kernel_us": kt["select"][0] * 1e3 / max(1, kt["select"][1]),
+        "torch_ops_us": torch_us, "speedup_vs_torch_ops": torch_us / hip_us,
+        "same_coreset": bool(same),
+    }))
 
 
 def bench_stack(args, torch, B, W, dev):

@@ -147,11 +147,13 @@ def des_route(shape: DesShape, x: torch.Tensor, w_router: torch.Tensor,
     return logits, probs
 
 
-def des_select_coreset(shape: DesShape, logits: torch.Tensor) -> Dict[str, torch.Tensor]:
+def des_select_coreset(shape: DesShape, logits: torch.Tensor,
+                       out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    """`out`: the dict of a previous call, to reuse its output tensors."""
     B, M = shape.n_seqs, shape.n_experts
     cap = des_coreset_capacity(shape)
     dev = logits.device
-    out = dict(
+    out = out if out is not None else dict(
         coreset_idx=torch.empty((B, cap), dtype=torch.int32, device=dev),
         coreset_size=torch.empty((B,), dtype=torch.int32, device=dev),
         votes=torch.zeros((B, M), dtype=torch.float32, device=dev),

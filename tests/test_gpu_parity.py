@@ -252,3 +252,38 @@ def test_m128_block_size_sweep():
             _say(f"  {r}")
     assert all(uniq[(N, "vote")] <= 32 for N in (4, 8, 16, 32, 64, 128))
     assert uniq[(128, "vanilla")] > uniq[(32, "vanilla")] > uniq[(4, "vanilla")]
+
+
+def test_graph_replay_matches_eager():
+    """A captured des_moe_forward (kernels only, no memset nodes) replayed several
+    times with new inputs, eager calls and synchronisations in between, must equal
+    the eager result every time (the routing flags are cleared by their consumer,
+    so a replay with the captured epoch cannot be satisfied by stale flags)."""
+    cfg = MID["mid_bf16"]
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    shape = H.shape_of(cfg, "vote")
+    x_static = dev["x"].clone()
+    bufs = B.MoeBuffers(shape, "cuda", torch.bfloat16)
+    args = (shape, x_static, dev["w_router"], dev["bias"], dev["w_gate"], dev["w_up"], dev["w_down"])
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        B.des_moe_forward(*args, shared=dev["shared"], buffers=bufs)  # warm-up outside capture
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            B.des_moe_forward(*args, shared=dev["shared"], buffers=bufs)
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    for rep in range(4):
+        x_new = torch.randn(x_static.shape, generator=gen, device="cuda").to(torch.bfloat16)
+        eager = B.des_moe_forward(shape, x_new, dev["w_router"], dev["bias"], dev["w_gate"], dev["w_up"],
+                                  dev["w_down"], shared=dev["shared"])
+        torch.cuda.synchronize()
+        x_static.copy_(x_new)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(bufs.y, eager.y), f"replay {rep}: y differs"
+        assert torch.equal(bufs.topk_idx, eager.topk_idx), f"replay {rep}: routing differs"
+        assert torch.equal(bufs.expert_counts, eager.expert_counts)
+        assert int(bufs.n_unique[0]) == int(eager.n_unique[0]) >= 1
