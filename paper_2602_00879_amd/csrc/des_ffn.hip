@@ -310,51 +310,49 @@ constexpr int kGuTiles = 2;   // gate/up row tiles per task (F % 32 == 0, so F/1
 // 36.2 us for four and 34.5 us for one).
 // One gate/up task (see the kernel comment): returns false if the slot is unused.
 // `fused`: publish the task's readiness flag when its H rows are stored.
-template <int MAXNT, bool PACKED, bool FUSED, int U1 = 2, int U2 = 2>
+template <int MAXNT, bool PACKED, bool FUSED, int U1 = 2, int U2 = 2, int GT = kGuTiles>
 __device__ __forceinline__ bool gateup_task(const FfnArgs& a, int task, int lane) {
-  const int tiles_r = a.F / (16 * kGuTiles);
+  const int tiles_r = a.F / (16 * GT);
   const int routed = a.n_slots * tiles_r;
   Task t;
   int ft;
   FfnArgs v = a;
   if (task < routed) {
     if (!make_task(a, task / tiles_r, false, false, t, lane)) return false;
-    ft = (task % tiles_r) * kGuTiles;
+    ft = (task % tiles_r) * GT;
   } else {
     make_task(a, 0, true, false, t, lane);
     v = shared_view(a, t, 2);
-    ft = (task - routed) * kGuTiles;
+    ft = (task - routed) * GT;
   }
   const int nt = (t.count + 15) / 16;
   bool done = false;
   if (MAXNT == 1 || nt <= 1) {
-    gateup_group<kGuTiles, 1, U1, PACKED, FUSED>(v, t, ft, 0, lane);
+    gateup_group<GT, 1, U1, PACKED, FUSED>(v, t, ft, 0, lane);
     done = true;
   }
   if constexpr (MAXNT >= 2) {
     if (!done && (MAXNT == 2 || nt <= 2)) {
-      gateup_group<kGuTiles, 2, U2, PACKED, FUSED>(v, t, ft, 0, lane);
+      gateup_group<GT, 2, U2, PACKED, FUSED>(v, t, ft, 0, lane);
       done = true;
     }
   }
   if constexpr (MAXNT >= 4) {
     if (!done && (MAXNT == 4 || nt <= 4)) {
-      gateup_group<kGuTiles, 4, 2, PACKED, FUSED>(v, t, ft, 0, lane);
+      gateup_group<GT, 4, 2, PACKED, FUSED>(v, t, ft, 0, lane);
       done = true;
     }
   }
   if constexpr (MAXNT >= 8) {
     if (!done && (MAXNT == 8 || nt <= 8)) {
-      gateup_group<kGuTiles, 8, 1, PACKED, FUSED>(v, t, ft, 0, lane);
+      gateup_group<GT, 8, 1, PACKED, FUSED>(v, t, ft, 0, lane);
       done = true;
     }
   }
   if constexpr (MAXNT >= 16) {
     if (!done)
-      for (int g0 = 0; g0 < t.count; g0 += 256) {
-        gateup_group<1, 16, 1, PACKED, FUSED>(v, t, ft, g0, lane);
-        gateup_group<1, 16, 1, PACKED, FUSED>(v, t, ft + 1, g0, lane);
-      }
+      for (int g0 = 0; g0 < t.count; g0 += 256)
+        for (int f = 0; f < GT; ++f) gateup_group<1, 16, 1, PACKED, FUSED>(v, t, ft + f, g0, lane);
   }
   if (FUSED) publish_flag(a.h_ready + task, a.epoch, lane);
   return true;
@@ -365,12 +363,14 @@ __device__ __forceinline__ bool gateup_task(const FfnArgs& a, int task, int lane
 // the k-steps per prefetch stage of the one- and two-token-tile paths; two
 // stages of two k-steps measured best on the 128-expert layer (34.3 us against
 // 36.2 us for four and 34.5 us for one).
-template <int MAXNT, bool PACKED, int U1 = 2, int U2 = 2>
+// GT = row tiles per task: 2 normally, 1 when the launch would otherwise have
+// too few wavefronts to keep enough bytes in flight (small coresets).
+template <int MAXNT, bool PACKED, int U1 = 2, int U2 = 2, int GT = kGuTiles>
 __global__ __launch_bounds__(kFfnWaves* kWave) void gateup_bf16_kernel(FfnArgs a) {
   const int lane = threadIdx.x & 63;
   const int task = blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
-  const int tasks = a.n_slots * (a.F / (16 * kGuTiles)) + a.Fs / (16 * kGuTiles);
-  if (task < tasks) gateup_task<MAXNT, PACKED, false, U1, U2>(a, task, lane);
+  const int tasks = a.n_slots * (a.F / (16 * GT)) + a.Fs / (16 * GT);
+  if (task < tasks) gateup_task<MAXNT, PACKED, false, U1, U2, GT>(a, task, lane);
 }
 
 // down for pairs [g0, g0+16*NT), output rows (dt0 .. dt0+RT-1)*16
@@ -466,10 +466,10 @@ __device__ __forceinline__ void down_group(const FfnArgs& a, const Task& t, int 
 }
 
 // One down task: 64 output rows of one expert for all of its pairs.
-template <int MAXNT, bool PACKED, bool FUSED, int U1 = 2, int U2 = 2>
+template <int MAXNT, bool PACKED, bool FUSED, int U1 = 2, int U2 = 2, int RTG = 4>
 __device__ __forceinline__ bool down_task(const FfnArgs& a, int task, int lane) {
   const int dtiles = a.D / 16;
-  const int groups = (dtiles + 3) / 4;  // 64 output rows per task
+  const int groups = (dtiles + RTG - 1) / RTG;  // 16 * RTG output rows per task
   const int routed = a.n_slots * groups;
   const int tiles_r = a.F / (16 * kGuTiles);
   Task t;
@@ -491,31 +491,31 @@ __device__ __forceinline__ bool down_task(const FfnArgs& a, int task, int lane) 
       hw.n = a.Fs / (16 * kGuTiles);
     }
   }
-  const int dt_begin = dg * 4;
-  const int dt_end = min(dt_begin + 4, dtiles);
+  const int dt_begin = dg * RTG;
+  const int dt_end = min(dt_begin + RTG, dtiles);
   const int nt = (t.count + 15) / 16;
   bool done = false;
-  if (dt_end - dt_begin == 4) {
+  if (dt_end - dt_begin == RTG) {
     if (MAXNT == 1 || nt <= 1) {
-      down_group<4, 1, U1, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
+      down_group<RTG, 1, U1, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
       done = true;
     }
     if constexpr (MAXNT >= 2) {
       if (!done && (MAXNT == 2 || nt <= 2)) {
-        down_group<4, 2, U2, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
+        down_group<RTG, 2, U2, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
         done = true;
       }
     }
     if constexpr (MAXNT >= 4) {
       if (!done && (MAXNT == 4 || nt <= 4)) {
-        down_group<4, 4, 1, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
+        down_group<RTG, 4, 1, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
         done = true;
       }
     }
     if constexpr (MAXNT >= 8) {
       if (!done && (MAXNT == 8 || nt <= 8)) {
-        down_group<2, 8, 1, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
-        down_group<2, 8, 1, PACKED, FUSED>(v, t, dt_begin + 2, 0, lane, &hw);
+        for (int r2 = 0; r2 < RTG; r2 += 2)
+          down_group<2, 8, 1, PACKED, FUSED>(v, t, dt_begin + r2, 0, lane, &hw);
         done = true;
       }
     }
@@ -540,13 +540,13 @@ __device__ __forceinline__ bool down_task(const FfnArgs& a, int task, int lane) 
   return true;
 }
 
-template <int MAXNT, bool PACKED, int U1 = 2, int U2 = 2>
+template <int MAXNT, bool PACKED, int U1 = 2, int U2 = 2, int RTG = 4>
 __global__ __launch_bounds__(kFfnWaves* kWave) void down_bf16_kernel(FfnArgs a) {
   const int lane = threadIdx.x & 63;
   const int task = blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
-  const int groups = (a.D / 16 + 3) / 4;
+  const int groups = (a.D / 16 + RTG - 1) / RTG;
   const int tasks = a.n_slots * groups + (a.Fs > 0 ? groups : 0);
-  if (task < tasks) down_task<MAXNT, PACKED, false, U1, U2>(a, task, lane);
+  if (task < tasks) down_task<MAXNT, PACKED, false, U1, U2, RTG>(a, task, lane);
 }
 
 // ------------------------------------------ larger blocks: activations via LDS
@@ -1097,11 +1097,23 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
       return fe == hipSuccess ? DES_OK : hip_fail(fe, "ffn launch");                        \
     }                                                                                       \
   } while (0)
+    // Few experts (small coreset): halve the task size so that about a thousand
+    // wavefronts keep enough bytes in flight (a task then prefetches twice as deep).
+    const bool gu_fine = gu_tasks < 1024, dn_fine = dn_tasks < 1024;
+    const int gu_fine_tasks = a.n_slots * (a.F / 16) + a.Fs / 16;
+    const int dn_fine_groups = (a.D / 16 + 1) / 2;
+    const int dn_fine_tasks = a.n_slots * dn_fine_groups + (a.Fs > 0 ? dn_fine_groups : 0);
 #define DES_LAUNCH_FFN(NTV, PK)                                                             \
   do {                                                                                      \
     if (fused_requested) DES_TRY_FUSED(NTV, PK);                                            \
-    launch(kKGateUp, gateup_bf16_kernel<NTV, PK>, dim3(gu_blocks), blk, 0, st, a);          \
-    launch(kKDown, down_bf16_kernel<NTV, PK>, dim3(dn_blocks), blk, 0, st, a);              \
+    if (gu_fine && NTV <= 2)                                                                \
+      launch(kKGateUp, gateup_bf16_kernel<NTV, PK, 4, 4, 1>, dim3(gu_fine_tasks), blk, 0, st, a); \
+    else                                                                                    \
+      launch(kKGateUp, gateup_bf16_kernel<NTV, PK>, dim3(gu_blocks), blk, 0, st, a);        \
+    if (dn_fine && NTV <= 2)                                                                \
+      launch(kKDown, down_bf16_kernel<NTV, PK, 4, 4, 2>, dim3(dn_fine_tasks), blk, 0, st, a); \
+    else                                                                                    \
+      launch(kKDown, down_bf16_kernel<NTV, PK>, dim3(dn_blocks), blk, 0, st, a);            \
   } while (0)
 #define DES_LAUNCH_BY_NT(PK)                                                                \
   do {                                                                                      \
