@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--replicas", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="also time the steps replayed from a HIP graph")
+    ap.add_argument("--sweep", action="store_true",
+                    help="block-length sweep N = 4..128, vanilla against DES-Vote C=32, and the "
+                         "affine latency law of Eq. 2/3 fitted over the coreset size at N=32")
     ap.add_argument("--selection-only", action="store_true",
                     help="time coreset selection alone (one fused HIP launch) beside the same "
                          "selection written with torch ops (Sec. 4.3 / Fig. 6 of the paper)")
@@ -78,6 +81,8 @@ def main():
 
     if args.selection_only:
         return bench_selection(args, torch, B, W, dev)
+    if args.sweep:
+        return bench_sweep(args, torch, B, W, dev)
     if args.workload == "stack48":
         return bench_stack(args, torch, B, W, dev)
     cfg = W.CONFIGS[args.workload]
@@ -137,6 +142,35 @@ def main():
     B.des_kernel_timing_enable(False)
     kernels_us = {k: (v[0] * 1e3 / v[1]) for k, v in kt.items() if v[1] > 0}
 
+    # distribution of the step time: one event before every step (the launch
+    # queue stays backed up, so consecutive events are one step apart)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    for i in range(args.steps):
+        evs[i].record()
+        step(i)
+    evs[args.steps].record()
+    torch.cuda.synchronize()
+    per_step = np.sort(np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(args.steps)]))
+    step_us = {"median": float(np.median(per_step)), "p10": float(per_step[int(0.1 * (len(per_step) - 1))]),
+               "p90": float(per_step[int(0.9 * (len(per_step) - 1))])}
+
+    # the machine's practical ceiling: a bare streaming read of as many bytes as
+    # the gate/up kernel must fetch, rotating over the same replicas
+    el = 2 if cfg.dtype == "bf16" else 4
+    gateup_bytes = n_unique * 2 * cfg.hidden * cfg.ffn * el + 2 * cfg.hidden * cfg.ffn_shared * el
+    probe_bytes = min(gateup_bytes, base[0].numel() * base[0].element_size()) // 65536 * 65536
+    ceiling = None
+    if probe_bytes > 0:
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        B.des_kernel_timing_enable(True)
+        for i in range(60):
+            B.des_hbm_read_probe(replicas[i % len(replicas)][0], probe_bytes, sink)
+        torch.cuda.synchronize()
+        pr = B.des_kernel_timing_read()["read_probe"]
+        B.des_kernel_timing_enable(False)
+        pus = pr[0] * 1e3 / pr[1]
+        ceiling = {"bytes": probe_bytes, "us": pus, "GB/s": probe_bytes / (pus * 1e-6) / 1e9}
+
     graph_us = None
     if args.graph:
         g = torch.cuda.CUDAGraph()
@@ -159,10 +193,8 @@ def main():
         torch.cuda.synchronize()
         graph_us = (time.perf_counter() - tg0) * 1e6 / (reps * n_rep)
 
-    el = 2 if cfg.dtype == "bf16" else 4
     per_expert = 3 * cfg.hidden * cfg.ffn * el
     unique_bytes = n_unique * per_expert + (3 * cfg.hidden * cfg.ffn_shared * el)
-    gateup_bytes = n_unique * 2 * cfg.hidden * cfg.ffn * el + 2 * cfg.hidden * cfg.ffn_shared * el
     dom_us = kernels_us.get("gateup")
     achieved = gateup_bytes / (dom_us * 1e-6) / 1e9 if dom_us else None
     roofline = {
@@ -170,6 +202,8 @@ def main():
         "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
         "traffic": MEASURED_TRAFFIC.get((args.workload, args.mode, args.layout)),
         "algorithmic_bytes_per_launch": gateup_bytes, "avg_launch_us": dom_us,
+        "read_ceiling": ceiling,
+        "frac_of_read_ceiling": (achieved / ceiling["GB/s"]) if (achieved and ceiling) else None,
     }
     ffn_us = sum(kernels_us.get(k, 0.0) for k in ("gateup", "down"))
     expert_gbs_step = unique_bytes / (ms_per_step * 1e-3) / 1e9
@@ -190,6 +224,7 @@ def main():
         "expert_weight_GBps_ffn_kernels": expert_gbs_ffn,
         "pct_of_hbm_peak_whole_step": 100.0 * expert_gbs_step / HBM_PEAK_GBS,
         "pct_of_hbm_peak_ffn_kernels": (100.0 * expert_gbs_ffn / HBM_PEAK_GBS) if expert_gbs_ffn else None,
+        "step_us": step_us,
         "kernel_us": kernels_us,
         "graph_replay_us_per_block": graph_us,
         "roofline": roofline,
@@ -253,6 +288,90 @@ def bench_selection(args, torch, B, W, dev):
         "hip_launches": 1, "hip_kernel_us": kt["select"][0] * 1e3 / max(1, kt["select"][1]),
         "torch_ops_us": torch_us, "speedup_vs_torch_ops": torch_us / hip_us,
         "same_coreset": bool(same),
+    }))
+
+
+def bench_sweep(args, torch, B, W, dev):
+    """Block-length sweep on the 128-expert layer: vanilla routing against
+    DES-Vote with a coreset of 32 for N = 4..128 (Fig. 1 / Fig. 7 of the paper:
+    latency follows the number of unique experts, not N), then the latency law
+    of Eq. 2/3 at fixed N*K: us per block against unique experts as the coreset
+    size varies, fitted by least squares to t = t0 + b*U."""
+    cfg = W.CONFIGS["m128_sweep"]
+    layer = W.make_layer(cfg.with_(n_tokens=128))
+
+    def dev_t(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    packed = args.layout == "packed"
+    layout = B.DES_LAYOUT_PACKED if packed else B.DES_LAYOUT_ROWMAJOR
+    x_all = dev_t(layer["x"])
+    w_router, bias = dev_t(layer["w_router"]), dev_t(layer["bias"])
+    base = []
+    for k in ("w_gate", "w_up", "w_down"):
+        t = dev_t(layer[k])
+        base.append(B.des_pack_expert_weights(t) if packed else t)
+    torch.cuda.synchronize()
+    replicas = [base] + [[t.clone() for t in base] for _ in range(max(1, args.replicas) - 1)]
+    per_expert = 3 * cfg.hidden * cfg.ffn * 2
+    steps, warm = min(args.steps, 100), min(args.warmup, 10)
+
+    def run(mode, N, C):
+        shape = B.make_shape(1, N, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k, C, mode, cfg.dtype,
+                             weight_layout=layout)
+        x = x_all[:, :N].contiguous()
+        bufs = B.MoeBuffers(shape, dev, x.dtype)
+
+        def step(i):
+            wg, wu, wd = replicas[i % len(replicas)]
+            B.des_moe_forward(shape, x, w_router, bias, wg, wu, wd, buffers=bufs)
+
+        for i in range(warm):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / steps
+        B.des_kernel_timing_enable(True)
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        kt = B.des_kernel_timing_read()
+        B.des_kernel_timing_enable(False)
+        ku = {k: round(v[0] * 1e3 / v[1], 2) for k, v in kt.items() if v[1] > 0}
+        U = int(bufs.n_unique.cpu()[0])
+        return {"mode": mode, "N": N, "C": C, "n_unique": U, "us": round(us, 2),
+                "expert_GBps_whole_step": round(U * per_expert / us / 1e3, 1),
+                "expert_GBps_ffn_kernels": round(U * per_expert / (ku.get("gateup", 0) + ku.get("down", 0)) / 1e3, 1),
+                "kernel_us": ku}
+
+    rows = []
+    for N in (4, 8, 16, 32, 64, 128):
+        for mode in ("vanilla", "vote"):
+            rows.append(run(mode, N, cfg.coreset))
+            print("# " + json.dumps(rows[-1]), file=sys.stderr, flush=True)
+    law = [run("vote", 32, C) for C in (8, 16, 24, 32, 48, 64, 96, 128)]
+    U = np.array([r["n_unique"] for r in law], dtype=np.float64)
+    t = np.array([r["us"] for r in law], dtype=np.float64)
+    A = np.stack([np.ones_like(U), U], axis=1)
+    (t0_fit, b_fit), *_ = np.linalg.lstsq(A, t, rcond=None)
+    resid = t - A @ np.array([t0_fit, b_fit])
+    r2 = 1.0 - float(resid @ resid) / float(((t - t.mean()) ** 2).sum())
+    print(json.dumps({
+        "metric": "MoE-layer us per block over block length N, vanilla vs DES-Vote C=32",
+        "unit": "us/block", "n_gpus": 1, "steps": steps, "warmup": warm, "higher_is_better": False,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"m128_sweep: M={cfg.n_experts} D={cfg.hidden} F={cfg.ffn} K={cfg.top_k} "
+                               f"zipf_s={cfg.zipf_s} N in 4..128", "weight_layout": args.layout,
+                   "weight_replicas": len(replicas)},
+        "sweep": rows,
+        "latency_law": {"fixed": "N=32, K=8 (N*K = 256 routed pairs)", "points": [[r["C"], r["n_unique"], r["us"]] for r in law],
+                        "t0_us": float(t0_fit), "b_us_per_expert": float(b_fit), "r2": r2,
+                        "implied_GBps_per_expert_slope": per_expert / float(b_fit) / 1e3},
     }))
 
 

@@ -188,13 +188,26 @@ int des_pack_expert_weights(const void* src, void* dst, int64_t n_mats, int32_t 
                             int32_t cols, void* hip_stream);
 
 /*
+ * Measurement aid, not part of the hot path: one launch that reads `bytes`
+ * bytes at `src` from HBM once (each wavefront streams one contiguous 64 KB
+ * chunk) and computes nothing.  Its duration is the practical ceiling of a
+ * weight scan of that size on this machine, against which the expert FFN of
+ * Alg. 1 (whose cost is the fetch of the selected experts' weights, Eq. 2) is
+ * quoted.  `bytes` must be a positive multiple of 65536, `src` and `sink`
+ * 16-byte aligned; `sink` is 16 bytes of device memory that are never written
+ * for real data.
+ */
+int des_hbm_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream);
+
+/*
  * Measurement aid, off by default and not part of the hot path: while enabled,
  * every kernel launch of this library carries a pair of HIP events that take
  * the dispatch's own begin and end timestamps (the events are created on the
  * host at launch time, so do not enable it under graph capture).  des_kernel_timing_read() waits for the
  * recorded events and returns the accumulated duration and launch count of one
  * kernel id in [0, des_kernel_timing_count()); des_kernel_timing_name() names
- * it (router, softmax, select, permute, gateup, down, combine, pack).
+ * it (router, softmax, select, permute, gateup, down, combine, pack, routing,
+ * ffn, read_probe).
  * des_kernel_timing_enable() also clears the accumulators.  Not thread-safe.
  */
 int des_kernel_timing_enable(int enable);

@@ -25,7 +25,7 @@ EXPORTS = (
     "des_moe_forward", "des_stack_workspace_bytes", "des_moe_stack_forward",
     "des_pack_expert_weights", "des_strerror", "des_last_hip_error",
     "des_kernel_timing_enable", "des_kernel_timing_count", "des_kernel_timing_name",
-    "des_kernel_timing_read",
+    "des_kernel_timing_read", "des_hbm_read_probe",
 )
 
 
@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
         L.des_moe_stack_forward.argtypes = [sp, i32] + [vp] * 13 + [sz, vp]
         L.des_pack_expert_weights.restype = ctypes.c_int
         L.des_pack_expert_weights.argtypes = [vp, vp, ctypes.c_int64, i32, i32, vp]
+        L.des_hbm_read_probe.restype = ctypes.c_int
+        L.des_hbm_read_probe.argtypes = [vp, sz, vp, vp]
         L.des_strerror.restype = ctypes.c_char_p
         L.des_strerror.argtypes = [ctypes.c_int]
         L.des_last_hip_error.restype = ctypes.c_char_p
@@ -230,6 +232,13 @@ def des_pack_expert_weights(src: torch.Tensor) -> torch.Tensor:
     dst = torch.empty_like(src)
     _check(lib().des_pack_expert_weights(_ptr(src), _ptr(dst), n_mats, rows, cols, _stream()))
     return dst
+
+
+def des_hbm_read_probe(src: torch.Tensor, n_bytes: int, sink: torch.Tensor) -> None:
+    """One bare streaming read of the first n_bytes of src (a multiple of 64 KiB)."""
+    if n_bytes > src.numel() * src.element_size() or sink.numel() * sink.element_size() < 16:
+        raise ValueError("read probe: n_bytes exceeds src, or sink smaller than 16 bytes")
+    _check(lib().des_hbm_read_probe(_ptr(src), n_bytes, _ptr(sink), _stream()))
 
 
 def des_kernel_timing_enable(enable: bool) -> None:

@@ -243,6 +243,13 @@ int des_pack_expert_weights(const void* src, void* dst, int64_t n_mats, int32_t 
   return launch_pack(src, dst, n_mats, rows, cols, static_cast<hipStream_t>(hip_stream));
 }
 
+int des_hbm_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream) {
+  if (!src || !sink) return DES_ERR_NULL;
+  if (bytes < 65536 || bytes % 65536 || bytes / 65536 > 0x7FFFFFFFull) return DES_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(sink)) & 15) return DES_ERR_SHAPE;
+  return launch_read_probe(src, bytes, sink, static_cast<hipStream_t>(hip_stream));
+}
+
 const char* des_strerror(int code) {
   switch (code) {
     case DES_OK: return "ok";
@@ -269,7 +276,7 @@ int des_kernel_timing_count(void) { return kKCount; }
 
 const char* des_kernel_timing_name(int kernel_id) {
   static const char* names[kKCount] = {"router", "softmax", "select", "permute", "gateup",
-                                       "down", "combine", "pack", "routing", "ffn"};
+                                       "down", "combine", "pack", "routing", "ffn", "read_probe"};
   return (kernel_id >= 0 && kernel_id < kKCount) ? names[kernel_id] : "";
 }
 

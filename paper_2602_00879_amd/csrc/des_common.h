@@ -163,12 +163,13 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
                const int32_t* topk_idx, const float* topk_w, int32_t* n_unique, void* y, char* ws,
                unsigned long long epoch, hipStream_t st);
 int launch_pack(const void* src, void* dst, int64_t n_mats, int rows, int cols, hipStream_t st);
+int launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st);
 
 int hip_fail(hipError_t e, const char* what);  // records text, returns DES_ERR_HIP
 
 // Kernel ids for the optional per-kernel event timing (des_kernel_timing_*).
 enum KernelId { kKRouter = 0, kKSoftmax, kKSelect, kKPermute, kKGateUp, kKDown, kKCombine, kKPack,
-                kKRouting, kKFfn, kKCount };
+                kKRouting, kKFfn, kKProbe, kKCount };
 extern bool g_timing_on;
 // Creates the event pair of one timed launch and remembers it under kernel_id.
 bool timing_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop);

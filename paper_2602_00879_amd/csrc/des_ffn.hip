@@ -1038,6 +1038,37 @@ int launch_pack(const void* src, void* dst, int64_t n_mats, int rows, int cols, 
   return e == hipSuccess ? DES_OK : hip_fail(e, "pack launch");
 }
 
+// ------------------------------------------------------------- read ceiling
+// Bare streaming read: every wavefront pulls one contiguous 64 KB chunk with
+// sixteen 16-byte loads per lane in flight and does nothing else.  What this
+// reaches is the machine's practical ceiling for a weight scan, the figure
+// the FFN kernels are quoted against beside the 8 TB/s data-sheet peak.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kProbeChunk = 65536;
+
+__global__ __launch_bounds__(kWave) void read_probe_kernel(const u32x4* __restrict__ src,
+                                                           u32x4* __restrict__ sink) {
+  constexpr int kVecs = kProbeChunk / 16, kU = 16;
+  const u32x4* p = src + static_cast<size_t>(blockIdx.x) * kVecs + threadIdx.x;
+  u32x4 acc = {0, 0, 0, 0};
+  for (int i = 0; i < kVecs; i += kWave * kU) {
+    u32x4 v[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) v[u] = __builtin_nontemporal_load(p + i + u * kWave);
+#pragma unroll
+    for (int u = 0; u < kU; ++u) acc ^= v[u];
+  }
+  // keeps the loads alive; the pattern does not occur in real data
+  if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u && acc.z == 0x0fedcba9u) sink[0] = acc;
+}
+
+int launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st) {
+  launch(kKProbe, read_probe_kernel, dim3(static_cast<unsigned>(bytes / kProbeChunk)), dim3(kWave), 0,
+         st, static_cast<const u32x4*>(src), static_cast<u32x4*>(sink));
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? DES_OK : hip_fail(e, "read probe launch");
+}
+
 // ------------------------------------------------------------------ launcher
 int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const void* w_up,
                const void* w_down, const void* ws_gate, const void* ws_up, const void* ws_down,
@@ -1097,9 +1128,12 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
       return fe == hipSuccess ? DES_OK : hip_fail(fe, "ffn launch");                        \
     }                                                                                       \
   } while (0)
-    // Few experts (small coreset): halve the task size so that about a thousand
-    // wavefronts keep enough bytes in flight (a task then prefetches twice as deep).
-    const bool gu_fine = gu_tasks < 1024, dn_fine = dn_tasks < 1024;
+    // Few experts (small coreset): halve the task size so that enough wavefronts
+    // keep bytes in flight.  Measured: gate/up gains below ~512 tasks (18.4 vs
+    // 20.5 us at 272) and loses above (36.4 vs 34.4 us at 768); the down projection
+    // gains up to 1024 tasks while a halved task still streams >= 48 KB (F >= 768).
+    const bool gu_fine = gu_tasks < 512;
+    const bool dn_fine = dn_tasks <= 1024 && a.F >= 768;
     const int gu_fine_tasks = a.n_slots * (a.F / 16) + a.Fs / 16;
     const int dn_fine_groups = (a.D / 16 + 1) / 2;
     const int dn_fine_tasks = a.n_slots * dn_fine_groups + (a.Fs > 0 ? dn_fine_groups : 0);
