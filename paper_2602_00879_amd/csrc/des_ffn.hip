@@ -552,88 +552,230 @@ __global__ __launch_bounds__(kFfnWaves* kWave) void down_bf16_kernel(FfnArgs a) 
 // ------------------------------------------ larger blocks: activations via LDS
 // With more than two token tiles per expert the direct scheme above runs out
 // of registers for its prefetch (every token fragment is double-buffered in
-// registers) and re-reads the activations once per wavefront.  For T > 32 the
-// expert's activation rows are staged through LDS instead: a workgroup of four
-// wavefronts works on one expert, each wavefront streams its own weight rows
-// from HBM straight into MFMA operands as before, and all four read the token
-// fragments of the current 128-wide reduction chunk from LDS, which the
-// workgroup fills cooperatively one chunk ahead.  The weights are still read
-// once; the activations are read from L2 once per workgroup, not per wavefront.
-constexpr int kLW = 4;              // wavefronts per workgroup
+// registers).  For T > 32 the expert's activation rows go through LDS instead:
+//   * a workgroup of LW wavefronts works on LW weight-row groups of one expert;
+//     each wavefront streams its own two weight tiles from HBM straight into
+//     MFMA operands, three chunks of 128 reduction elements deep, so that two
+//     chunks (16 KB per wavefront) stay in flight across every barrier;
+//   * the expert's token rows of the next chunk are gathered from L2 into LDS
+//     by direct global-to-LDS loads (no staging registers), double-buffered;
+//   * LDS rows are 256 B with the 16-byte pieces of row r stored at piece
+//     index p ^ (r & 15): a direct load writes lane l at base + 16*l, so the
+//     swizzle is applied on the global side (which piece a lane fetches), and
+//     the 16 token rows an MFMA operand reads fall into 16 different banks.
+// The compiler cannot tell which LDS reads depend on which direct load and
+// would wait for all of them before every read; the token fragments are
+// therefore read with inline ds_read_b128 (each group followed by its own
+// lgkmcnt wait) and the direct loads are waited for by explicit vmcnt counts.
+// None of these asm statements claims to touch memory (a "memory" clobber makes
+// the compiler wait for every pending direct load first); they are volatile,
+// which keeps them in program order with each other, the barriers and the
+// direct loads.
 constexpr int kKC = 128;            // reduction elements per LDS chunk (4 k-steps)
-constexpr int kLRow = kKC + 8;      // padded LDS row: 272 B, spreads rows over banks
-constexpr int kLRows = 128;         // token rows per workgroup pass (8 token tiles)
-constexpr int kLPieces = kLRows / 16;  // 16-byte pieces a thread moves per chunk
-struct LdsGemm {
-  uint16_t buf[2][kLRows * kLRow];
-  const uint16_t* rowptr[kLRows];   // global row of each token row of this pass
-};
+#define DES_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N));
+}
+
+// b[i] = 16 bytes at LDS address addr + BASE + i*4096 (token tile i of a buffer).
+template <int NT, int BASE>
+__device__ __forceinline__ void lds_frags(bf16x8 (&b)[NT], uint32_t addr) {
+  static_assert(NT == 1 || NT == 2 || NT == 4 || NT == 6 || NT == 8, "token tiles per pass");
+  if constexpr (NT == 1) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(b[0])
+                 : "v"(addr), "n"(BASE + 0 * 4096)
+                 :);
+  }
+  if constexpr (NT == 2) {
+    asm volatile("ds_read_b128 %0, %2 offset:%3\n\t"
+                 "ds_read_b128 %1, %2 offset:%4\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(b[0]), "=&v"(b[1])
+                 : "v"(addr), "n"(BASE + 0 * 4096), "n"(BASE + 1 * 4096)
+                 :);
+  }
+  if constexpr (NT == 4) {
+    asm volatile("ds_read_b128 %0, %4 offset:%5\n\t"
+                 "ds_read_b128 %1, %4 offset:%6\n\t"
+                 "ds_read_b128 %2, %4 offset:%7\n\t"
+                 "ds_read_b128 %3, %4 offset:%8\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2]), "=&v"(b[3])
+                 : "v"(addr), "n"(BASE + 0 * 4096), "n"(BASE + 1 * 4096), "n"(BASE + 2 * 4096), "n"(BASE + 3 * 4096)
+                 :);
+  }
+  if constexpr (NT == 6) {
+    asm volatile("ds_read_b128 %0, %6 offset:%7\n\t"
+                 "ds_read_b128 %1, %6 offset:%8\n\t"
+                 "ds_read_b128 %2, %6 offset:%9\n\t"
+                 "ds_read_b128 %3, %6 offset:%10\n\t"
+                 "ds_read_b128 %4, %6 offset:%11\n\t"
+                 "ds_read_b128 %5, %6 offset:%12\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2]), "=&v"(b[3]), "=&v"(b[4]), "=&v"(b[5])
+                 : "v"(addr), "n"(BASE + 0 * 4096), "n"(BASE + 1 * 4096), "n"(BASE + 2 * 4096), "n"(BASE + 3 * 4096), "n"(BASE + 4 * 4096), "n"(BASE + 5 * 4096)
+                 :);
+  }
+  if constexpr (NT == 8) {
+    asm volatile("ds_read_b128 %0, %8 offset:%9\n\t"
+                 "ds_read_b128 %1, %8 offset:%10\n\t"
+                 "ds_read_b128 %2, %8 offset:%11\n\t"
+                 "ds_read_b128 %3, %8 offset:%12\n\t"
+                 "ds_read_b128 %4, %8 offset:%13\n\t"
+                 "ds_read_b128 %5, %8 offset:%14\n\t"
+                 "ds_read_b128 %6, %8 offset:%15\n\t"
+                 "ds_read_b128 %7, %8 offset:%16\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2]), "=&v"(b[3]), "=&v"(b[4]), "=&v"(b[5]), "=&v"(b[6]), "=&v"(b[7])
+                 : "v"(addr), "n"(BASE + 0 * 4096), "n"(BASE + 1 * 4096), "n"(BASE + 2 * 4096), "n"(BASE + 3 * 4096), "n"(BASE + 4 * 4096), "n"(BASE + 5 * 4096), "n"(BASE + 6 * 4096), "n"(BASE + 7 * 4096)
+                 :);
+  }
+}
+
+// One 16-byte weight fragment, asynchronously: the register is valid only after
+// a wait_weights() that names it.  (The compiler's own vmcnt bookkeeping gives
+// up across the rotating stages and early exits of the chunk loop and waits for
+// everything at every use, which would drain the prefetch; so these loads and
+// their waits are explicit.)
+template <int OFF>
+__device__ __forceinline__ void ld8_async(bf16x8& v, const uint16_t* ubase, uint32_t lane_off) {
+  asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt"
+               : "=v"(v)
+               : "v"(lane_off), "s"(ubase), "n"(OFF));
+}
+// A pointer the compiler may keep in scalar registers (the value is the same in all lanes).
+template <typename T>
+__device__ __forceinline__ T* uniform_ptr(T* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+  return reinterpret_cast<T*>((static_cast<unsigned long long>(hi) << 32) | lo);
+}
+// Weight tile rt of a [rows][kd] matrix as uniform base + per-lane byte offset.
+template <bool PACKED>
+__device__ __forceinline__ const uint16_t* tile_base(const uint16_t* base, int rt, int kd) {
+  return base + static_cast<size_t>(rt) * 16 * kd;  // 16 rows of kd values in either layout
+}
+template <bool PACKED>
+__device__ __forceinline__ uint32_t tile_lane_off(int kd, int lane) {
+  return PACKED ? lane * 16u : ((lane & 15) * static_cast<uint32_t>(kd) + (lane >> 4) * 8u) * 2u;
+}
+// Waits until at most N vector-memory operations are outstanding and makes the
+// eight fragments of a stage depend on that wait.
+template <int N>
+__device__ __forceinline__ void wait_weights(bf16x8 (&a)[4], bf16x8 (&b)[4]) {
+  asm volatile("s_waitcnt vmcnt(%8)"
+               : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]),
+                 "+v"(b[3])
+               : "n"(N));
+}
 
 // acc0/acc1 += A0/A1 (this wavefront's two 16-row weight tiles, reduction
-// length kd) x rows (the workgroup's token rows).  All four wavefronts call it.
-template <int NT, bool PACKED>
-__device__ __forceinline__ void lds_stream_gemm(const uint16_t* a0, const uint16_t* a1, bool active,
-                                                int kd, int rows_valid, LdsGemm& sm,
+// length kd, a multiple of 128) x token rows.  Row r of the pass (r < 16*NT) is
+// `base + row_off(min(r, rows_valid-1))`.  `lds` is the workgroup's buffer of
+// 2 * ROWS * 256 bytes.  All LW wavefronts of the workgroup call it together;
+// a0, a1, base and `wave` are wavefront-uniform; w_lane_off is the lane's byte
+// offset inside a weight fragment.
+//
+// A wavefront without a tile of its own (row tiles not a multiple of LW) runs
+// on tile 0 and drops its result.
+template <int NT, int ROWS, bool PACKED, int LW, typename RowOff>
+__device__ __forceinline__ void dma_stream_gemm(const uint16_t* a0, const uint16_t* a1,
+                                                uint32_t w_lane_off, int wave, int kd,
+                                                int rows_valid, const uint16_t* base,
+                                                RowOff row_off, uint16_t* lds,
                                                 f32x4 (&acc0)[NT], f32x4 (&acc1)[NT]) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int nks = kd / 32;
-  const int nchunks = (kd + kKC - 1) / kKC;
-  const int c16 = tid & 15, r0 = tid >> 4;  // this thread's 16-byte column and first row
-  bf16x8 st[kLPieces];
-  bf16x8 aw0[2][4], aw1[2][4];
-  auto gload = [&](int chunk) {
+  const int lane = threadIdx.x & 63;
+  const int nchunks = kd / kKC;
+  constexpr int ND = 4 * NT / LW;    // direct loads per wavefront and chunk (4 rows each)
+  static_assert(4 * NT % LW == 0, "rows must divide over the wavefronts");
+  constexpr int kBufBytes = ROWS * 256;
+  constexpr int kFragBytes = frag_step<PACKED>() * 2;  // between k-steps of a weight tile
+  // All addresses are a uniform base, advanced per chunk in scalar registers,
+  // plus a per-lane byte offset that never changes.
+  uint32_t off[ND];                  // byte offset of this lane's piece of its rows, chunk 0
 #pragma unroll
-    for (int i = 0; i < kLPieces; ++i) {
-      const int row = r0 + 16 * i;
-      const int k = chunk * kKC + c16 * 8;
-      st[i] = (row < rows_valid && k < kd) ? ld8(sm.rowptr[row] + k) : zero8();
+  for (int i = 0; i < ND; ++i) {
+    const int row = (i * LW + wave) * 4 + (lane >> 4);
+    off[i] = (static_cast<uint32_t>(row_off(min(row, rows_valid - 1))) +
+              (((lane & 15) ^ (row & 15)) << 3)) * 2u;
+  }
+  // (asm, not the builtin: after the builtin the compiler waits for all
+  // outstanding loads as soon as an address register is reused)
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<size_t>(DES_LDS_PTR(lds)));
+  auto dma = [&](int chunk, auto bufc) {
+    constexpr int bs = decltype(bufc)::value;
+    const uint16_t* g = base + chunk * kKC;  // uniform
+#pragma unroll
+    for (int i = 0; i < ND; ++i) {
+      const uint32_t dst = lds0 + bs * kBufBytes + (i * LW + wave) * 4 * 256;  // uniform
+      const uint32_t o = off[i];
+      asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                   ::"v"(o), "s"(g), "s"(dst)
+                   : "m0");
     }
   };
-  auto lstore = [&](int b) {
-#pragma unroll
-    for (int i = 0; i < kLPieces; ++i)
-      *reinterpret_cast<bf16x8*>(&sm.buf[b][(r0 + 16 * i) * kLRow + c16 * 8]) = st[i];
-  };
+  bf16x8 aw0[2][4], aw1[2][4];
   auto loadw = [&](int chunk, auto stage) {
     constexpr int s = decltype(stage)::value;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int ks = chunk * 4 + u;
-      const bool ok = active && ks < nks;
-      aw0[s][u] = ok ? ld8_stream(a0 + static_cast<size_t>(ks) * frag_step<PACKED>()) : zero8();
-      aw1[s][u] = ok ? ld8_stream(a1 + static_cast<size_t>(ks) * frag_step<PACKED>()) : zero8();
-    }
+    const uint16_t* q0 = a0 + static_cast<size_t>(chunk) * 4 * frag_step<PACKED>();
+    const uint16_t* q1 = a1 + static_cast<size_t>(chunk) * 4 * frag_step<PACKED>();
+    ld8_async<0 * kFragBytes>(aw0[s][0], q0, w_lane_off);
+    ld8_async<0 * kFragBytes>(aw1[s][0], q1, w_lane_off);
+    ld8_async<1 * kFragBytes>(aw0[s][1], q0, w_lane_off);
+    ld8_async<1 * kFragBytes>(aw1[s][1], q1, w_lane_off);
+    ld8_async<2 * kFragBytes>(aw0[s][2], q0, w_lane_off);
+    ld8_async<2 * kFragBytes>(aw1[s][2], q1, w_lane_off);
+    ld8_async<3 * kFragBytes>(aw0[s][3], q0, w_lane_off);
+    ld8_async<3 * kFragBytes>(aw1[s][3], q1, w_lane_off);
   };
-  auto compute = [&](int b, auto stage) {
+  // LDS byte address of this lane's fragment of token tile 0, k-step u of a chunk
+  uint32_t fa[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    fa[u] = lds0 + (lane & 15) * 256 + (((u * 4 + (lane >> 4)) ^ (lane & 15)) << 4);
+  auto compute = [&](auto bufc, auto stage) {
+    constexpr int bs = decltype(bufc)::value;
     constexpr int s = decltype(stage)::value;
-    if (!active) return;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
+      bf16x8 b[NT];
+      lds_frags<NT, bs * kBufBytes>(b, fa[u]);
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
-        const bf16x8 bv = *reinterpret_cast<const bf16x8*>(
-            &sm.buf[b][(i * 16 + (lane & 15)) * kLRow + u * 32 + (lane >> 4) * 8]);
-        acc0[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw0[s][u], bv, acc0[i], 0, 0, 0);
-        acc1[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw1[s][u], bv, acc1[i], 0, 0, 0);
+        acc0[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw0[s][u], b[i], acc0[i], 0, 0, 0);
+        acc1[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw1[s][u], b[i], acc1[i], 0, 0, 0);
       }
     }
   };
-  gload(0);
+  // Step c: everything this wavefront asked for (its share of the activations
+  // of chunk c, its weights of chunk c) has landed; the barrier then says the
+  // same of the other wavefronts' shares, and that everybody is done reading
+  // the other buffer, which the loads of chunk c+1 overwrite while chunk c is
+  // multiplied.  Loads stay in flight during the arithmetic only; several
+  // workgroups per compute unit fill the gaps at the barriers.
+  auto step = [&](int c, auto bufc, auto nextbuf) {
+    constexpr int s = decltype(bufc)::value;
+    wait_weights<0>(aw0[s], aw1[s]);
+    __builtin_amdgcn_s_barrier();
+    if (c + 1 < nchunks) {
+      dma(c + 1, nextbuf);
+      loadw(c + 1, nextbuf);
+    }
+    compute(bufc, bufc);
+  };
+  dma(0, S0{});
   loadw(0, S0{});
-  lstore(0);
-  __syncthreads();
   for (int c = 0; c < nchunks; c += 2) {
-    // chunk c from buffer 0 / stage 0 while chunk c+1 is fetched
-    if (c + 1 < nchunks) { gload(c + 1); loadw(c + 1, S1{}); }
-    compute(0, S0{});
-    if (c + 1 < nchunks) lstore(1);
-    __syncthreads();
+    step(c, S0{}, S1{});
     if (c + 1 >= nchunks) break;
-    if (c + 2 < nchunks) { gload(c + 2); loadw(c + 2, S0{}); }
-    compute(1, S1{});
-    if (c + 2 < nchunks) lstore(0);
-    __syncthreads();
+    step(c + 1, S1{}, S0{});
   }
+  __builtin_amdgcn_s_barrier();  // nobody still reads a buffer the next pass refills
 }
 
 // Which expert and which pairs a workgroup works on (as Task), shared by the two kernels.
@@ -654,36 +796,38 @@ __device__ __forceinline__ bool lds_task(const FfnArgs& a, int per_expert, int& 
   return true;
 }
 
-template <bool PACKED>
-__global__ __launch_bounds__(kLW* kWave) void gateup_lds_kernel(FfnArgs a) {
-  __shared__ __align__(16) LdsGemm sm;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// MAXNT = token tiles per workgroup pass (the LDS buffer holds 16*MAXNT rows);
+// LW = wavefronts per workgroup.  blockIdx.y picks every gridDim.y-th group of
+// 16*MAXNT pairs of the expert: an expert with more pairs than one pass holds
+// is spread over several workgroups (its weights are then read once per pass).
+template <bool PACKED, int MAXNT, int LW>
+__global__ __launch_bounds__(LW* kWave, (MAXNT <= 4 ? 2 : 1)) void gateup_lds_kernel(FfnArgs a) {
+  constexpr int kRows = 16 * MAXNT;
+  __shared__ __align__(16) uint16_t lds[2 * kRows * 128];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   Task t;
   FfnArgs v;
   int group;
-  const int per_r = (a.F / 16 + kLW - 1) / kLW;
-  const int per_s = (a.Fs / 16 + kLW - 1) / kLW;
+  const int per_r = (a.F / 16 + LW - 1) / LW;
+  const int per_s = (a.Fs / 16 + LW - 1) / LW;
   if (static_cast<int>(blockIdx.x) >= a.n_slots * per_r + per_s) return;
   if (!lds_task<false>(a, per_r, group, t, v, lane)) return;  // uniform per workgroup
-  // blockIdx.y picks 128 of the expert's pairs: an expert with more pairs than
-  // that is spread over two or more workgroups instead of looping in one (its
-  // weights are then read once per 128 pairs; measured faster than looping,
-  // while 64-pair groups were slower: the extra weight reads are real HBM reads)
-  const int tile = group * kLW + wave;
+  const int tile = group * LW + wave;
   const bool active = tile < t.fdim / 16;
-  const uint16_t* gp = frag_ptr<PACKED>(t.w0, active ? tile : 0, a.D, lane);
-  const uint16_t* up = frag_ptr<PACKED>(t.w1, active ? tile : 0, a.D, lane);
-  const uint16_t* x = static_cast<const uint16_t*>(a.x);
+  const uint16_t* w0 = uniform_ptr(t.w0);
+  const uint16_t* gp = tile_base<PACKED>(w0, active ? tile : 0, a.D);
+  const uint16_t* up = tile_base<PACKED>(uniform_ptr(t.w1), active ? tile : 0, a.D);
+  const uint32_t wlo = tile_lane_off<PACKED>(a.D, lane);
+  const uint16_t* x = uniform_ptr(static_cast<const uint16_t*>(a.x));
   uint16_t* h = static_cast<uint16_t*>(v.h);
-  for (int g0 = blockIdx.y * kLRows; g0 < t.count; g0 += gridDim.y * kLRows) {
-    const int rows = min(kLRows, t.count - g0);
-    if (tid < kLRows) {
-      const int pi = min(g0 + tid, t.count - 1);
-      const int tok = t.shared ? pi : a.pair_tok[t.pair0 + pi];
-      sm.rowptr[tid] = x + static_cast<size_t>(tok) * a.D;
-    }
-    __syncthreads();
+  for (int g0 = blockIdx.y * kRows; g0 < t.count; g0 += gridDim.y * kRows) {
+    const int rows = min(kRows, t.count - g0);
     const int nt = (rows + 15) / 16;
+    auto row_off = [&](int r) {
+      const int tok = t.shared ? g0 + r : a.pair_tok[t.pair0 + g0 + r];
+      return tok * a.D;
+    };
     auto run = [&](auto ntc) {
       constexpr int NT = decltype(ntc)::value;
       f32x4 accg[NT], accu[NT];
@@ -692,7 +836,8 @@ __global__ __launch_bounds__(kLW* kWave) void gateup_lds_kernel(FfnArgs a) {
         accg[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         accu[i] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
-      lds_stream_gemm<NT, PACKED>(gp, up, active, a.D, rows, sm, accg, accu);
+      dma_stream_gemm<NT, kRows, PACKED, LW>(gp, up, wlo, wave, a.D, rows, x, row_off, lds, accg,
+                                             accu);
       if (!active) return;
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
@@ -707,39 +852,39 @@ __global__ __launch_bounds__(kLW* kWave) void gateup_lds_kernel(FfnArgs a) {
     };
     if (nt <= 1) run(std::integral_constant<int, 1>{});
     else if (nt <= 2) run(std::integral_constant<int, 2>{});
-    else if (nt <= 4) run(std::integral_constant<int, 4>{});
-    else if (nt <= 6) run(std::integral_constant<int, 6>{});
-    else run(std::integral_constant<int, 8>{});
-    __syncthreads();  // the next pass rewrites rowptr and the buffers
+    else if (MAXNT <= 4 || nt <= 4) run(std::integral_constant<int, 4>{});
+    else if (nt <= 6) run(std::integral_constant<int, MAXNT >= 8 ? 6 : 4>{});
+    else run(std::integral_constant<int, MAXNT >= 8 ? 8 : 4>{});
   }
 }
 
-template <bool PACKED>
-__global__ __launch_bounds__(kLW* kWave) void down_lds_kernel(FfnArgs a) {
-  __shared__ __align__(16) LdsGemm sm;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+template <bool PACKED, int MAXNT, int LW>
+__global__ __launch_bounds__(LW* kWave, (MAXNT <= 4 ? 2 : 1)) void down_lds_kernel(FfnArgs a) {
+  constexpr int kRows = 16 * MAXNT;
+  __shared__ __align__(16) uint16_t lds[2 * kRows * 128];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   Task t;
   FfnArgs v;
   int group;
   const int dtiles = a.D / 16;                       // even: D is a multiple of 32
-  const int per = (dtiles / 2 + kLW - 1) / kLW;      // a wavefront owns two row tiles
+  const int per = (dtiles / 2 + LW - 1) / LW;        // a wavefront owns two row tiles
   if (static_cast<int>(blockIdx.x) >= a.n_slots * per + (a.Fs > 0 ? per : 0)) return;
   if (!lds_task<true>(a, per, group, t, v, lane)) return;
-  const int dt0 = (group * kLW + wave) * 2;
+  const int dt0 = (group * LW + wave) * 2;
   const bool active = dt0 < dtiles;
   const int F = t.fdim;
-  const uint16_t* p0 = frag_ptr<PACKED>(t.w0, active ? dt0 : 0, F, lane);
-  const uint16_t* p1 = frag_ptr<PACKED>(t.w0, active ? dt0 + 1 : 0, F, lane);
-  const uint16_t* h = static_cast<const uint16_t*>(v.h);
+  const uint16_t* w0 = uniform_ptr(t.w0);
+  const uint16_t* p0 = tile_base<PACKED>(w0, active ? dt0 : 0, F);
+  const uint16_t* p1 = tile_base<PACKED>(w0, active ? dt0 + 1 : 0, F);
+  const uint32_t wlo = tile_lane_off<PACKED>(F, lane);
+  const uint16_t* h = uniform_ptr(static_cast<const uint16_t*>(v.h));
   const size_t orow0 = t.shared ? static_cast<size_t>(a.T) * a.K : static_cast<size_t>(t.pair0);
-  for (int g0 = blockIdx.y * kLRows; g0 < t.count; g0 += gridDim.y * kLRows) {
-    const int rows = min(kLRows, t.count - g0);
-    if (tid < kLRows) {
-      const int pi = min(g0 + tid, t.count - 1);
-      sm.rowptr[tid] = h + (t.row_base + pi) * F;
-    }
-    __syncthreads();
+  for (int g0 = blockIdx.y * kRows; g0 < t.count; g0 += gridDim.y * kRows) {
+    const int rows = min(kRows, t.count - g0);
     const int nt = (rows + 15) / 16;
+    const int hrow0 = static_cast<int>(t.row_base) + g0;
+    auto row_off = [&](int r) { return (hrow0 + r) * F; };
     auto run = [&](auto ntc) {
       constexpr int NT = decltype(ntc)::value;
       f32x4 acc0[NT], acc1[NT];
@@ -748,7 +893,8 @@ __global__ __launch_bounds__(kLW* kWave) void down_lds_kernel(FfnArgs a) {
         acc0[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         acc1[i] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
-      lds_stream_gemm<NT, PACKED>(p0, p1, active, F, rows, sm, acc0, acc1);
+      dma_stream_gemm<NT, kRows, PACKED, LW>(p0, p1, wlo, wave, F, rows, h, row_off, lds, acc0,
+                                             acc1);
       if (!active) return;
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
@@ -762,10 +908,9 @@ __global__ __launch_bounds__(kLW* kWave) void down_lds_kernel(FfnArgs a) {
     };
     if (nt <= 1) run(std::integral_constant<int, 1>{});
     else if (nt <= 2) run(std::integral_constant<int, 2>{});
-    else if (nt <= 4) run(std::integral_constant<int, 4>{});
-    else if (nt <= 6) run(std::integral_constant<int, 6>{});
-    else run(std::integral_constant<int, 8>{});
-    __syncthreads();
+    else if (MAXNT <= 4 || nt <= 4) run(std::integral_constant<int, 4>{});
+    else if (nt <= 6) run(std::integral_constant<int, MAXNT >= 8 ? 6 : 4>{});
+    else run(std::integral_constant<int, MAXNT >= 8 ? 8 : 4>{});
   }
 }
 
@@ -1157,20 +1302,42 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     else if (maxnt <= 8) DES_LAUNCH_FFN(8, PK);                                             \
     else DES_LAUNCH_FFN(16, PK);                                                            \
   } while (0)
-    if (a.T > 32 && !fused_requested) {
+    static const int lds_min_t = getenv("DES_LDS_MIN_T") ? atoi(getenv("DES_LDS_MIN_T")) : 32;
+    const bool chunked = a.D % kKC == 0 && a.F % kKC == 0 && a.Fs % kKC == 0;
+    if (a.T > lds_min_t && chunked && !fused_requested) {
       // larger blocks: activations staged through LDS, four wavefronts per expert group
-      const int gu_lds = a.n_slots * ((a.F / 16 + kLW - 1) / kLW) + (a.Fs / 16 + kLW - 1) / kLW;
-      const int per_dn = (a.D / 32 + kLW - 1) / kLW;
-      const int dn_lds = a.n_slots * per_dn + (a.Fs > 0 ? per_dn : 0);
-      int splits = (a.T + kLRows - 1) / kLRows;  // token groups of 128 (grid.y), at most 8
+      // token rows per workgroup pass: 64 while no expert can have more, else 128;
+      // an expert with more pairs is spread over grid.y (at most 8 ways)
+      const bool small = a.T <= 64;
+      const int rows_pass = small ? 64 : 128;
+      int splits = (a.T + rows_pass - 1) / rows_pass;
       if (splits > 8) splits = 8;
-      if (packed) {
-        launch(kKGateUp, gateup_lds_kernel<true>, dim3(gu_lds, splits), dim3(kLW * kWave), 0, st, a);
-        launch(kKDown, down_lds_kernel<true>, dim3(dn_lds, splits), dim3(kLW * kWave), 0, st, a);
-      } else {
-        launch(kKGateUp, gateup_lds_kernel<false>, dim3(gu_lds, splits), dim3(kLW * kWave), 0, st, a);
-        launch(kKDown, down_lds_kernel<false>, dim3(dn_lds, splits), dim3(kLW * kWave), 0, st, a);
-      }
+      static const int lw_env = getenv("DES_LDS_WAVES") ? atoi(getenv("DES_LDS_WAVES")) : 2;
+      const int lw = lw_env;
+      const int gu_lds = a.n_slots * ((a.F / 16 + lw - 1) / lw) + (a.Fs / 16 + lw - 1) / lw;
+      const int per_dn = (a.D / 32 + lw - 1) / lw;
+      const int dn_lds = a.n_slots * per_dn + (a.Fs > 0 ? per_dn : 0);
+      const dim3 gg(gu_lds, splits), dg(dn_lds, splits), lb(lw * kWave);
+#define DES_LAUNCH_LDS2(PK, LWV)                                                  \
+  do {                                                                            \
+    if (small) {                                                                  \
+      launch(kKGateUp, gateup_lds_kernel<PK, 4, LWV>, gg, lb, 0, st, a);          \
+      launch(kKDown, down_lds_kernel<PK, 4, LWV>, dg, lb, 0, st, a);              \
+    } else {                                                                      \
+      launch(kKGateUp, gateup_lds_kernel<PK, 8, LWV>, gg, lb, 0, st, a);          \
+      launch(kKDown, down_lds_kernel<PK, 8, LWV>, dg, lb, 0, st, a);              \
+    }                                                                             \
+  } while (0)
+#define DES_LAUNCH_LDS(PK)                                                        \
+  do {                                                                            \
+    if (lw == 1) DES_LAUNCH_LDS2(PK, 1);                                          \
+    else if (lw == 2) DES_LAUNCH_LDS2(PK, 2);                                     \
+    else DES_LAUNCH_LDS2(PK, 4);                                                  \
+  } while (0)
+      if (packed) DES_LAUNCH_LDS(true);
+      else DES_LAUNCH_LDS(false);
+#undef DES_LAUNCH_LDS2
+#undef DES_LAUNCH_LDS
     } else if (packed) {
       DES_LAUNCH_BY_NT(true);
     } else {
