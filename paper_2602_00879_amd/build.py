@@ -33,5 +33,17 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def device_asm(source: str, out_path: str) -> str:
+    """gfx950 assembly of one source file (device side only), for checks on the
+    generated code (wait states around hand-written asm, register spills)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in FLAGS if f not in ("-fPIC", "-shared")]
+    cmd = [hipcc, *flags, "--cuda-device-only", "-S", os.path.join(CSRC, source), "-o", out_path]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + r.stderr)
+    return out_path
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

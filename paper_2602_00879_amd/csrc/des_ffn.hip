@@ -582,7 +582,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 // b[i] = 16 bytes at LDS address addr + BASE + i*4096 (token tile i of a buffer).
 template <int NT, int BASE>
 __device__ __forceinline__ void lds_frags(bf16x8 (&b)[NT], uint32_t addr) {
-  static_assert(NT == 1 || NT == 2 || NT == 4 || NT == 6 || NT == 8, "token tiles per pass");
+  static_assert(NT >= 1 && NT <= 4, "token tiles fetched at a time");
   if constexpr (NT == 1) {
     asm volatile("ds_read_b128 %0, %1 offset:%2\n\t"
                  "s_waitcnt lgkmcnt(0)"
@@ -608,30 +608,13 @@ __device__ __forceinline__ void lds_frags(bf16x8 (&b)[NT], uint32_t addr) {
                  : "v"(addr), "n"(BASE + 0 * 4096), "n"(BASE + 1 * 4096), "n"(BASE + 2 * 4096), "n"(BASE + 3 * 4096)
                  :);
   }
-  if constexpr (NT == 6) {
-    asm volatile("ds_read_b128 %0, %6 offset:%7\n\t"
-                 "ds_read_b128 %1, %6 offset:%8\n\t"
-                 "ds_read_b128 %2, %6 offset:%9\n\t"
-                 "ds_read_b128 %3, %6 offset:%10\n\t"
-                 "ds_read_b128 %4, %6 offset:%11\n\t"
-                 "ds_read_b128 %5, %6 offset:%12\n\t"
+  if constexpr (NT == 3) {
+    asm volatile("ds_read_b128 %0, %3 offset:%4\n\t"
+                 "ds_read_b128 %1, %3 offset:%5\n\t"
+                 "ds_read_b128 %2, %3 offset:%6\n\t"
                  "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2]), "=&v"(b[3]), "=&v"(b[4]), "=&v"(b[5])
-                 : "v"(addr), "n"(BASE + 0 * 4096), "n"(BASE + 1 * 4096), "n"(BASE + 2 * 4096), "n"(BASE + 3 * 4096), "n"(BASE + 4 * 4096), "n"(BASE + 5 * 4096)
-                 :);
-  }
-  if constexpr (NT == 8) {
-    asm volatile("ds_read_b128 %0, %8 offset:%9\n\t"
-                 "ds_read_b128 %1, %8 offset:%10\n\t"
-                 "ds_read_b128 %2, %8 offset:%11\n\t"
-                 "ds_read_b128 %3, %8 offset:%12\n\t"
-                 "ds_read_b128 %4, %8 offset:%13\n\t"
-                 "ds_read_b128 %5, %8 offset:%14\n\t"
-                 "ds_read_b128 %6, %8 offset:%15\n\t"
-                 "ds_read_b128 %7, %8 offset:%16\n\t"
-                 "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2]), "=&v"(b[3]), "=&v"(b[4]), "=&v"(b[5]), "=&v"(b[6]), "=&v"(b[7])
-                 : "v"(addr), "n"(BASE + 0 * 4096), "n"(BASE + 1 * 4096), "n"(BASE + 2 * 4096), "n"(BASE + 3 * 4096), "n"(BASE + 4 * 4096), "n"(BASE + 5 * 4096), "n"(BASE + 6 * 4096), "n"(BASE + 7 * 4096)
+                 : "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2])
+                 : "v"(addr), "n"(BASE + 0 * 4096), "n"(BASE + 1 * 4096), "n"(BASE + 2 * 4096)
                  :);
   }
 }
@@ -643,7 +626,10 @@ __device__ __forceinline__ void lds_frags(bf16x8 (&b)[NT], uint32_t addr) {
 // their waits are explicit.)
 template <int OFF>
 __device__ __forceinline__ void ld8_async(bf16x8& v, const uint16_t* ubase, uint32_t lane_off) {
-  asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt"
+  // s_nop 4: the base may have just been written by a vector instruction (a
+  // scalar register restored from a spill lane); a vector-memory instruction
+  // needs five wait states after that, and the compiler adds none inside asm.
+  asm volatile("s_nop 4\n\tglobal_load_dwordx4 %0, %1, %2 offset:%3 nt"
                : "=v"(v)
                : "v"(lane_off), "s"(ubase), "n"(OFF));
 }
@@ -674,6 +660,11 @@ __device__ __forceinline__ void wait_weights(bf16x8 (&a)[4], bf16x8 (&b)[4]) {
                : "n"(N));
 }
 
+template <int... I, typename F>
+__device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+
 // acc0/acc1 += A0/A1 (this wavefront's two 16-row weight tiles, reduction
 // length kd, a multiple of 128) x token rows.  Row r of the pass (r < 16*NT) is
 // `base + row_off(min(r, rows_valid-1))`.  `lds` is the workgroup's buffer of
@@ -683,7 +674,7 @@ __device__ __forceinline__ void wait_weights(bf16x8 (&a)[4], bf16x8 (&b)[4]) {
 //
 // A wavefront without a tile of its own (row tiles not a multiple of LW) runs
 // on tile 0 and drops its result.
-template <int NT, int ROWS, bool PACKED, int LW, typename RowOff>
+template <int NT, int ROWS, bool PACKED, int LW, int NCH, typename RowOff>
 __device__ __forceinline__ void dma_stream_gemm(const uint16_t* a0, const uint16_t* a1,
                                                 uint32_t w_lane_off, int wave, int kd,
                                                 int rows_valid, const uint16_t* base,
@@ -714,12 +705,16 @@ __device__ __forceinline__ void dma_stream_gemm(const uint16_t* a0, const uint16
     for (int i = 0; i < ND; ++i) {
       const uint32_t dst = lds0 + bs * kBufBytes + (i * LW + wave) * 4 * 256;  // uniform
       const uint32_t o = off[i];
-      asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+      // Wait states the compiler would insert for its own instructions but does
+      // not for asm: one between the write of M0 and the load, five between a
+      // vector instruction that wrote the base registers (a scalar register
+      // restored from a spill lane) and the load.
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %0, %1"
                    ::"v"(o), "s"(g), "s"(dst)
                    : "m0");
     }
   };
-  bf16x8 aw0[2][4], aw1[2][4];
+  bf16x8 aw0[NCH > 0 ? 3 : 2][4], aw1[NCH > 0 ? 3 : 2][4];
   auto loadw = [&](int chunk, auto stage) {
     constexpr int s = decltype(stage)::value;
     const uint16_t* q0 = a0 + static_cast<size_t>(chunk) * 4 * frag_step<PACKED>();
@@ -741,39 +736,67 @@ __device__ __forceinline__ void dma_stream_gemm(const uint16_t* a0, const uint16
   auto compute = [&](auto bufc, auto stage) {
     constexpr int bs = decltype(bufc)::value;
     constexpr int s = decltype(stage)::value;
+    constexpr int G = NT > 4 ? NT / 2 : NT;  // token tiles fetched from LDS at a time
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      bf16x8 b[NT];
-      lds_frags<NT, bs * kBufBytes>(b, fa[u]);
 #pragma unroll
-      for (int i = 0; i < NT; ++i) {
-        acc0[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw0[s][u], b[i], acc0[i], 0, 0, 0);
-        acc1[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw1[s][u], b[i], acc1[i], 0, 0, 0);
+      for (int g = 0; g < NT; g += G) {
+        bf16x8 b[G];
+        if (g == 0) lds_frags<G, bs * kBufBytes>(b, fa[u]);
+        else lds_frags<G, bs * kBufBytes + G * 4096>(b, fa[u]);
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+          acc0[g + i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw0[s][u], b[i], acc0[g + i], 0, 0, 0);
+          acc1[g + i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw1[s][u], b[i], acc1[g + i], 0, 0, 0);
+        }
       }
     }
   };
-  // Step c: everything this wavefront asked for (its share of the activations
-  // of chunk c, its weights of chunk c) has landed; the barrier then says the
-  // same of the other wavefronts' shares, and that everybody is done reading
-  // the other buffer, which the loads of chunk c+1 overwrite while chunk c is
-  // multiplied.  Loads stay in flight during the arithmetic only; several
-  // workgroups per compute unit fill the gaps at the barriers.
-  auto step = [&](int c, auto bufc, auto nextbuf) {
-    constexpr int s = decltype(bufc)::value;
-    wait_weights<0>(aw0[s], aw1[s]);
-    __builtin_amdgcn_s_barrier();
-    if (c + 1 < nchunks) {
-      dma(c + 1, nextbuf);
-      loadw(c + 1, nextbuf);
+  if constexpr (NCH > 0) {
+    // Reduction length known at compile time (kd == NCH * 128): straight-line
+    // code, weights three chunks deep.  Issue order of vector-memory operations:
+    //   W(0) A(0) W(1) | step 0: A(1) W(2) | step 1: A(2) W(3) | ...
+    // (W = the 8 weight loads of a chunk, A = this wavefront's share of the
+    // activation loads of a chunk).  They complete in order, so "at most 8
+    // outstanding" at the top of step c means A(c) and W(c) have landed while
+    // W(c+1) may still be in flight across the barrier.
+    loadw(0, S0{});
+    dma(0, S0{});
+    if constexpr (NCH > 1) loadw(1, S1{});
+    static_for(std::make_integer_sequence<int, NCH>{}, [&](auto cc) {
+      constexpr int c = decltype(cc)::value;
+      typedef std::integral_constant<int, c % 3> Stage;
+      typedef std::integral_constant<int, c % 2> Buf;
+      if constexpr (c + 1 < NCH) wait_weights<8>(aw0[c % 3], aw1[c % 3]);
+      else wait_weights<0>(aw0[c % 3], aw1[c % 3]);
+      __builtin_amdgcn_s_barrier();
+      if constexpr (c + 1 < NCH) dma(c + 1, std::integral_constant<int, (c + 1) % 2>{});
+      if constexpr (c + 2 < NCH) loadw(c + 2, std::integral_constant<int, (c + 2) % 3>{});
+      compute(Buf{}, Stage{});
+    });
+  } else {
+    // Any reduction length: two stages.  Step c: everything this wavefront asked
+    // for (its share of the activations of chunk c, its weights of chunk c) has
+    // landed; the barrier then says the same of the other wavefronts' shares, and
+    // that everybody is done reading the other buffer, which the loads of chunk
+    // c+1 overwrite while chunk c is multiplied.
+    auto step = [&](int c, auto bufc, auto nextbuf) {
+      constexpr int s = decltype(bufc)::value;
+      wait_weights<0>(aw0[s], aw1[s]);
+      __builtin_amdgcn_s_barrier();
+      if (c + 1 < nchunks) {
+        dma(c + 1, nextbuf);
+        loadw(c + 1, nextbuf);
+      }
+      compute(bufc, bufc);
+    };
+    dma(0, S0{});
+    loadw(0, S0{});
+    for (int c = 0; c < nchunks; c += 2) {
+      step(c, S0{}, S1{});
+      if (c + 1 >= nchunks) break;
+      step(c + 1, S1{}, S0{});
     }
-    compute(bufc, bufc);
-  };
-  dma(0, S0{});
-  loadw(0, S0{});
-  for (int c = 0; c < nchunks; c += 2) {
-    step(c, S0{}, S1{});
-    if (c + 1 >= nchunks) break;
-    step(c + 1, S1{}, S0{});
   }
   __builtin_amdgcn_s_barrier();  // nobody still reads a buffer the next pass refills
 }
@@ -797,11 +820,12 @@ __device__ __forceinline__ bool lds_task(const FfnArgs& a, int per_expert, int& 
 }
 
 // MAXNT = token tiles per workgroup pass (the LDS buffer holds 16*MAXNT rows);
-// LW = wavefronts per workgroup.  blockIdx.y picks every gridDim.y-th group of
+// LW = wavefronts per workgroup; NCH = reduction length / 128 when the host
+// knows it to be one of the unrolled cases, else 0.  blockIdx.y picks every gridDim.y-th group of
 // 16*MAXNT pairs of the expert: an expert with more pairs than one pass holds
 // is spread over several workgroups (its weights are then read once per pass).
-template <bool PACKED, int MAXNT, int LW>
-__global__ __launch_bounds__(LW* kWave, (MAXNT <= 4 ? 2 : 1)) void gateup_lds_kernel(FfnArgs a) {
+template <bool PACKED, int MAXNT, int LW, int NCH>
+__global__ __launch_bounds__(LW* kWave, 2) void gateup_lds_kernel(FfnArgs a) {
   constexpr int kRows = 16 * MAXNT;
   __shared__ __align__(16) uint16_t lds[2 * kRows * 128];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -836,8 +860,8 @@ __global__ __launch_bounds__(LW* kWave, (MAXNT <= 4 ? 2 : 1)) void gateup_lds_ke
         accg[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         accu[i] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
-      dma_stream_gemm<NT, kRows, PACKED, LW>(gp, up, wlo, wave, a.D, rows, x, row_off, lds, accg,
-                                             accu);
+      dma_stream_gemm<NT, kRows, PACKED, LW, NCH>(gp, up, wlo, wave, a.D, rows, x, row_off, lds,
+                                                  accg, accu);
       if (!active) return;
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
@@ -858,8 +882,8 @@ __global__ __launch_bounds__(LW* kWave, (MAXNT <= 4 ? 2 : 1)) void gateup_lds_ke
   }
 }
 
-template <bool PACKED, int MAXNT, int LW>
-__global__ __launch_bounds__(LW* kWave, (MAXNT <= 4 ? 2 : 1)) void down_lds_kernel(FfnArgs a) {
+template <bool PACKED, int MAXNT, int LW, int NCH>
+__global__ __launch_bounds__(LW* kWave, 2) void down_lds_kernel(FfnArgs a) {
   constexpr int kRows = 16 * MAXNT;
   __shared__ __align__(16) uint16_t lds[2 * kRows * 128];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -893,8 +917,8 @@ __global__ __launch_bounds__(LW* kWave, (MAXNT <= 4 ? 2 : 1)) void down_lds_kern
         acc0[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         acc1[i] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
-      dma_stream_gemm<NT, kRows, PACKED, LW>(p0, p1, wlo, wave, F, rows, h, row_off, lds, acc0,
-                                             acc1);
+      dma_stream_gemm<NT, kRows, PACKED, LW, NCH>(p0, p1, wlo, wave, F, rows, h, row_off, lds,
+                                                  acc0, acc1);
       if (!active) return;
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
@@ -1318,25 +1342,40 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
       const int per_dn = (a.D / 32 + lw - 1) / lw;
       const int dn_lds = a.n_slots * per_dn + (a.Fs > 0 ? per_dn : 0);
       const dim3 gg(gu_lds, splits), dg(dn_lds, splits), lb(lw * kWave);
+      // unrolled reduction lengths (the shared expert shares the down launch)
+      const int gu_nch = a.D == 2048 ? 16 : 0;
+      const int dn_nch = (a.Fs != 0 && a.Fs != a.F) ? 0 : a.F == 768 ? 6 : a.F == 512 ? 4 : 0;
+#define DES_LAUNCH_GU(PK, MNT, LWV)                                                         \
+  do {                                                                                      \
+    if (gu_nch == 16) launch(kKGateUp, gateup_lds_kernel<PK, MNT, LWV, 16>, gg, lb, 0, st, a); \
+    else launch(kKGateUp, gateup_lds_kernel<PK, MNT, LWV, 0>, gg, lb, 0, st, a);            \
+  } while (0)
+#define DES_LAUNCH_DN(PK, MNT, LWV)                                                         \
+  do {                                                                                      \
+    if (dn_nch == 6) launch(kKDown, down_lds_kernel<PK, MNT, LWV, 6>, dg, lb, 0, st, a);    \
+    else if (dn_nch == 4) launch(kKDown, down_lds_kernel<PK, MNT, LWV, 4>, dg, lb, 0, st, a); \
+    else launch(kKDown, down_lds_kernel<PK, MNT, LWV, 0>, dg, lb, 0, st, a);                \
+  } while (0)
 #define DES_LAUNCH_LDS2(PK, LWV)                                                  \
   do {                                                                            \
     if (small) {                                                                  \
-      launch(kKGateUp, gateup_lds_kernel<PK, 4, LWV>, gg, lb, 0, st, a);          \
-      launch(kKDown, down_lds_kernel<PK, 4, LWV>, dg, lb, 0, st, a);              \
+      DES_LAUNCH_GU(PK, 4, LWV);                                                  \
+      DES_LAUNCH_DN(PK, 4, LWV);                                                  \
     } else {                                                                      \
-      launch(kKGateUp, gateup_lds_kernel<PK, 8, LWV>, gg, lb, 0, st, a);          \
-      launch(kKDown, down_lds_kernel<PK, 8, LWV>, dg, lb, 0, st, a);              \
+      DES_LAUNCH_GU(PK, 8, LWV);                                                  \
+      DES_LAUNCH_DN(PK, 8, LWV);                                                  \
     }                                                                             \
   } while (0)
 #define DES_LAUNCH_LDS(PK)                                                        \
   do {                                                                            \
-    if (lw == 1) DES_LAUNCH_LDS2(PK, 1);                                          \
-    else if (lw == 2) DES_LAUNCH_LDS2(PK, 2);                                     \
-    else DES_LAUNCH_LDS2(PK, 4);                                                  \
+    if (lw == 4) DES_LAUNCH_LDS2(PK, 4);                                          \
+    else DES_LAUNCH_LDS2(PK, 2);                                                  \
   } while (0)
       if (packed) DES_LAUNCH_LDS(true);
       else DES_LAUNCH_LDS(false);
 #undef DES_LAUNCH_LDS2
+#undef DES_LAUNCH_GU
+#undef DES_LAUNCH_DN
 #undef DES_LAUNCH_LDS
     } else if (packed) {
       DES_LAUNCH_BY_NT(true);

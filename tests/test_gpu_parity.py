@@ -123,6 +123,13 @@ MID = dict(
     mid_f32=W.LayerConfig("mid_f32", "f32", 2, 9, 72, 24, 20, 12, 3, 6, 1.1, 12),
     wide_tok=W.LayerConfig("wide_tok", "bf16", 1, 150, 128, 12, 64, 0, 4, 3, 0.0, 13),
     many_tok=W.LayerConfig("many_tok", "bf16", 3, 100, 64, 8, 32, 32, 2, 2, 0.0, 14),
+    # blocks of more than 32 tokens with D, F multiples of 128: the kernels that stage
+    # the activations through LDS.  lds_64: one 64-row pass, a single 128-wide chunk in
+    # the down projection; lds_128: 128-row passes, shared expert; lds_split: experts
+    # with 44..210 pairs (two workgroups along the tokens, ragged last pass), three chunks
+    lds_64=W.LayerConfig("lds_64", "bf16", 1, 48, 256, 12, 128, 0, 4, 5, 1.1, 16),
+    lds_128=W.LayerConfig("lds_128", "bf16", 1, 80, 256, 12, 128, 128, 4, 5, 1.1, 17),
+    lds_split=W.LayerConfig("lds_split", "bf16", 3, 70, 384, 8, 256, 0, 2, 2, 1.1, 18),
 )
 
 
@@ -227,6 +234,21 @@ def test_m256_shared_full_size():
                                        label=f"m256 {mode} C={C}")
             _say(f"  {r}")
             assert r["n_unique"] <= C
+    # a longer block (96 tokens) through the same layer: the shared expert and the
+    # routed experts in the kernels for more than 32 tokens, both weight layouts
+    cfg96 = cfg.with_(n_tokens=96)
+    rng = np.random.default_rng([cfg.seed, 96])
+    layer["x"] = W._normal(rng, (1, 96, cfg.hidden), 1.0, cfg.dtype)
+    dev["x"] = H.dev_tensor(layer["x"])
+    _say("m256_shared N=96 vote")
+    out = H.run_gpu(cfg96, dev, "vote")
+    r = H.check_against_oracle(cfg96, layer, out, "vote", only_tokens=_sample_tokens(cfg96, 6, 96),
+                               label="m256 N=96 vote")
+    _say(f"  {r}")
+    packed = tuple(B.des_pack_expert_weights(dev[k]) for k in ("w_gate", "w_up", "w_down"))
+    psh = tuple(B.des_pack_expert_weights(m) for m in dev["shared"])
+    out2 = H.run_gpu(cfg96, dev, "vote", layout=B.DES_LAYOUT_PACKED, packed_weights=(*packed, psh))
+    assert torch.equal(out.y, out2.y), "m256 N=96: packed layout differs"
 
 
 def test_m128_block_size_sweep():
@@ -235,6 +257,7 @@ def test_m128_block_size_sweep():
     base = W.CONFIGS["m128_sweep"]
     layer = W.make_layer(base, with_x=False)
     dev_w = None
+    packed = None
     uniq = {}
     for N in (4, 8, 16, 32, 64, 128):
         cfg = base.with_(n_tokens=N)
@@ -250,6 +273,11 @@ def test_m128_block_size_sweep():
                                        label=f"sweep N={N} {mode}")
             uniq[(N, mode)] = r["n_unique"]
             _say(f"  {r}")
+            if N >= 64 and mode == "vote":  # the tiled weight layout through the same kernels
+                if packed is None:
+                    packed = tuple(B.des_pack_expert_weights(dev_w[k]) for k in ("w_gate", "w_up", "w_down"))
+                out2 = H.run_gpu(cfg, dev_w, mode, layout=B.DES_LAYOUT_PACKED, packed_weights=(*packed, None))
+                assert torch.equal(out.y, out2.y), f"sweep N={N}: packed layout differs"
     assert all(uniq[(N, "vote")] <= 32 for N in (4, 8, 16, 32, 64, 128))
     assert uniq[(128, "vanilla")] > uniq[(32, "vanilla")] > uniq[(4, "vanilla")]
 
