@@ -571,7 +571,7 @@ __global__ __launch_bounds__(kFfnWaves* kWave) void down_bf16_kernel(FfnArgs a) 
 // the compiler wait for every pending direct load first); they are volatile,
 // which keeps them in program order with each other, the barriers and the
 // direct loads.
-constexpr int kKC = 128;            // reduction elements per LDS chunk (4 k-steps)
+constexpr int kKC = 128;            // reduction lengths must be multiples of this
 #define DES_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 template <int N>
@@ -579,15 +579,16 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N));
 }
 
-// b[i] = 16 bytes at LDS address addr + BASE + i*4096 (token tile i of a buffer).
-template <int NT, int BASE>
+// b[i] = 16 bytes at LDS address addr + BASE + i*TILE (token tile i of a buffer;
+// TILE = bytes of 16 token rows).
+template <int NT, int BASE, int TILE>
 __device__ __forceinline__ void lds_frags(bf16x8 (&b)[NT], uint32_t addr) {
   static_assert(NT >= 1 && NT <= 4, "token tiles fetched at a time");
   if constexpr (NT == 1) {
     asm volatile("ds_read_b128 %0, %1 offset:%2\n\t"
                  "s_waitcnt lgkmcnt(0)"
                  : "=&v"(b[0])
-                 : "v"(addr), "n"(BASE + 0 * 4096)
+                 : "v"(addr), "n"(BASE + 0 * TILE)
                  :);
   }
   if constexpr (NT == 2) {
@@ -595,7 +596,16 @@ __device__ __forceinline__ void lds_frags(bf16x8 (&b)[NT], uint32_t addr) {
                  "ds_read_b128 %1, %2 offset:%4\n\t"
                  "s_waitcnt lgkmcnt(0)"
                  : "=&v"(b[0]), "=&v"(b[1])
-                 : "v"(addr), "n"(BASE + 0 * 4096), "n"(BASE + 1 * 4096)
+                 : "v"(addr), "n"(BASE + 0 * TILE), "n"(BASE + 1 * TILE)
+                 :);
+  }
+  if constexpr (NT == 3) {
+    asm volatile("ds_read_b128 %0, %3 offset:%4\n\t"
+                 "ds_read_b128 %1, %3 offset:%5\n\t"
+                 "ds_read_b128 %2, %3 offset:%6\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2])
+                 : "v"(addr), "n"(BASE + 0 * TILE), "n"(BASE + 1 * TILE), "n"(BASE + 2 * TILE)
                  :);
   }
   if constexpr (NT == 4) {
@@ -605,16 +615,7 @@ __device__ __forceinline__ void lds_frags(bf16x8 (&b)[NT], uint32_t addr) {
                  "ds_read_b128 %3, %4 offset:%8\n\t"
                  "s_waitcnt lgkmcnt(0)"
                  : "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2]), "=&v"(b[3])
-                 : "v"(addr), "n"(BASE + 0 * 4096), "n"(BASE + 1 * 4096), "n"(BASE + 2 * 4096), "n"(BASE + 3 * 4096)
-                 :);
-  }
-  if constexpr (NT == 3) {
-    asm volatile("ds_read_b128 %0, %3 offset:%4\n\t"
-                 "ds_read_b128 %1, %3 offset:%5\n\t"
-                 "ds_read_b128 %2, %3 offset:%6\n\t"
-                 "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2])
-                 : "v"(addr), "n"(BASE + 0 * 4096), "n"(BASE + 1 * 4096), "n"(BASE + 2 * 4096)
+                 : "v"(addr), "n"(BASE + 0 * TILE), "n"(BASE + 1 * TILE), "n"(BASE + 2 * TILE), "n"(BASE + 3 * TILE)
                  :);
   }
 }
@@ -651,13 +652,17 @@ __device__ __forceinline__ uint32_t tile_lane_off(int kd, int lane) {
   return PACKED ? lane * 16u : ((lane & 15) * static_cast<uint32_t>(kd) + (lane >> 4) * 8u) * 2u;
 }
 // Waits until at most N vector-memory operations are outstanding and makes the
-// eight fragments of a stage depend on that wait.
+// fragments of a stage depend on that wait.
 template <int N>
 __device__ __forceinline__ void wait_weights(bf16x8 (&a)[4], bf16x8 (&b)[4]) {
   asm volatile("s_waitcnt vmcnt(%8)"
                : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]),
                  "+v"(b[3])
                : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void wait_weights(bf16x8 (&a)[2], bf16x8 (&b)[2]) {
+  asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a[0]), "+v"(a[1]), "+v"(b[0]), "+v"(b[1]) : "n"(N));
 }
 
 template <int... I, typename F>
@@ -666,44 +671,65 @@ __device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F&&
 }
 
 // acc0/acc1 += A0/A1 (this wavefront's two 16-row weight tiles, reduction
-// length kd, a multiple of 128) x token rows.  Row r of the pass (r < 16*NT) is
-// `base + row_off(min(r, rows_valid-1))`.  `lds` is the workgroup's buffer of
-// 2 * ROWS * 256 bytes.  All LW wavefronts of the workgroup call it together;
+// length kd) x token rows.  KC = reduction elements per chunk (128 or 64), KD =
+// the reduction length if known at compile time (then kd == KD), else 0; kd is a
+// multiple of KC.  Row r of the pass (r < 16*NT) is `base + row_off(min(r,
+// rows_valid-1))`.  `lds` is the workgroup's buffer of NB * ROWS * 2*KC bytes
+// (ROWS >= 16*NT), NB = 3 if KD > 0, else 2.  All LW wavefronts of the workgroup call it together;
 // a0, a1, base and `wave` are wavefront-uniform; w_lane_off is the lane's byte
 // offset inside a weight fragment.
 //
+// LDS rows hold one chunk of a token row (2*KC bytes) with the 16-byte piece p
+// of row r stored at piece index p ^ swz(r), swz(r) = r & 15 for 256-byte rows,
+// (r >> 1) & 7 for 128-byte rows: the 16 token rows an MFMA operand reads fall
+// into 16 different bank groups.  A direct load writes lane l at base + 16*l,
+// so the swizzle is applied on the global side (which piece a lane fetches).
+//
 // A wavefront without a tile of its own (row tiles not a multiple of LW) runs
 // on tile 0 and drops its result.
-template <int NT, int ROWS, bool PACKED, int LW, int NCH, typename RowOff>
+template <int NT, int ROWS, bool PACKED, int LW, int KC, int KD, typename RowOff>
 __device__ __forceinline__ void dma_stream_gemm(const uint16_t* a0, const uint16_t* a1,
                                                 uint32_t w_lane_off, int wave, int kd,
                                                 int rows_valid, const uint16_t* base,
                                                 RowOff row_off, uint16_t* lds,
                                                 f32x4 (&acc0)[NT], f32x4 (&acc1)[NT]) {
+  static_assert(KC == 128 || KC == 64, "chunk of 4 or 2 k-steps");
+  static_assert(KD % KC == 0, "reduction length must be whole chunks");
   const int lane = threadIdx.x & 63;
-  const int nchunks = kd / kKC;
-  constexpr int ND = 4 * NT / LW;    // direct loads per wavefront and chunk (4 rows each)
-  static_assert(4 * NT % LW == 0, "rows must divide over the wavefronts");
-  constexpr int kBufBytes = ROWS * 256;
+  const int nchunks = kd / KC;
+  constexpr int NCH = KD / KC;
+  constexpr int KS = KC / 32;        // k-steps per chunk
+  constexpr int RB = KC * 2;         // bytes of a token row in LDS
+  constexpr int PP = KC / 8;         // 16-byte pieces per row
+  constexpr int RPI = 64 / PP;       // rows one direct load (64 lanes x 16 B) covers
+  constexpr int NG = 16 * NT / RPI;  // direct loads per chunk (RPI rows each)
+  constexpr int ND = (NG + LW - 1) / LW;  // ... per wavefront: every wavefront issues as many,
+                                     // so that the wait counts below hold for all of them; one
+                                     // without a group of its own repeats the last group
+                                     // (same bytes to the same place)
+  constexpr int NW = 2 * KS;         // weight loads per wavefront and chunk
+  constexpr int kBufBytes = ROWS * RB;
+  constexpr int kTile = 16 * RB;     // bytes of one token tile in a buffer
   constexpr int kFragBytes = frag_step<PACKED>() * 2;  // between k-steps of a weight tile
+  auto swz = [](int r) { return KC == 128 ? (r & 15) : ((r >> 1) & 7); };
   // All addresses are a uniform base, advanced per chunk in scalar registers,
   // plus a per-lane byte offset that never changes.
   uint32_t off[ND];                  // byte offset of this lane's piece of its rows, chunk 0
 #pragma unroll
   for (int i = 0; i < ND; ++i) {
-    const int row = (i * LW + wave) * 4 + (lane >> 4);
+    const int row = min(i * LW + wave, NG - 1) * RPI + lane / PP;
     off[i] = (static_cast<uint32_t>(row_off(min(row, rows_valid - 1))) +
-              (((lane & 15) ^ (row & 15)) << 3)) * 2u;
+              (((lane % PP) ^ swz(row)) << 3)) * 2u;
   }
   // (asm, not the builtin: after the builtin the compiler waits for all
   // outstanding loads as soon as an address register is reused)
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<size_t>(DES_LDS_PTR(lds)));
   auto dma = [&](int chunk, auto bufc) {
     constexpr int bs = decltype(bufc)::value;
-    const uint16_t* g = base + chunk * kKC;  // uniform
+    const uint16_t* g = base + chunk * KC;  // uniform
 #pragma unroll
     for (int i = 0; i < ND; ++i) {
-      const uint32_t dst = lds0 + bs * kBufBytes + (i * LW + wave) * 4 * 256;  // uniform
+      const uint32_t dst = lds0 + bs * kBufBytes + min(i * LW + wave, NG - 1) * 1024;  // uniform
       const uint32_t o = off[i];
       // Wait states the compiler would insert for its own instructions but does
       // not for asm: one between the write of M0 and the load, five between a
@@ -714,36 +740,38 @@ __device__ __forceinline__ void dma_stream_gemm(const uint16_t* a0, const uint16
                    : "m0");
     }
   };
-  bf16x8 aw0[NCH > 0 ? 3 : 2][4], aw1[NCH > 0 ? 3 : 2][4];
+  bf16x8 aw0[KD > 0 ? 3 : 2][KS], aw1[KD > 0 ? 3 : 2][KS];
   auto loadw = [&](int chunk, auto stage) {
     constexpr int s = decltype(stage)::value;
-    const uint16_t* q0 = a0 + static_cast<size_t>(chunk) * 4 * frag_step<PACKED>();
-    const uint16_t* q1 = a1 + static_cast<size_t>(chunk) * 4 * frag_step<PACKED>();
+    const uint16_t* q0 = a0 + static_cast<size_t>(chunk) * KS * frag_step<PACKED>();
+    const uint16_t* q1 = a1 + static_cast<size_t>(chunk) * KS * frag_step<PACKED>();
     ld8_async<0 * kFragBytes>(aw0[s][0], q0, w_lane_off);
     ld8_async<0 * kFragBytes>(aw1[s][0], q1, w_lane_off);
     ld8_async<1 * kFragBytes>(aw0[s][1], q0, w_lane_off);
     ld8_async<1 * kFragBytes>(aw1[s][1], q1, w_lane_off);
-    ld8_async<2 * kFragBytes>(aw0[s][2], q0, w_lane_off);
-    ld8_async<2 * kFragBytes>(aw1[s][2], q1, w_lane_off);
-    ld8_async<3 * kFragBytes>(aw0[s][3], q0, w_lane_off);
-    ld8_async<3 * kFragBytes>(aw1[s][3], q1, w_lane_off);
+    if constexpr (KS == 4) {
+      ld8_async<2 * kFragBytes>(aw0[s][2], q0, w_lane_off);
+      ld8_async<2 * kFragBytes>(aw1[s][2], q1, w_lane_off);
+      ld8_async<3 * kFragBytes>(aw0[s][3], q0, w_lane_off);
+      ld8_async<3 * kFragBytes>(aw1[s][3], q1, w_lane_off);
+    }
   };
   // LDS byte address of this lane's fragment of token tile 0, k-step u of a chunk
-  uint32_t fa[4];
+  uint32_t fa[KS];
 #pragma unroll
-  for (int u = 0; u < 4; ++u)
-    fa[u] = lds0 + (lane & 15) * 256 + (((u * 4 + (lane >> 4)) ^ (lane & 15)) << 4);
+  for (int u = 0; u < KS; ++u)
+    fa[u] = lds0 + (lane & 15) * RB + (((u * 4 + (lane >> 4)) ^ swz(lane & 15)) << 4);
   auto compute = [&](auto bufc, auto stage) {
     constexpr int bs = decltype(bufc)::value;
     constexpr int s = decltype(stage)::value;
     constexpr int G = NT > 4 ? NT / 2 : NT;  // token tiles fetched from LDS at a time
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < KS; ++u) {
 #pragma unroll
       for (int g = 0; g < NT; g += G) {
         bf16x8 b[G];
-        if (g == 0) lds_frags<G, bs * kBufBytes>(b, fa[u]);
-        else lds_frags<G, bs * kBufBytes + G * 4096>(b, fa[u]);
+        if (g == 0) lds_frags<G, bs * kBufBytes, kTile>(b, fa[u]);
+        else lds_frags<G, bs * kBufBytes + G * kTile, kTile>(b, fa[u]);
 #pragma unroll
         for (int i = 0; i < G; ++i) {
           acc0[g + i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw0[s][u], b[i], acc0[g + i], 0, 0, 0);
@@ -752,27 +780,35 @@ __device__ __forceinline__ void dma_stream_gemm(const uint16_t* a0, const uint16
       }
     }
   };
-  if constexpr (NCH > 0) {
-    // Reduction length known at compile time (kd == NCH * 128): straight-line
-    // code, weights three chunks deep.  Issue order of vector-memory operations:
-    //   W(0) A(0) W(1) | step 0: A(1) W(2) | step 1: A(2) W(3) | ...
-    // (W = the 8 weight loads of a chunk, A = this wavefront's share of the
-    // activation loads of a chunk).  They complete in order, so "at most 8
-    // outstanding" at the top of step c means A(c) and W(c) have landed while
-    // W(c+1) may still be in flight across the barrier.
-    loadw(0, S0{});
+  if constexpr (KD > 0) {
+    // Reduction length known at compile time, three LDS buffers: straight-line
+    // code, activations and weights both two chunks ahead.  Issue order of
+    // vector-memory operations (A = this wavefront's ND activation loads of a
+    // chunk, W = its NW weight loads):
+    //   A(0) W(0) A(1) W(1) | step 0: A(2) W(2) | step 1: A(3) W(3) | ...
+    // They complete in order, so "at most ND + NW outstanding" at the top of
+    // step c means A(c) and W(c) have landed while chunk c+1 is still in flight.
+    // A(c+2) overwrites the buffer chunk c-1 was read from; the barrier of step
+    // c comes after everybody's reads of it.
+    static_assert(ND + NW <= 63, "wait count must fit the counter");
     dma(0, S0{});
-    if constexpr (NCH > 1) loadw(1, S1{});
+    loadw(0, S0{});
+    if constexpr (NCH > 1) {
+      dma(1, S1{});
+      loadw(1, S1{});
+    }
     static_for(std::make_integer_sequence<int, NCH>{}, [&](auto cc) {
       constexpr int c = decltype(cc)::value;
-      typedef std::integral_constant<int, c % 3> Stage;
-      typedef std::integral_constant<int, c % 2> Buf;
-      if constexpr (c + 1 < NCH) wait_weights<8>(aw0[c % 3], aw1[c % 3]);
+      typedef std::integral_constant<int, c % 3> Cur;
+      typedef std::integral_constant<int, (c + 2) % 3> Nxt;
+      if constexpr (c + 1 < NCH) wait_weights<ND + NW>(aw0[c % 3], aw1[c % 3]);
       else wait_weights<0>(aw0[c % 3], aw1[c % 3]);
       __builtin_amdgcn_s_barrier();
-      if constexpr (c + 1 < NCH) dma(c + 1, std::integral_constant<int, (c + 1) % 2>{});
-      if constexpr (c + 2 < NCH) loadw(c + 2, std::integral_constant<int, (c + 2) % 3>{});
-      compute(Buf{}, Stage{});
+      if constexpr (c + 2 < NCH) {
+        dma(c + 2, Nxt{});
+        loadw(c + 2, Nxt{});
+      }
+      compute(Cur{}, Cur{});
     });
   } else {
     // Any reduction length: two stages.  Step c: everything this wavefront asked
@@ -801,6 +837,13 @@ __device__ __forceinline__ void dma_stream_gemm(const uint16_t* a0, const uint16
   __builtin_amdgcn_s_barrier();  // nobody still reads a buffer the next pass refills
 }
 
+// Every pass works in buffers of 16 KB: up to 64 token rows with chunks of 128
+// reduction elements, or up to 128 rows with chunks of 64.  Three buffers when
+// the reduction length is a compile-time constant (48 KB: three workgroups per
+// compute unit), else two.
+constexpr int kLdsBufElems = 8192;
+__host__ __device__ constexpr int lds_elems(int kd) { return (kd > 0 ? 3 : 2) * kLdsBufElems; }
+
 // Which expert and which pairs a workgroup works on (as Task), shared by the two kernels.
 template <bool DOWN>
 __device__ __forceinline__ bool lds_task(const FfnArgs& a, int per_expert, int& group, Task& t,
@@ -820,14 +863,14 @@ __device__ __forceinline__ bool lds_task(const FfnArgs& a, int per_expert, int& 
 }
 
 // MAXNT = token tiles per workgroup pass (the LDS buffer holds 16*MAXNT rows);
-// LW = wavefronts per workgroup; NCH = reduction length / 128 when the host
-// knows it to be one of the unrolled cases, else 0.  blockIdx.y picks every gridDim.y-th group of
+// LW = wavefronts per workgroup; KD = the reduction length when the host knows
+// it to be one of the unrolled cases, else 0.  blockIdx.y picks every gridDim.y-th group of
 // 16*MAXNT pairs of the expert: an expert with more pairs than one pass holds
 // is spread over several workgroups (its weights are then read once per pass).
-template <bool PACKED, int MAXNT, int LW, int NCH>
-__global__ __launch_bounds__(LW* kWave, 2) void gateup_lds_kernel(FfnArgs a) {
+template <bool PACKED, int MAXNT, int LW, int KD>
+__global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void gateup_lds_kernel(FfnArgs a) {
   constexpr int kRows = 16 * MAXNT;
-  __shared__ __align__(16) uint16_t lds[2 * kRows * 128];
+  __shared__ __align__(16) uint16_t lds[lds_elems(KD)];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   Task t;
@@ -860,8 +903,9 @@ __global__ __launch_bounds__(LW* kWave, 2) void gateup_lds_kernel(FfnArgs a) {
         accg[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         accu[i] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
-      dma_stream_gemm<NT, kRows, PACKED, LW, NCH>(gp, up, wlo, wave, a.D, rows, x, row_off, lds,
-                                                  accg, accu);
+      constexpr int KC = NT <= 4 ? 128 : 64;  // rows * KC = one 16 KB buffer
+      dma_stream_gemm<NT, kLdsBufElems / KC, PACKED, LW, KC, KD>(gp, up, wlo, wave, a.D, rows, x,
+                                                                 row_off, lds, accg, accu);
       if (!active) return;
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
@@ -882,10 +926,10 @@ __global__ __launch_bounds__(LW* kWave, 2) void gateup_lds_kernel(FfnArgs a) {
   }
 }
 
-template <bool PACKED, int MAXNT, int LW, int NCH>
-__global__ __launch_bounds__(LW* kWave, 2) void down_lds_kernel(FfnArgs a) {
+template <bool PACKED, int MAXNT, int LW, int KD>
+__global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void down_lds_kernel(FfnArgs a) {
   constexpr int kRows = 16 * MAXNT;
-  __shared__ __align__(16) uint16_t lds[2 * kRows * 128];
+  __shared__ __align__(16) uint16_t lds[lds_elems(KD)];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   Task t;
@@ -917,8 +961,9 @@ __global__ __launch_bounds__(LW* kWave, 2) void down_lds_kernel(FfnArgs a) {
         acc0[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         acc1[i] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
-      dma_stream_gemm<NT, kRows, PACKED, LW, NCH>(p0, p1, wlo, wave, F, rows, h, row_off, lds,
-                                                  acc0, acc1);
+      constexpr int KC = NT <= 4 ? 128 : 64;
+      dma_stream_gemm<NT, kLdsBufElems / KC, PACKED, LW, KC, KD>(p0, p1, wlo, wave, F, rows, h,
+                                                                 row_off, lds, acc0, acc1);
       if (!active) return;
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
@@ -1326,54 +1371,51 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     else if (maxnt <= 8) DES_LAUNCH_FFN(8, PK);                                             \
     else DES_LAUNCH_FFN(16, PK);                                                            \
   } while (0)
-    static const int lds_min_t = getenv("DES_LDS_MIN_T") ? atoi(getenv("DES_LDS_MIN_T")) : 32;
     const bool chunked = a.D % kKC == 0 && a.F % kKC == 0 && a.Fs % kKC == 0;
-    if (a.T > lds_min_t && chunked && !fused_requested) {
-      // larger blocks: activations staged through LDS, four wavefronts per expert group
-      // token rows per workgroup pass: 64 while no expert can have more, else 128;
-      // an expert with more pairs is spread over grid.y (at most 8 ways)
+    if (a.T > 32 && chunked && !fused_requested) {
+      // Larger blocks: activations staged through LDS.  Token rows per workgroup
+      // pass: 64 while no expert can have more, else 128; an expert with more
+      // pairs is spread over grid.y (at most 8 ways).  Wavefronts per workgroup:
+      // two give the finest spread of the weight bytes over the compute units;
+      // four share the staged activations among more weight rows, which
+      // measured better once experts have many tokens (48-layer stack: 7.7 ms
+      // against 8.0 ms; down projection at T = 128: 23 us against 27 us).
       const bool small = a.T <= 64;
       const int rows_pass = small ? 64 : 128;
       int splits = (a.T + rows_pass - 1) / rows_pass;
       if (splits > 8) splits = 8;
-      static const int lw_env = getenv("DES_LDS_WAVES") ? atoi(getenv("DES_LDS_WAVES")) : 2;
-      const int lw = lw_env;
-      const int gu_lds = a.n_slots * ((a.F / 16 + lw - 1) / lw) + (a.Fs / 16 + lw - 1) / lw;
-      const int per_dn = (a.D / 32 + lw - 1) / lw;
+      const int gu_lw = a.T <= 128 ? 2 : 4;
+      const int dn_lw = a.T <= 64 ? 2 : 4;
+      const int gu_lds = a.n_slots * ((a.F / 16 + gu_lw - 1) / gu_lw) + (a.Fs / 16 + gu_lw - 1) / gu_lw;
+      const int per_dn = (a.D / 32 + dn_lw - 1) / dn_lw;
       const int dn_lds = a.n_slots * per_dn + (a.Fs > 0 ? per_dn : 0);
-      const dim3 gg(gu_lds, splits), dg(dn_lds, splits), lb(lw * kWave);
+      const dim3 gg(gu_lds, splits), dg(dn_lds, splits);
       // unrolled reduction lengths (the shared expert shares the down launch)
-      const int gu_nch = a.D == 2048 ? 16 : 0;
-      const int dn_nch = (a.Fs != 0 && a.Fs != a.F) ? 0 : a.F == 768 ? 6 : a.F == 512 ? 4 : 0;
+      const int gu_kd = a.D == 2048 ? 2048 : 0;
+      const int dn_kd = (a.Fs != 0 && a.Fs != a.F) ? 0 : (a.F == 768 || a.F == 512) ? a.F : 0;
 #define DES_LAUNCH_GU(PK, MNT, LWV)                                                         \
   do {                                                                                      \
-    if (gu_nch == 16) launch(kKGateUp, gateup_lds_kernel<PK, MNT, LWV, 16>, gg, lb, 0, st, a); \
+    const dim3 lb(LWV* kWave);                                                              \
+    if (gu_kd == 2048) launch(kKGateUp, gateup_lds_kernel<PK, MNT, LWV, 2048>, gg, lb, 0, st, a); \
     else launch(kKGateUp, gateup_lds_kernel<PK, MNT, LWV, 0>, gg, lb, 0, st, a);            \
   } while (0)
 #define DES_LAUNCH_DN(PK, MNT, LWV)                                                         \
   do {                                                                                      \
-    if (dn_nch == 6) launch(kKDown, down_lds_kernel<PK, MNT, LWV, 6>, dg, lb, 0, st, a);    \
-    else if (dn_nch == 4) launch(kKDown, down_lds_kernel<PK, MNT, LWV, 4>, dg, lb, 0, st, a); \
+    const dim3 lb(LWV* kWave);                                                              \
+    if (dn_kd == 768) launch(kKDown, down_lds_kernel<PK, MNT, LWV, 768>, dg, lb, 0, st, a); \
+    else if (dn_kd == 512) launch(kKDown, down_lds_kernel<PK, MNT, LWV, 512>, dg, lb, 0, st, a); \
     else launch(kKDown, down_lds_kernel<PK, MNT, LWV, 0>, dg, lb, 0, st, a);                \
-  } while (0)
-#define DES_LAUNCH_LDS2(PK, LWV)                                                  \
-  do {                                                                            \
-    if (small) {                                                                  \
-      DES_LAUNCH_GU(PK, 4, LWV);                                                  \
-      DES_LAUNCH_DN(PK, 4, LWV);                                                  \
-    } else {                                                                      \
-      DES_LAUNCH_GU(PK, 8, LWV);                                                  \
-      DES_LAUNCH_DN(PK, 8, LWV);                                                  \
-    }                                                                             \
   } while (0)
 #define DES_LAUNCH_LDS(PK)                                                        \
   do {                                                                            \
-    if (lw == 4) DES_LAUNCH_LDS2(PK, 4);                                          \
-    else DES_LAUNCH_LDS2(PK, 2);                                                  \
+    if (small) DES_LAUNCH_GU(PK, 4, 2);                                           \
+    else if (gu_lw == 2) DES_LAUNCH_GU(PK, 8, 2);                                 \
+    else DES_LAUNCH_GU(PK, 8, 4);                                                 \
+    if (small) DES_LAUNCH_DN(PK, 4, 2);                                           \
+    else DES_LAUNCH_DN(PK, 8, 4);                                                 \
   } while (0)
       if (packed) DES_LAUNCH_LDS(true);
       else DES_LAUNCH_LDS(false);
-#undef DES_LAUNCH_LDS2
 #undef DES_LAUNCH_GU
 #undef DES_LAUNCH_DN
 #undef DES_LAUNCH_LDS
