@@ -34,8 +34,8 @@ HBM_PEAK_GBS = 8000.0
 # launch (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size); the
 # summaries are under profiles/.  None until measured for a workload/layout.
 MEASURED_TRAFFIC = {
-    # profiles/hbm_traffic_m128_zipf_vote_c32_packed.txt: 202,582,016 B read + 393,216 B written
-    ("m128_zipf", "vote", "packed"): 202582016 + 393216,
+    # profiles/hbm_traffic_m128_zipf_vote_c32_packed.txt: 202,574,600 B read + 393,216 B written
+    ("m128_zipf", "vote", "packed"): 202574600 + 393216,
 }
 
 
