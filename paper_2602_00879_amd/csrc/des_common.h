@@ -105,9 +105,22 @@ inline size_t ffn_o_flags(const des_shape_t& s) {
 
 constexpr int kSlotToks = 32;  // tokens per slot kept in the slot-major token table
 
+// The selector workgroup (1024 threads) gives a token max(4, next power of two of
+// ceil(M/8)) lanes, so it handles this many tokens at once; longer sequences are
+// spread over up to kMaxSelGroups selector workgroups (all sequences together),
+// which exchange their election partials through the workspace.
+constexpr int kMaxSelGroups = 64;
+constexpr int kSelPartStride = 512;  // 32-bit words per partial array (M <= 512)
+inline int selector_tokens_per_pass(int n_experts) {
+  int lanes = (n_experts + 7) / 8, lpt = 4;
+  while (lpt < lanes) lpt *= 2;
+  return 1024 / lpt;
+}
+
 // All offsets in bytes from the (256-byte aligned) workspace base.
 struct WsLayout {
-  size_t flags;     // u64   [router tiles + B]  epoch flags of the routing launch
+  size_t flags;     // u64   [router tiles + 2 * max(B, kMaxSelGroups)]  epoch flags of the routing launch
+  size_t sel_part;  // u32   [kMaxSelGroups][3][kSelPartStride]  selectors' election partials
   size_t ffn_flags; // u64   [ffn_h_flags + ffn_o_flags]  cleared by the routing launch
   size_t slot_of;   // int32 [M]       slot of each live expert
   size_t slot_tok;  // u16   [n_slots][kSlotToks]  tokens of each slot's first pairs
@@ -132,7 +145,9 @@ inline WsLayout ws_layout(const des_shape_t& s) {
   const size_t tiles = static_cast<size_t>((s.n_experts + 15) / 16) * ((T + 15) / 16);
   WsLayout w;
   size_t p = 0;
-  w.flags = p;    p = align256(p + 8 * (tiles + s.n_seqs));
+  const size_t nsel = static_cast<size_t>(s.n_seqs) > kMaxSelGroups ? s.n_seqs : kMaxSelGroups;
+  w.flags = p;    p = align256(p + 8 * (tiles + 2 * nsel));
+  w.sel_part = p; p = align256(p + 4 * static_cast<size_t>(kMaxSelGroups) * 3 * kSelPartStride);
   w.ffn_flags = p; p = align256(p + 8 * (ffn_h_flags(s) + ffn_o_flags(s)));
   w.slot_of = p;  p = align256(p + 4 * static_cast<size_t>(s.n_experts));
   w.slot_tok = p; p = align256(p + 2 * static_cast<size_t>(max_live_experts(s)) * kSlotToks);

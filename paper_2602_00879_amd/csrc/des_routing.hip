@@ -9,8 +9,8 @@
 // kernel whose workgroups take one of three roles, chained through per-producer
 // flags in device memory instead of kernel boundaries:
 //   role R (one per 16x16 logits tile)  router GEMM tile, then flag[tile] = epoch
-//   role S (one per sequence)           waits for the R flags, elects the coreset,
-//                                       re-routes, then flag[seq] = epoch
+//   role S (one per sequence, or one    waits for the R flags, elects the coreset,
+//           per group of its tokens)    re-routes, then flag[seq] = epoch
 //   role P (one, merged into S if B==1) waits for the S flags, builds counts,
 //                                       offsets, the slot table and the permutation
 // A flag is a 64-bit word that a producer sets to the call's epoch (a host
@@ -62,13 +62,16 @@ struct RoutingArgs {
   int32_t* meta;          // [8]: [0] live experts, [1] routed pairs
   int32_t* pair_tok;      // [T*K] token of each sorted pair
   int32_t* pos;           // [T*K] sorted position of pair (t*K+j), -1 = unused slot
-  unsigned long long* flags;  // [n_tiles + B] epoch flags
+  unsigned long long* flags;  // [n_tiles + 2*B*groups] epoch flags: router tiles, selector
+                              // partials published, selectors done
+  uint32_t* sel_part;         // [B*groups][3][kSelPartStride] per-group election partials
   unsigned long long epoch;
   unsigned long long* ffn_flags;  // readiness flags of the FFN launch, cleared here
   int n_ffn_flags;
   int32_t* slot_of;       // [M] slot of each live expert, -1 otherwise
   uint16_t* slot_tok;     // [n_slots][kSlotToks] tokens of each slot's first pairs
   int B, N, M, K, C, k_seq, mode, cap, D, n_slots;
+  int groups;             // selector workgroups per sequence (each takes every groups-th pass)
   int tiles_m, tiles_t;   // router tiles along experts / tokens
   int do_router, do_select, do_permute, use_flags, bf16;
 };
@@ -301,7 +304,7 @@ __device__ __forceinline__ uint32_t row_draw(const Head& hd, bool& mine) {
 // code into the instruction cache while it waits for the router tiles (every
 // index below derives from lane and slot numbers, never from the data read).
 template <int LPT>
-__device__ void select_sequence(const RoutingArgs& a, int b, char* smem, bool dry) {
+__device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, bool dry) {
   using L = SelLds<LPT>;
   constexpr int MP = L::MP;
   constexpr int RPW = 64 / LPT;          // rows (tokens) per wave
@@ -322,7 +325,8 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem, bool dr
   const int N = a.N, M = a.M, K = a.K;
   const float* Lg = a.logits + static_cast<size_t>(b) * N * M;
   uint32_t* my_sorted = s_sorted + wave * (kEpl * 64) + lane;  // [s * 64]
-  const bool single_pass = N <= TPP;
+  const int G = a.groups;
+  const bool single_pass = N <= G * TPP;  // this workgroup sees each of its tokens once
 
   for (int e = threadIdx.x; e < MP; e += kRtThreads) {
     s_level[e] = K;
@@ -368,7 +372,7 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem, bool dr
 #pragma unroll
     for (int j = 0; j < kEpl; ++j) vacc[j] = 0.f;
 
-    for (int n0 = 0; n0 + wave * RPW < N; n0 += TPP) {  // fixed token order per row
+    for (int n0 = g * TPP; n0 + wave * RPW < N; n0 += G * TPP) {  // fixed token order per row
       float val[kEpl], p[kEpl];
       uint32_t key[kEpl];
       load_sort(n0 + slot, val, key);
@@ -427,14 +431,64 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem, bool dr
     __syncthreads();
     DES_STAMP(a, 11);
 
-    if (vote) {
-      for (int e = threadIdx.x; e < MP; e += kRtThreads) {
+    if (vote) {  // this workgroup's votes: waves in order
+      float vloc[(MP + kRtThreads - 1) / kRtThreads];
+      int q = 0;
+      for (int e = threadIdx.x; e < MP; e += kRtThreads, ++q) {
         float v = 0.f;
 #pragma unroll
         for (int w = 0; w < kRtWaves; ++w) v += s_vpart[w * MP + e];
+        vloc[q] = v;
+      }
+      __syncthreads();
+      q = 0;
+      for (int e = threadIdx.x; e < MP; e += kRtThreads, ++q) s_vpart[e] = vloc[q];
+      __syncthreads();
+    }
+    if (G > 1) {
+      // The sequence's tokens are spread over G workgroups: each publishes what
+      // its tokens contributed (votes, best nomination rank, top-1 nominations),
+      // waits for the others and combines all G records in group order, so every
+      // workgroup of the sequence elects the same coreset from the same numbers.
+      // The records travel with device-scope accesses, like the logits.
+      uint32_t* mine = a.sel_part + static_cast<size_t>(b * G + g) * 3 * kSelPartStride;
+      for (int e = threadIdx.x; e < MP; e += kRtThreads) {
+        __hip_atomic_store(mine + e, __float_as_uint(vote ? s_vpart[e] : 0.f), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(mine + kSelPartStride + e, static_cast<uint32_t>(s_level[e]),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(mine + 2 * kSelPartStride + e, static_cast<uint32_t>(s_cnt1[e]),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's stores have been acknowledged
+      __syncthreads();
+      unsigned long long* pf = a.flags + a.tiles_m * a.tiles_t + b * G;
+      if (threadIdx.x == 0) flag_publish(pf + g, a.epoch, false);
+      if (!flags_wait(pf, G, a.epoch, false)) return false;
+      for (int e = threadIdx.x; e < MP; e += kRtThreads) {
+        float v = 0.f;
+        int lvl = K, c1 = 0;
+        for (int gg = 0; gg < G; ++gg) {
+          const uint32_t* rec = a.sel_part + static_cast<size_t>(b * G + gg) * 3 * kSelPartStride;
+          v += __uint_as_float(__hip_atomic_load(rec + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+          lvl = min(lvl, static_cast<int>(__hip_atomic_load(rec + kSelPartStride + e, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT)));
+          c1 += static_cast<int>(__hip_atomic_load(rec + 2 * kSelPartStride + e, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT));
+        }
+        s_vpart[e] = v;
+        s_level[e] = lvl;
+        s_cnt1[e] = c1;
+      }
+      __syncthreads();
+    }
+
+    if (vote) {
+      for (int e = threadIdx.x; e < MP; e += kRtThreads) {
+        const float v = s_vpart[e];
         const bool nominated = e < M && s_level[e] < K;
         s_key[e] = nominated ? order_key(v) : 0u;
-        if (a.votes && e < M && !dry) a.votes[static_cast<size_t>(b) * M + e] = v;
+        if (a.votes && e < M && !dry && g == 0) a.votes[static_cast<size_t>(b) * M + e] = v;
       }
       if (threadIdx.x == 0) s_hist[33] = 0;
     } else if (a.k_seq > 0) {  // Eq. 5 with the caller's k
@@ -499,28 +553,28 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem, bool dr
       const bool f = e < MP && s_core[e] != 0;
       const unsigned long long bal = __ballot(f);
       const int pre = __popcll(bal & ((1ull << lane) - 1ull));
-      if (f && base + pre < a.cap && !dry) out[base + pre] = e;
+      if (f && base + pre < a.cap && !dry && g == 0) out[base + pre] = e;
       base += __popcll(bal);
     }
-    if (!dry)
+    if (!dry && g == 0)
       for (int i = base + lane; i < a.cap; i += 64) out[i] = -1;
     if (lane == 0) {
       s_hist[34] = base;
-      if (!dry) {
+      if (!dry && g == 0) {
         a.coreset_size[b] = base;
         if (a.k_seq_used) a.k_seq_used[b] = (a.mode == DES_SEQ) ? s_hist[33] : 0;
       }
     }
   }
   __syncthreads();
-  if (a.topk_idx == nullptr) return;
+  if (a.topk_idx == nullptr) return true;
 
   DES_STAMP(a, 4);
   // ------------------------------ stage 2: constrained local routing + gates
   const int keff = min(K, s_hist[34]);
   const bool reuse_sort = single_pass && a.mode != DES_VANILLA;  // stage 1 sorted this token
 
-  for (int n0 = 0; n0 + wave * RPW < N; n0 += TPP) {
+  for (int n0 = g * TPP; n0 + wave * RPW < N; n0 += G * TPP) {
     const int n = n0 + slot;
     const bool live = n < N && !dry;
     if (!reuse_sort) {
@@ -575,6 +629,7 @@ __device__ void select_sequence(const RoutingArgs& a, int b, char* smem, bool dr
       }
     }
   }
+  return true;
 }
 
 // ----------------------------------------------------- role P: permutation
@@ -692,8 +747,9 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
     return;
   }
   blk -= n_tiles;
-  const int n_sel = a.do_select ? a.B : 0;
+  const int n_sel = a.do_select ? a.B * a.groups : 0;
   const int all_tiles = a.tiles_m * a.tiles_t;
+  const int n_flags = all_tiles + 2 * a.B * a.groups;
   if (blk < n_sel) {  // ---- role S
     DES_STAMP(a, 0);
     if (a.use_flags && a.do_router && !flags_wait(a.flags, all_tiles, a.epoch, false)) {
@@ -701,10 +757,13 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
       return;
     }
     DES_STAMP(a, 1);
-    select_sequence<LPT>(a, blk, smem, false);
+    if (!select_sequence<LPT>(a, blk / a.groups, blk % a.groups, smem, false)) {
+      if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
+      return;
+    }
     DES_STAMP(a, 5);
     if (a.topk_idx == nullptr) return;
-    if (a.B == 1 && a.do_permute) {  // single sequence: permute right here
+    if (n_sel == 1 && a.do_permute) {  // a single selector: permute right here
       // same workgroup, same compute unit: the barrier orders the topk_idx
       // stores before the loads below, no device-scope fence needed
       __syncthreads();
@@ -714,24 +773,25 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
       // every flag of this call has been consumed: clear them, so that a replay
       // of a captured launch (same epoch) cannot be satisfied by stale flags
       if (a.use_flags)
-        for (int i = threadIdx.x; i < all_tiles + a.B; i += kRtThreads) a.flags[i] = 0ull;
+        for (int i = threadIdx.x; i < n_flags; i += kRtThreads) a.flags[i] = 0ull;
       return;
     }
     if (a.use_flags) {
       __syncthreads();
-      if (threadIdx.x == 0) flag_publish(a.flags + all_tiles + blk, a.epoch, true);
+      if (threadIdx.x == 0) flag_publish(a.flags + all_tiles + n_sel + blk, a.epoch, true);
     }
     return;
   }
   blk -= n_sel;
-  if (blk == 0 && a.do_permute && a.B > 1) {  // ---- role P
-    if (a.use_flags && a.do_select && !flags_wait(a.flags + all_tiles, a.B, a.epoch, true)) {
+  if (blk == 0 && a.do_permute && a.B * a.groups > 1) {  // ---- role P
+    if (a.use_flags && a.do_select &&
+        !flags_wait(a.flags + all_tiles + a.B * a.groups, a.B * a.groups, a.epoch, true)) {
       if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
       return;
     }
     permute_all(a, smem);
-    if (a.use_flags)  // all selectors have consumed the router flags and published theirs
-      for (int i = threadIdx.x; i < all_tiles + a.B; i += kRtThreads) a.flags[i] = 0ull;
+    if (a.use_flags)  // all selectors have consumed the other flags and published theirs
+      for (int i = threadIdx.x; i < n_flags; i += kRtThreads) a.flags[i] = 0ull;
   }
 }
 
@@ -788,6 +848,7 @@ static void fill_common(RoutingArgs& a, const des_shape_t& s) {
   a.tiles_m = (s.n_experts + 15) / 16;
   a.tiles_t = (s.n_seqs * s.n_tokens + 15) / 16;
   a.bf16 = s.dtype == DES_BF16;
+  a.groups = 1;
 }
 
 int launch_router(const des_shape_t& s, const void* x, const void* w_router, const float* bias,
@@ -839,11 +900,19 @@ int launch_routing(const des_shape_t& s, const void* x, const void* w_router, co
   a.n_ffn_flags = static_cast<int>(ffn_h_flags(s) + ffn_o_flags(s));
   a.slot_of = reinterpret_cast<int32_t*>(ws + w.slot_of);
   a.slot_tok = reinterpret_cast<uint16_t*>(ws + w.slot_tok);
+  a.sel_part = reinterpret_cast<uint32_t*>(ws + w.sel_part);
   const int n_tiles = a.tiles_m * a.tiles_t;
-  const int roles = n_tiles + a.B + (a.B > 1 ? 1 : 0);
   int fused_limit = device_compute_units();
   if (fused_limit > kMaxFusedRoutingBlocks) fused_limit = kMaxFusedRoutingBlocks;
+  // A selector workgroup handles selector_tokens_per_pass() tokens at once; a
+  // longer sequence is spread over several selector workgroups when they all fit.
+  const int tpp = selector_tokens_per_pass(s.n_experts);
+  int groups = (s.n_tokens + tpp - 1) / tpp;
+  if (groups > kMaxSelGroups / a.B) groups = kMaxSelGroups / a.B > 0 ? kMaxSelGroups / a.B : 1;
+  if (n_tiles + a.B * groups + 1 > fused_limit) groups = 1;
+  const int roles = n_tiles + a.B * groups + (a.B * groups > 1 ? 1 : 0);
   if (roles <= fused_limit) {  // all workgroups resident at once: one launch
+    a.groups = groups;
     a.do_router = a.do_select = a.do_permute = 1;
     a.use_flags = 1;
     return launch_routing_grid(a, roles, kKRouting, st);

@@ -130,6 +130,11 @@ MID = dict(
     lds_64=W.LayerConfig("lds_64", "bf16", 1, 48, 256, 12, 128, 0, 4, 5, 1.1, 16),
     lds_128=W.LayerConfig("lds_128", "bf16", 1, 80, 256, 12, 128, 128, 4, 5, 1.1, 17),
     lds_split=W.LayerConfig("lds_split", "bf16", 3, 70, 384, 8, 256, 0, 2, 2, 1.1, 18),
+    # 100 experts -> a selector workgroup takes 64 tokens at once: each of the two
+    # sequences of 150 tokens is spread over three selector workgroups (the last one
+    # ragged) that exchange their election partials; under DES-Seq one sequence fits
+    # k=1 and the other overflows even at k=1 (top-1 nomination counts decide)
+    sel_groups=W.LayerConfig("sel_groups", "bf16", 2, 150, 256, 100, 32, 0, 4, 16, 0.3, 19),
 )
 
 
