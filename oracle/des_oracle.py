@@ -15,6 +15,8 @@ one passage of the paper:
   coreset_seq          Eq. 5 / Alg. 2  (DES-Seq)
   coreset_vote         Eq. 6 / Alg. 3  (DES-Vote)
   constrained_topk     Alg. 1, stage 2, S_n
+  cumulative_skip      Sec. 5.1, Baselines: the adapted NAEE rule (skip the bottom
+                       experts whose cumulative probability is below beta)
   gates                Alg. 1, stage 2, g_n   (sigma = softmax, i.e. Eq. 1's
                        normalisation by the selected sum)
   expert_ffn           E_i(x): SwiGLU sub-network (form fixed by the workload)
@@ -33,6 +35,13 @@ the design notes of the repository):
     the coreset may be smaller than C;
   * a token uses k_eff = min(K, |coreset|) experts; unused slots carry
     index -1 and weight 0;
+  * k_route (Sec. 5.3, "Effect of active expert count"): the coreset is elected
+    with the model's K, then each token uses only its k_route < K best coreset
+    experts; gates are normalised over those;
+  * cumulative_skip: experts i..k (rank order) are dropped when the sum of their
+    gates is below beta times the sum of all k gates (strictly); the largest such
+    suffix is taken, the best expert always stays, and the surviving gates are
+    re-normalised over the survivors (the normalisation of Eq. 1);
   * DES-Seq with k_seq == 0 picks the largest k' <= K whose union has at most C
     members; if even k' = 1 overflows, the C most often top-1-nominated experts
     are kept (ties to the lowest index).
@@ -40,6 +49,7 @@ the design notes of the repository):
 Pins: tests/test_oracle_pins.py (brute force over subsets, a hand-worked
 3-token x 5-expert example, the closed form for uniform routing, Table 1's
 rounding, reductions to a plain numpy MLP and to a dense one-hot einsum,
+the skipping rule on hand-computed gates and against enumeration of every cut,
 and the invariants the method fixes).  The token-level statistics the paper
 reports on trained routers (hit-rate cosine similarity, accuracy) are
 "parity unpinned": they need trained weights.
@@ -202,6 +212,27 @@ def gates(row: Sequence[float], selected: Sequence[int]) -> np.ndarray:
     return e / e.sum()
 
 
+def cumulative_skip(g: np.ndarray, beta: float) -> Tuple[int, float]:
+    """Sec. 5.1 (Baselines), the adapted NAEE rule on one token's gates g (rank
+    order, best first): skip experts i..k when sum_{u=i..k} g_u < beta * sum_u g_u.
+    Returns (number of experts kept, margin), margin = the smallest relative
+    distance |suffix - beta * total| / total over all cuts (how close the
+    decision came to flipping)."""
+    g = np.asarray(g, dtype=np.float64)
+    k = len(g)
+    if k == 0 or beta <= 0.0:
+        return k, math.inf
+    total = float(g.sum())
+    keep, margin = k, math.inf
+    suffix = 0.0
+    for i in range(k - 1, 0, -1):          # the best expert (i = 0) is never skipped
+        suffix += float(g[i])
+        margin = min(margin, abs(suffix - beta * total) / total)
+        if suffix < beta * total:
+            keep = i
+    return keep, margin
+
+
 # --------------------------------------------------------------------------
 # Experts
 # --------------------------------------------------------------------------
@@ -233,21 +264,30 @@ class _F64Cache:
 # --------------------------------------------------------------------------
 # The layer (Alg. 1)
 # --------------------------------------------------------------------------
-def route_block(logits: np.ndarray, mode: str, K: int, C: int, k_seq: int = 0) -> Dict[str, object]:
+def route_block(logits: np.ndarray, mode: str, K: int, C: int, k_seq: int = 0,
+                k_route: int = 0, skip_beta: float = 0.0) -> Dict[str, object]:
     """Routing part of Alg. 1 for ONE sequence given its logits [N, M]:
-    coreset, per-token S_n (rank order, padded with -1) and gates (padded 0)."""
+    coreset, per-token S_n (rank order, padded with -1) and gates (padded 0).
+    k_route > 0: a token uses only its k_route best coreset experts (the
+    election still uses K).  skip_beta > 0: cumulative_skip on every token."""
     logits = np.asarray(logits, dtype=np.float64)
     N, M = logits.shape
     sel = select_coreset(logits, mode, K, C, k_seq)
     core = sel["coreset"]
     idx = -np.ones((N, K), dtype=np.int32)
     w = np.zeros((N, K), dtype=np.float64)
+    skip_margin = math.inf
     for n in range(N):
-        s_n = constrained_topk(logits[n], core, K)
+        s_n = constrained_topk(logits[n], core, k_route if k_route > 0 else K)
         g_n = gates(logits[n], s_n)
+        if skip_beta > 0.0:
+            keep, m = cumulative_skip(g_n, skip_beta)
+            skip_margin = min(skip_margin, m)
+            s_n = s_n[:keep]
+            g_n = gates(logits[n], s_n)
         idx[n, :len(s_n)] = s_n
         w[n, :len(s_n)] = g_n
-    sel.update(topk_idx=idx, topk_w=w)
+    sel.update(topk_idx=idx, topk_w=w, skip_margin=skip_margin)
     return sel
 
 
@@ -257,7 +297,8 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
                 shared: Optional[Tuple[np.ndarray, np.ndarray, np.ndarray]] = None,
                 logits_override: Optional[np.ndarray] = None,
                 compute_y: bool = True, residual: bool = False,
-                only_tokens: Optional[Sequence[Tuple[int, int]]] = None) -> Dict[str, object]:
+                only_tokens: Optional[Sequence[Tuple[int, int]]] = None,
+                k_route: int = 0, skip_beta: float = 0.0) -> Dict[str, object]:
     """Alg. 1 for B independent sequences.
 
     x: [B, N, D].  w_router [M, D]; w_gate, w_up [M, F, D]; w_down [M, D, F].
@@ -266,7 +307,7 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
     of computing them (the routing decisions are then a function of exactly
     these numbers).  Each sequence elects its own coreset.  only_tokens: compute
     y only for these (sequence, token) pairs (the rest of y stays NaN); routing
-    is always computed for every token.
+    is always computed for every token.  k_route, skip_beta: see route_block.
     """
     x = np.asarray(x)
     B, N, D = x.shape
@@ -283,8 +324,10 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
     votes: List[Optional[np.ndarray]] = []
     margins: List[float] = []
     k_seq_used: List[int] = []
+    skip_margin = math.inf
     for b in range(B):
-        r = route_block(logits[b], mode, K, C, k_seq)
+        r = route_block(logits[b], mode, K, C, k_seq, k_route, skip_beta)
+        skip_margin = min(skip_margin, r["skip_margin"])
         topk_idx[b], topk_w[b] = r["topk_idx"], r["topk_w"]
         coresets.append(r["coreset"])
         votes.append(r["votes"])
@@ -326,7 +369,7 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
                 y[b, n] = acc
     return dict(logits=logits, topk_idx=topk_idx, topk_w=topk_w, counts=counts,
                 n_unique=n_unique, coresets=coresets, votes=votes, margins=margins,
-                k_seq_used=k_seq_used, y=y)
+                k_seq_used=k_seq_used, y=y, skip_margin=skip_margin)
 
 
 def moe_stack_forward(x: np.ndarray, layers: Sequence[dict], K: int, C: int, mode: str,

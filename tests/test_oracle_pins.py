@@ -338,3 +338,77 @@ def test_workload_shapes_and_seeding():
     assert abs(float(a["w_gate"].std()) - 0.02) < 1e-3
     zb = W.zipf_bias(128, 1.1, np.random.default_rng(0))
     assert abs(float(zb.mean())) < 1e-5 and sorted(-zb)[1] - sorted(-zb)[0] == pytest.approx(1.1 * math.log(2), rel=1e-5)
+
+
+# ------------------------------------------- routing variants (Sec. 5.1 / 5.3)
+def test_cumulative_skip_hand_values():
+    """Sec. 5.1 (Baselines): experts i..K are skipped when their cumulative
+    probability is below beta of the total.  Gates 0.5 / 0.3 / 0.15 / 0.05:
+    beta = 0.1 -> only the last (0.05 < 0.1, but 0.05 + 0.15 = 0.2 is not);
+    beta = 0.25 -> the last two (0.2 < 0.25, 0.5 is not); beta = 0.6 -> three
+    (0.5 < 0.6); the best expert always stays."""
+    g = np.array([0.5, 0.3, 0.15, 0.05])
+    assert O.cumulative_skip(g, 0.0)[0] == 4
+    assert O.cumulative_skip(g, 0.1)[0] == 3
+    assert O.cumulative_skip(g, 0.25)[0] == 2
+    assert O.cumulative_skip(g, 0.6)[0] == 1
+    assert O.cumulative_skip(g, 0.999)[0] == 1
+    # scale invariance: "relative to the total routing sum"
+    assert O.cumulative_skip(7.0 * g, 0.25)[0] == 2
+    # the reported margin is the distance of the closest cut to the threshold
+    assert O.cumulative_skip(g, 0.1)[1] == pytest.approx(0.05)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_cumulative_skip_equals_enumeration_of_cuts(seed):
+    rng = np.random.default_rng(100 + seed)
+    k = int(rng.integers(1, 9))
+    g = np.sort(rng.random(k))[::-1].copy()
+    beta = float(rng.random()) * 0.9
+    total = g.sum()
+    valid = [i for i in range(1, k) if g[i:].sum() < beta * total]   # every admissible cut
+    want = min(valid) if valid else k                                  # the largest skipped suffix
+    keep, _ = O.cumulative_skip(g, beta)
+    assert keep == want
+    # monotone: a larger threshold never keeps more
+    assert O.cumulative_skip(g, min(0.95, beta + 0.05))[0] <= keep
+
+
+def test_k_route_keeps_the_coreset_and_truncates_each_token():
+    """Sec. 5.3 (effect of active expert count): same coreset, fewer experts per
+    token.  The election is unchanged, each token keeps the first k_route of
+    its K coreset experts (rank order), gates are normalised over those."""
+    L = W.make_logits(24, 40, seed=5, zipf_s=1.1)
+    full = O.route_block(L, "vote", 8, 12)
+    half = O.route_block(L, "vote", 8, 12, k_route=4)
+    assert half["coreset"] == full["coreset"]
+    assert np.array_equal(half["topk_idx"][:, :4], full["topk_idx"][:, :4])
+    assert np.all(half["topk_idx"][:, 4:] == -1) and np.all(half["topk_w"][:, 4:] == 0)
+    np.testing.assert_allclose(half["topk_w"].sum(axis=1), 1.0, atol=1e-12)
+    ratio = full["topk_w"][:, :4] / full["topk_w"][:, :4].sum(axis=1, keepdims=True)
+    np.testing.assert_allclose(half["topk_w"][:, :4], ratio, atol=1e-12)
+    # k_route = K is the default path
+    same = O.route_block(L, "vote", 8, 12, k_route=8)
+    assert np.array_equal(same["topk_idx"], full["topk_idx"])
+    # without a coreset, k_route = k is plain top-k routing (Table 1's "top-k" baseline)
+    van = O.route_block(L, "vanilla", 8, 40, k_route=4)
+    top4 = O.route_block(L, "vanilla", 4, 40)
+    assert np.array_equal(van["topk_idx"][:, :4], top4["topk_idx"])
+    np.testing.assert_allclose(van["topk_w"][:, :4], top4["topk_w"], atol=1e-12)
+
+
+def test_skip_in_route_block():
+    L = W.make_logits(16, 32, seed=9, zipf_s=1.1, scale=2.0)
+    base = O.route_block(L, "vanilla", 6, 32)
+    skp = O.route_block(L, "vanilla", 6, 32, skip_beta=0.15)
+    kept = (skp["topk_idx"] >= 0).sum(axis=1)
+    assert kept.min() >= 1 and kept.max() <= 6 and kept.min() < 6   # something was skipped
+    for n in range(16):
+        k = int(kept[n])
+        assert np.array_equal(skp["topk_idx"][n, :k], base["topk_idx"][n, :k])
+        g = base["topk_w"][n]
+        assert g[k:].sum() < 0.15 * g.sum() or k == 6                # the dropped tail is below beta
+        if k > 1:
+            assert g[k - 1:].sum() >= 0.15 * g.sum()                 # and no longer tail would be
+        np.testing.assert_allclose(skp["topk_w"][n, :k], g[:k] / g[:k].sum(), atol=1e-12)
+    assert skp["skip_margin"] > 0
