@@ -56,6 +56,13 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="block-length sweep N = 4..128, vanilla against DES-Vote C=32, and the "
                          "affine latency law of Eq. 2/3 fitted over the coreset size at N=32")
+    ap.add_argument("--k-route", type=int, default=0,
+                    help="experts per token inside the coreset (0 = K); Sec. 5.3 of the paper")
+    ap.add_argument("--skip-beta", type=float, default=0.0,
+                    help="cumulative-probability skipping threshold (0 = off); Sec. 5.1, Baselines")
+    ap.add_argument("--variants", action="store_true",
+                    help="routing variants on the 128-expert layer: top-k baseline, skipping, "
+                         "DES-Vote with k = 8 and k = 4 in the same coreset")
     ap.add_argument("--selection-only", action="store_true",
                     help="time coreset selection alone (one fused HIP launch) beside the same "
                          "selection written with torch ops (Sec. 4.3 / Fig. 6 of the paper)")
@@ -83,6 +90,8 @@ def main():
         return bench_selection(args, torch, B, W, dev)
     if args.sweep:
         return bench_sweep(args, torch, B, W, dev)
+    if args.variants:
+        return bench_variants(args, torch, B, W, dev)
     if args.workload == "stack48":
         return bench_stack(args, torch, B, W, dev)
     cfg = W.CONFIGS[args.workload]
@@ -101,7 +110,8 @@ def main():
     packed = args.layout == "packed" and cfg.dtype == "bf16"
     layout = B.DES_LAYOUT_PACKED if packed else B.DES_LAYOUT_ROWMAJOR
     shape = B.make_shape(cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k, C,
-                         args.mode, cfg.dtype, ffn_shared=cfg.ffn_shared, weight_layout=layout)
+                         args.mode, cfg.dtype, ffn_shared=cfg.ffn_shared, weight_layout=layout,
+                         k_route=args.k_route, skip_beta=args.skip_beta)
     x = dev_t(layer["x"])
     w_router, bias = dev_t(layer["w_router"]), dev_t(layer["bias"])
 
@@ -216,7 +226,9 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: M={cfg.n_experts} D={cfg.hidden} F={cfg.ffn} "
                                f"Fs={cfg.ffn_shared} K={cfg.top_k} N={cfg.n_tokens} B={cfg.n_seqs} "
-                               f"mode={args.mode} C={C} zipf_s={cfg.zipf_s}",
+                               f"mode={args.mode} C={C} zipf_s={cfg.zipf_s}"
+                               + (f" k_route={args.k_route}" if args.k_route else "")
+                               + (f" skip_beta={args.skip_beta}" if args.skip_beta else ""),
                    "weight_layout": args.layout, "weight_replicas": len(replicas)},
         "n_unique_experts": n_unique,
         "unique_expert_bytes": unique_bytes,
@@ -373,6 +385,64 @@ def bench_sweep(args, torch, B, W, dev):
                         "t0_us": float(t0_fit), "b_us_per_expert": float(b_fit), "r2": r2,
                         "implied_GBps_per_expert_slope": per_expert / float(b_fit) / 1e3},
     }))
+
+
+def bench_variants(args, torch, B, W, dev):
+    """Routing variants that reuse the same FFN kernels, on the 128-expert layer
+    (N = 32): the top-k baseline (fewer experts per token, Table 1 of the paper),
+    cumulative-probability skipping (Sec. 5.1, Baselines), and DES-Vote with
+    k = 8 against k = 4 experts per token inside the same coreset (Sec. 5.3).
+    Latency and expert counts only: accuracy needs trained weights."""
+    cfg = W.CONFIGS["m128_zipf"]
+    layer = W.make_layer(cfg)
+
+    def dev_t(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    x, w_router, bias = dev_t(layer["x"]), dev_t(layer["w_router"]), dev_t(layer["bias"])
+    base = [B.des_pack_expert_weights(dev_t(layer[k])) for k in ("w_gate", "w_up", "w_down")]
+    torch.cuda.synchronize()
+    replicas = [base] + [[t.clone() for t in base] for _ in range(max(1, args.replicas) - 1)]
+    steps, warm = min(args.steps, 200), min(args.warmup, 20)
+    rows = []
+    for name, mode, k_route, beta in (("vanilla K=8", "vanilla", 0, 0.0),
+                                      ("top-k baseline k=4", "vanilla", 4, 0.0),
+                                      ("vanilla + skipping beta=0.1", "vanilla", 0, 0.1),
+                                      ("vanilla + skipping beta=0.2", "vanilla", 0, 0.2),
+                                      ("vanilla + skipping beta=0.3", "vanilla", 0, 0.3),
+                                      ("DES-Vote C=32 k=8", "vote", 0, 0.0),
+                                      ("DES-Vote C=32 k=4 (same coreset)", "vote", 4, 0.0),
+                                      ("DES-Vote C=32 + skipping beta=0.2", "vote", 0, 0.2)):
+        shape = B.make_shape(1, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k, cfg.coreset,
+                             mode, cfg.dtype, weight_layout=B.DES_LAYOUT_PACKED, k_route=k_route,
+                             skip_beta=beta)
+        bufs = B.MoeBuffers(shape, dev, x.dtype)
+
+        def step(i):
+            wg, wu, wd = replicas[i % len(replicas)]
+            B.des_moe_forward(shape, x, w_router, bias, wg, wu, wd, buffers=bufs)
+
+        for i in range(warm):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / steps
+        pairs = int((bufs.topk_idx >= 0).sum().cpu())
+        rows.append({"variant": name, "us": round(us, 2), "n_unique": int(bufs.n_unique.cpu()[0]),
+                     "routed_pairs": pairs, "experts_per_token": round(pairs / cfg.n_tokens, 2)})
+        print("# " + json.dumps(rows[-1]), file=sys.stderr, flush=True)
+    print(json.dumps({
+        "metric": "MoE-layer us per block under routing variants", "unit": "us/block", "n_gpus": 1,
+        "steps": steps, "warmup": warm, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"m128_zipf: M={cfg.n_experts} D={cfg.hidden} F={cfg.ffn} K={cfg.top_k} "
+                               f"N={cfg.n_tokens} zipf_s={cfg.zipf_s}", "weight_layout": "packed",
+                   "weight_replicas": len(replicas)},
+        "variants": rows}))
 
 
 def bench_stack(args, torch, B, W, dev):

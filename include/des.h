@@ -81,12 +81,25 @@ typedef struct {
   int32_t dtype;         /* des_dtype_t of x, w_router, expert weights and y       */
   int32_t weight_layout; /* des_layout_t of w_gate / w_up / w_down (+ shared)      */
   int32_t residual;      /* 1: y = x + MoE(x)  (layer inside a residual stack)     */
+  int32_t k_route;       /* experts a token finally uses (Alg. 1 stage 2) while the */
+                         /* election still uses K; 0 = K.  Sec. 5.3, "Effect of    */
+                         /* active expert count" (same coreset, k = 8 vs k = 4);   */
+                         /* in vanilla mode this is the plain top-k baseline       */
+  float skip_beta;       /* > 0: after stage 2, a token drops its experts i..k     */
+                         /* (rank order) when their gates sum to less than         */
+                         /* skip_beta of the sum of all k gates - the largest such */
+                         /* tail, never the best expert - and the gates are        */
+                         /* re-normalised over the rest (the adapted NAEE rule of  */
+                         /* Sec. 5.1, Baselines).  0 = off.  The comparison is in  */
+                         /* fp32; a tail within ~1e-6 (relative) of the threshold  */
+                         /* may fall either way                                    */
 } des_shape_t;
 
 /*
  * Limits checked by every entry point (DES_ERR_SHAPE otherwise):
  *   B, N, D, M, F, K >= 1;  K <= M;  K <= 32;  M <= 512;  B*N <= 4096;
  *   M * ceil(B*N/64) <= 4096;  C >= 1 in seq / vote mode;  0 <= k_seq <= K;
+ *   0 <= k_route <= K;  0 <= skip_beta < 1;
  *   seq mode with an explicit k_seq needs C >= min(M, N*k_seq) so that the
  *   union of Eq. 5 always fits the coreset_idx buffer;
  *   bf16: D, F, F_s multiples of 32 (matrix-core K step); fp32: multiples of 4.

@@ -32,7 +32,8 @@ EXPORTS = (
 class DesShape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "n_seqs", "n_tokens", "hidden", "n_experts", "ffn", "ffn_shared", "top_k", "coreset",
-        "k_seq", "mode", "dtype", "weight_layout", "residual")]
+        "k_seq", "mode", "dtype", "weight_layout", "residual", "k_route")] + [
+        ("skip_beta", ctypes.c_float)]
 
 
 class DesError(RuntimeError):
@@ -104,7 +105,8 @@ def _check(code: int) -> None:
 
 def make_shape(n_seqs: int, n_tokens: int, hidden: int, n_experts: int, ffn: int, top_k: int,
                coreset: int, mode, dtype, ffn_shared: int = 0, k_seq: int = 0,
-               weight_layout: int = DES_LAYOUT_ROWMAJOR, residual: int = 0) -> DesShape:
+               weight_layout: int = DES_LAYOUT_ROWMAJOR, residual: int = 0, k_route: int = 0,
+               skip_beta: float = 0.0) -> DesShape:
     if isinstance(mode, str):
         mode = MODES[mode]
     if isinstance(dtype, str):
@@ -112,7 +114,7 @@ def make_shape(n_seqs: int, n_tokens: int, hidden: int, n_experts: int, ffn: int
     elif isinstance(dtype, torch.dtype):
         dtype = {torch.float32: DES_F32, torch.bfloat16: DES_BF16}[dtype]
     return DesShape(n_seqs, n_tokens, hidden, n_experts, ffn, ffn_shared, top_k, coreset, k_seq,
-                    mode, dtype, weight_layout, residual)
+                    mode, dtype, weight_layout, residual, k_route, skip_beta)
 
 
 def _ptr(t: Optional[torch.Tensor]):

@@ -81,6 +81,8 @@ static int check_shape(const des_shape_t* s, bool need_ffn) {
     if (s->coreset < u) return DES_ERR_SHAPE;
   }
   if (s->residual != 0 && s->residual != 1) return DES_ERR_SHAPE;
+  if (s->k_route < 0 || s->k_route > s->top_k) return DES_ERR_SHAPE;
+  if (!(s->skip_beta >= 0.0f && s->skip_beta < 1.0f)) return DES_ERR_SHAPE;  // also rejects NaN
   const int align = s->dtype == DES_BF16 ? 32 : 4;
   if (s->hidden % align) return DES_ERR_SHAPE;
   if (need_ffn) {

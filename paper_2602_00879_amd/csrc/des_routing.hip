@@ -72,6 +72,8 @@ struct RoutingArgs {
   uint16_t* slot_tok;     // [n_slots][kSlotToks] tokens of each slot's first pairs
   int B, N, M, K, C, k_seq, mode, cap, D, n_slots;
   int groups;             // selector workgroups per sequence (each takes every groups-th pass)
+  int k_route;            // experts per token in stage 2 (<= K)
+  float skip_beta;        // > 0: cumulative-probability skipping of a token's weakest experts
   int tiles_m, tiles_t;   // router tiles along experts / tokens
   int do_router, do_select, do_permute, use_flags, bf16;
 };
@@ -571,7 +573,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
 
   DES_STAMP(a, 4);
   // ------------------------------ stage 2: constrained local routing + gates
-  const int keff = min(K, s_hist[34]);
+  const int keff = min(a.k_route, s_hist[34]);  // experts per token: Alg. 1 stage 2 with k <= K
   const bool reuse_sort = single_pass && a.mode != DES_VANILLA;  // stage 1 sorted this token
 
   for (int n0 = g * TPP; n0 + wave * RPW < N; n0 += G * TPP) {
@@ -615,16 +617,39 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
       mye[q] = mkey[q] ? exp_neg(key_to_f32(mkey[q]) - mx) : 0.f;
       part += mye[q];
     }
-    const float den = row_sum_f32<LPT>(part);
+    float den = row_sum_f32<LPT>(part);
     DES_STAMP(a, 17);
+    int keep = keff;
+    if (a.skip_beta > 0.f && keff > 1) {
+      // Sec. 5.1 (Baselines), adapted NAEE rule: drop experts i..k when their
+      // gates sum to less than beta of the total.  Tail sums from the weakest
+      // expert upwards, fp32, rank order; numerators suffice (the ratio to the
+      // total does not depend on the normalisation).
+      const float thr = a.skip_beta * den;
+      float suf = 0.f;
+      for (int it = keff - 1; it >= 1; --it) {  // keff is the same for every row
+        float v = 0.f;
+#pragma unroll
+        for (int q = 0; q < NW; ++q) {
+          const float c = __shfl(mye[q], (lane & ~(LPT - 1)) + (it % LPT));
+          if (it / LPT == q) v = c;
+        }
+        suf += v;
+        if (suf < thr) keep = it;
+      }
+      part = 0.f;
+#pragma unroll
+      for (int q = 0; q < NW; ++q) part += (q * LPT + rl < keep) ? mye[q] : 0.f;
+      den = row_sum_f32<LPT>(part);  // gates re-normalised over the survivors
+    }
     // g_n = softmax of the selected logits (Alg. 1 stage 2); unused slots -1 / 0
     if (live) {
 #pragma unroll
       for (int q = 0; q < NW; ++q) {
         const int it = q * LPT + rl;
         if (it < K) {
-          a.topk_w[o + it] = it < keff ? mye[q] / den : 0.f;
-          if (it >= keff) a.topk_idx[o + it] = -1;
+          a.topk_w[o + it] = it < keep ? mye[q] / den : 0.f;
+          if (it >= keep) a.topk_idx[o + it] = -1;
         }
       }
     }
@@ -849,6 +874,8 @@ static void fill_common(RoutingArgs& a, const des_shape_t& s) {
   a.tiles_t = (s.n_seqs * s.n_tokens + 15) / 16;
   a.bf16 = s.dtype == DES_BF16;
   a.groups = 1;
+  a.k_route = s.k_route > 0 ? s.k_route : s.top_k;
+  a.skip_beta = s.skip_beta;
 }
 
 int launch_router(const des_shape_t& s, const void* x, const void* w_router, const float* bias,

@@ -60,6 +60,11 @@ def test_workspace_and_capacity_are_host_only():
     (dict(n_seqs=200), -2),
     (dict(mode="seq", k_seq=2, coreset=32), -2),   # union of 32*2 may not fit 32
     (dict(residual=2), -2),
+    (dict(k_route=9), -2),
+    (dict(k_route=-1), -2),
+    (dict(skip_beta=1.0), -2),
+    (dict(skip_beta=-0.1), -2),
+    (dict(skip_beta=float("nan")), -2),
 ])
 def test_bad_shapes_are_rejected_before_launch(kw, code):
     s = _shape(**kw)

@@ -186,6 +186,43 @@ def test_runs_are_bit_identical():
         assert torch.equal(ya, b.y) and torch.equal(ia, b.topk_idx) and torch.equal(wa, b.topk_w)
 
 
+@pytest.mark.parametrize("mode", ["vanilla", "seq", "vote"])
+def test_routing_variants(mode):
+    """Fewer experts per token inside the same coreset (Sec. 5.3) and the
+    cumulative-probability skipping rule (Sec. 5.1, Baselines), alone and together,
+    on sequences long enough to be spread over several selector workgroups."""
+    cfg = MID["sel_groups"]
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    base = H.run_gpu(cfg, dev, mode)
+    for k_route, beta in ((2, 0.0), (0, 0.2), (3, 0.35), (1, 0.5)):
+        _say(f"variants {mode} k_route={k_route} beta={beta}")
+        out = H.run_gpu(cfg, dev, mode, k_route=k_route, skip_beta=beta)
+        r = H.check_against_oracle(cfg, layer, out, mode, k_route=k_route, skip_beta=beta,
+                                   label=f"variants {mode} k_route={k_route} beta={beta}")
+        # the election is the same as with the full K
+        assert torch.equal(out.coreset_idx, base.coreset_idx)
+        used = (out.topk_idx >= 0).sum(dim=-1)
+        assert int(used.min()) >= 1
+        if k_route:
+            assert int(used.max()) <= k_route
+        _say(f"  {r} experts per token {int(used.min())}..{int(used.max())}")
+
+
+def test_skipping_on_the_128_expert_layer():
+    """Vanilla routing with skipping (the baseline the paper compares against) and
+    DES-Vote with k = 4 of 8 on the benchmark layer: routing exact, outputs sampled."""
+    cfg = W.CONFIGS["m128_zipf"]
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    for mode, k_route, beta in (("vanilla", 0, 0.2), ("vanilla", 4, 0.0), ("vote", 4, 0.0), ("vote", 0, 0.3)):
+        _say(f"m128 {mode} k_route={k_route} beta={beta}")
+        out = H.run_gpu(cfg, dev, mode, k_route=k_route, skip_beta=beta)
+        r = H.check_against_oracle(cfg, layer, out, mode, k_route=k_route, skip_beta=beta,
+                                   only_tokens=_sample_tokens(cfg, 5, 7), label=f"m128 {mode} {k_route} {beta}")
+        _say(f"  {r}")
+
+
 def test_coreset_smaller_than_k():
     # a single token with C=2 < K=4: k_eff = 2, unused slots are -1 / 0
     cfg = W.LayerConfig("small_core", "bf16", 1, 1, 64, 16, 32, 0, 4, 2, 0.0, 15)
