@@ -11,6 +11,8 @@ one passage of the paper:
 
   router_logits        Background, "Efficient Mixture-of-Experts": G: R^D -> R^M
   softmax_rows         Sec. 4.3 (per-token softmax of the selection kernel)
+  router_scores        the "routing function sigma from the model architecture"
+                       (Sec. 4.1): softmax over the experts, or a per-expert sigmoid
   rank_order           TopK = "the K highest-scoring experts" (below Eq. 1)
   coreset_seq          Eq. 5 / Alg. 2  (DES-Seq)
   coreset_vote         Eq. 6 / Alg. 3  (DES-Vote)
@@ -35,6 +37,12 @@ the design notes of the repository):
     the coreset may be smaller than C;
   * a token uses k_eff = min(K, |coreset|) experts; unused slots carry
     index -1 and weight 0;
+  * act = "sigmoid": the router weight of an expert is sigmoid(logit); votes add
+    these scores and a token's gates are its selected scores divided by their
+    sum; rankings still compare logits (the sigmoid is monotone);
+  * renorm = True (the alternative reading of "aggregate the router weights",
+    Sec. 4.2): a token's K votes are divided by their sum, so every token casts
+    a total weight of one;
   * k_route (Sec. 5.3, "Effect of active expert count"): the coreset is elected
     with the model's K, then each token uses only its k_route < K best coreset
     experts; gates are normalised over those;
@@ -90,6 +98,19 @@ def softmax_rows(logits: np.ndarray) -> np.ndarray:
     return e / e.sum(axis=-1, keepdims=True)
 
 
+ACTS = ("softmax", "sigmoid")
+
+
+def router_scores(logits: np.ndarray, act: str = "softmax") -> np.ndarray:
+    """Router weights of every (token, expert): sigma of Sec. 4.1.  softmax over
+    the M experts of a token, or the logistic sigmoid of each logit."""
+    if act == "softmax":
+        return softmax_rows(logits)
+    if act == "sigmoid":
+        return 1.0 / (1.0 + np.exp(-np.asarray(logits, dtype=np.float64)))
+    raise ValueError(f"unknown router activation {act!r}")
+
+
 def rank_order(row: Sequence[float]) -> List[int]:
     """Expert ids of one token sorted best first: value descending, ties to the
     lowest index (TopK below Eq. 1 with the tie rule stated in the header)."""
@@ -136,22 +157,27 @@ def coreset_seq_capped(logits: np.ndarray, K: int, C: int) -> Tuple[List[int], i
     return sorted(cand[:C]), 0
 
 
-def vote_vector(logits: np.ndarray, K: int) -> Tuple[np.ndarray, np.ndarray]:
-    """Alg. 3, lines 1-2: V_i = sum over tokens of the token's softmax weight
+def vote_vector(logits: np.ndarray, K: int, act: str = "softmax",
+                renorm: bool = False) -> Tuple[np.ndarray, np.ndarray]:
+    """Alg. 3, lines 1-2: V_i = sum over tokens of the token's router weight
     for expert i, counted only where i is inside that token's own top-K.
+    renorm: each token's K weights are first divided by their sum.
     Returns (V float64 [M], nominated bool [M])."""
     N, M = logits.shape
-    P = softmax_rows(logits)
+    P = router_scores(logits, act)
     V = np.zeros(M, dtype=np.float64)
     nominated = np.zeros(M, dtype=bool)
     for n in range(N):
-        for i in topk(logits[n], K):
-            V[i] += P[n, i]
+        mine = topk(logits[n], K)
+        scale = 1.0 / sum(P[n, i] for i in mine) if renorm else 1.0
+        for i in mine:
+            V[i] += P[n, i] * scale
             nominated[i] = True
     return V, nominated
 
 
-def coreset_vote(logits: np.ndarray, K: int, C: int) -> Tuple[List[int], np.ndarray, float]:
+def coreset_vote(logits: np.ndarray, K: int, C: int, act: str = "softmax",
+                 renorm: bool = False) -> Tuple[List[int], np.ndarray, float]:
     """Eq. 6 / Alg. 3: the C experts with the largest total vote among the
     nominated ones (ties to the lowest index).
 
@@ -159,7 +185,7 @@ def coreset_vote(logits: np.ndarray, K: int, C: int) -> Tuple[List[int], np.ndar
     (V_(C) - V_(C+1)) / V_(C) between the last expert taken and the first one
     left out (inf when nothing was left out).
     """
-    V, nominated = vote_vector(logits, K)
+    V, nominated = vote_vector(logits, K, act, renorm)
     cand = [i for i in range(len(V)) if nominated[i]]
     cand.sort(key=lambda i: (-V[i], i))
     taken = cand[:C]
@@ -172,7 +198,7 @@ def coreset_vote(logits: np.ndarray, K: int, C: int) -> Tuple[List[int], np.ndar
 
 
 def select_coreset(logits: np.ndarray, mode: str, K: int, C: int,
-                   k_seq: int = 0) -> Dict[str, object]:
+                   k_seq: int = 0, act: str = "softmax", renorm: bool = False) -> Dict[str, object]:
     """Stage 1 of Alg. 1 for one sequence: coreset = Phi(logits)."""
     if mode not in MODES:
         raise ValueError(f"unknown mode {mode!r}")
@@ -188,7 +214,7 @@ def select_coreset(logits: np.ndarray, mode: str, K: int, C: int,
             core, used = coreset_seq_capped(logits, K, C)
             out["coreset"], out["k_seq_used"] = core, used
     else:
-        core, V, margin = coreset_vote(logits, K, C)
+        core, V, margin = coreset_vote(logits, K, C, act, renorm)
         out["coreset"], out["votes"], out["margin"] = core, V, margin
     return out
 
@@ -202,13 +228,19 @@ def constrained_topk(row: Sequence[float], coreset: Sequence[int], K: int) -> Li
     return [i for i in rank_order(row) if i in inside][:K]
 
 
-def gates(row: Sequence[float], selected: Sequence[int]) -> np.ndarray:
-    """Alg. 1 stage 2: g_n = softmax of the token's logits over S_n
-    (equal to P_i / sum_{j in S_n} P_j, the normalisation of Eq. 1)."""
+def gates(row: Sequence[float], selected: Sequence[int], act: str = "softmax") -> np.ndarray:
+    """Alg. 1 stage 2: g_n = the token's router weights over S_n divided by their
+    sum (the normalisation of Eq. 1).  For the softmax router that is the
+    softmax of the selected logits, P_i / sum_{j in S_n} P_j."""
     if len(selected) == 0:
         return np.zeros(0, dtype=np.float64)
     z = np.array([float(row[i]) for i in selected], dtype=np.float64)
-    e = np.exp(z - z.max())
+    if act == "sigmoid":
+        e = 1.0 / (1.0 + np.exp(-z))
+    elif act == "softmax":
+        e = np.exp(z - z.max())
+    else:
+        raise ValueError(f"unknown router activation {act!r}")
     return e / e.sum()
 
 
@@ -265,26 +297,28 @@ class _F64Cache:
 # The layer (Alg. 1)
 # --------------------------------------------------------------------------
 def route_block(logits: np.ndarray, mode: str, K: int, C: int, k_seq: int = 0,
-                k_route: int = 0, skip_beta: float = 0.0) -> Dict[str, object]:
+                k_route: int = 0, skip_beta: float = 0.0, act: str = "softmax",
+                renorm: bool = False) -> Dict[str, object]:
     """Routing part of Alg. 1 for ONE sequence given its logits [N, M]:
     coreset, per-token S_n (rank order, padded with -1) and gates (padded 0).
     k_route > 0: a token uses only its k_route best coreset experts (the
-    election still uses K).  skip_beta > 0: cumulative_skip on every token."""
+    election still uses K).  skip_beta > 0: cumulative_skip on every token.
+    act, renorm: router activation and vote normalisation (see the header)."""
     logits = np.asarray(logits, dtype=np.float64)
     N, M = logits.shape
-    sel = select_coreset(logits, mode, K, C, k_seq)
+    sel = select_coreset(logits, mode, K, C, k_seq, act, renorm)
     core = sel["coreset"]
     idx = -np.ones((N, K), dtype=np.int32)
     w = np.zeros((N, K), dtype=np.float64)
     skip_margin = math.inf
     for n in range(N):
         s_n = constrained_topk(logits[n], core, k_route if k_route > 0 else K)
-        g_n = gates(logits[n], s_n)
+        g_n = gates(logits[n], s_n, act)
         if skip_beta > 0.0:
             keep, m = cumulative_skip(g_n, skip_beta)
             skip_margin = min(skip_margin, m)
             s_n = s_n[:keep]
-            g_n = gates(logits[n], s_n)
+            g_n = gates(logits[n], s_n, act)
         idx[n, :len(s_n)] = s_n
         w[n, :len(s_n)] = g_n
     sel.update(topk_idx=idx, topk_w=w, skip_margin=skip_margin)
@@ -298,7 +332,8 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
                 logits_override: Optional[np.ndarray] = None,
                 compute_y: bool = True, residual: bool = False,
                 only_tokens: Optional[Sequence[Tuple[int, int]]] = None,
-                k_route: int = 0, skip_beta: float = 0.0) -> Dict[str, object]:
+                k_route: int = 0, skip_beta: float = 0.0, act: str = "softmax",
+                renorm: bool = False) -> Dict[str, object]:
     """Alg. 1 for B independent sequences.
 
     x: [B, N, D].  w_router [M, D]; w_gate, w_up [M, F, D]; w_down [M, D, F].
@@ -307,7 +342,8 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
     of computing them (the routing decisions are then a function of exactly
     these numbers).  Each sequence elects its own coreset.  only_tokens: compute
     y only for these (sequence, token) pairs (the rest of y stays NaN); routing
-    is always computed for every token.  k_route, skip_beta: see route_block.
+    is always computed for every token.  k_route, skip_beta, act, renorm: see
+    route_block.
     """
     x = np.asarray(x)
     B, N, D = x.shape
@@ -326,7 +362,7 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
     k_seq_used: List[int] = []
     skip_margin = math.inf
     for b in range(B):
-        r = route_block(logits[b], mode, K, C, k_seq, k_route, skip_beta)
+        r = route_block(logits[b], mode, K, C, k_seq, k_route, skip_beta, act, renorm)
         skip_margin = min(skip_margin, r["skip_margin"])
         topk_idx[b], topk_w[b] = r["topk_idx"], r["topk_w"]
         coresets.append(r["coreset"])

@@ -412,3 +412,43 @@ def test_skip_in_route_block():
             assert g[k - 1:].sum() >= 0.15 * g.sum()                 # and no longer tail would be
         np.testing.assert_allclose(skp["topk_w"][n, :k], g[:k] / g[:k].sum(), atol=1e-12)
     assert skp["skip_margin"] > 0
+
+
+# ------------------------------------------- other routers (Sec. 4.1, sigma)
+def test_sigmoid_router_and_renormalised_votes():
+    """sigma "from the model architecture": with a sigmoid router the weights are
+    logistic scores; rankings (and therefore DES-Seq and every top-K) do not
+    change because the sigmoid is monotone; votes and gates do."""
+    L = W.make_logits(20, 24, seed=3, zipf_s=0.7, scale=1.5)
+    # closed forms on hand values
+    np.testing.assert_allclose(O.router_scores(np.array([[0.0, np.log(3.0)]]), "sigmoid"), [[0.5, 0.75]])
+    np.testing.assert_allclose(O.gates([0.0, np.log(3.0), 5.0], [1, 0], "sigmoid"), [0.6, 0.4])
+    # votes: brute-force double loop over (token, expert) with an explicit mask
+    for act in ("softmax", "sigmoid"):
+        S = O.router_scores(L, act)
+        for renorm in (False, True):
+            V, nominated = O.vote_vector(L, 5, act, renorm)
+            want = np.zeros(24)
+            for n in range(20):
+                order = sorted(range(24), key=lambda i: (-L[n, i], i))[:5]
+                tot = sum(S[n, i] for i in order)
+                for i in order:
+                    want[i] += S[n, i] / (tot if renorm else 1.0)
+            np.testing.assert_allclose(V, want, rtol=1e-13)
+            if renorm:   # every token casts a total weight of one
+                assert V.sum() == pytest.approx(20.0)
+    # monotone activation: DES-Seq and vanilla index decisions are unchanged
+    for mode in ("vanilla", "seq"):
+        a = O.route_block(L, mode, 5, 9)
+        b = O.route_block(L, mode, 5, 9, act="sigmoid")
+        assert a["coreset"] == b["coreset"] and np.array_equal(a["topk_idx"], b["topk_idx"])
+        assert not np.allclose(a["topk_w"], b["topk_w"])
+        np.testing.assert_allclose(b["topk_w"].sum(axis=1), 1.0, atol=1e-12)
+    # renormalised softmax votes = softmax over the K selected logits
+    V, _ = O.vote_vector(L, 5, "softmax", True)
+    want = np.zeros(24)
+    for n in range(20):
+        sel = O.topk(L[n], 5)
+        for i, g in zip(sel, O.gates(L[n], sel)):
+            want[i] += g
+    np.testing.assert_allclose(V, want, rtol=1e-12)
