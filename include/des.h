@@ -55,6 +55,12 @@ typedef enum { DES_F32 = 0, DES_BF16 = 1 } des_dtype_t;
 
 typedef enum { DES_LAYOUT_ROWMAJOR = 0, DES_LAYOUT_PACKED = 1 } des_layout_t;
 
+/* The routing function sigma "from the model architecture" (Sec. 4.1): router weight of
+ * expert i for a token = softmax over the M logits, or sigmoid of its own logit.  Either
+ * way a token's gates are its selected weights divided by their sum (Eq. 1), and every
+ * ranking compares logits (both functions are monotone). */
+typedef enum { DES_ROUTER_SOFTMAX = 0, DES_ROUTER_SIGMOID = 1 } des_router_act_t;
+
 typedef enum {
   DES_OK = 0,
   DES_ERR_NULL = -1,      /* a required pointer is NULL                          */
@@ -93,13 +99,19 @@ typedef struct {
                          /* Sec. 5.1, Baselines).  0 = off.  The comparison is in  */
                          /* fp32; a tail within ~1e-6 (relative) of the threshold  */
                          /* may fall either way                                    */
+  int32_t router_act;    /* des_router_act_t: weights that are voted with (Eq. 6)  */
+                         /* and turned into gates (Alg. 1 stage 2)                 */
+  int32_t vote_renorm;   /* 1: a token's K votes are divided by their sum, so each */
+                         /* token casts a total weight of one (the other reading   */
+                         /* of "aggregate the router weights", Sec. 4.2); 0: as    */
+                         /* Alg. 3 is written (mask, then sum)                     */
 } des_shape_t;
 
 /*
  * Limits checked by every entry point (DES_ERR_SHAPE otherwise):
  *   B, N, D, M, F, K >= 1;  K <= M;  K <= 32;  M <= 512;  B*N <= 4096;
  *   M * ceil(B*N/64) <= 4096;  C >= 1 in seq / vote mode;  0 <= k_seq <= K;
- *   0 <= k_route <= K;  0 <= skip_beta < 1;
+ *   0 <= k_route <= K;  0 <= skip_beta < 1;  router_act, vote_renorm in {0, 1};
  *   seq mode with an explicit k_seq needs C >= min(M, N*k_seq) so that the
  *   union of Eq. 5 always fits the coreset_idx buffer;
  *   bf16: D, F, F_s multiples of 32 (matrix-core K step); fp32: multiples of 4.
@@ -113,10 +125,11 @@ int32_t des_coreset_capacity(const des_shape_t* shape);
 size_t des_workspace_bytes(const des_shape_t* shape);
 
 /*
- * Router scores (Background: G: R^D -> R^M) and their per-token softmax (the
- * per-token softmax of Sec. 4.3):
+ * Router scores (Background: G: R^D -> R^M) and the router weights made of them
+ * (the per-token softmax of Sec. 4.3, or sigmoids if router_act says so):
  *   logits[b][n][i] = sum_d x[b][n][d] * w_router[i][d] (+ router_bias[i]),
- *   probs [b][n][:] = softmax over all M of logits[b][n][:]   (if probs != NULL)
+ *   probs [b][n][:] = softmax over all M of logits[b][n][:], or sigmoid of each
+ *                     logit (if probs != NULL)
  * Inputs are read in `dtype`, accumulated in fp32; outputs are fp32
  * [B][N][M].  Uses no workspace.
  */
@@ -227,6 +240,14 @@ int des_kernel_timing_enable(int enable);
 int des_kernel_timing_count(void);
 const char* des_kernel_timing_name(int kernel_id);
 int des_kernel_timing_read(int kernel_id, double* total_ms, int64_t* launches);
+
+/*
+ * Coreset size for a budget given as a fraction of the experts, M_core = beta * M
+ * (Sec. 5.1), rounded down as the sizes printed in Table 1 imply (0.15 * 256 -> 38,
+ * 0.6 * 64 -> 38).  Host only.  Returns 0 for beta outside (0, 1] or n_experts < 1;
+ * at least 1 otherwise.
+ */
+int32_t des_coreset_from_beta(double beta, int32_t n_experts);
 
 const char* des_strerror(int code);
 /* Text of the last HIP error seen by this thread's DES_ERR_HIP ("" if none). */

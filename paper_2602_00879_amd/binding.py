@@ -25,15 +25,19 @@ EXPORTS = (
     "des_moe_forward", "des_stack_workspace_bytes", "des_moe_stack_forward",
     "des_pack_expert_weights", "des_strerror", "des_last_hip_error",
     "des_kernel_timing_enable", "des_kernel_timing_count", "des_kernel_timing_name",
-    "des_kernel_timing_read", "des_hbm_read_probe",
+    "des_kernel_timing_read", "des_hbm_read_probe", "des_coreset_from_beta",
 )
+
+
+DES_ROUTER_SOFTMAX, DES_ROUTER_SIGMOID = 0, 1
+ROUTER_ACTS = {"softmax": DES_ROUTER_SOFTMAX, "sigmoid": DES_ROUTER_SIGMOID}
 
 
 class DesShape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "n_seqs", "n_tokens", "hidden", "n_experts", "ffn", "ffn_shared", "top_k", "coreset",
         "k_seq", "mode", "dtype", "weight_layout", "residual", "k_route")] + [
-        ("skip_beta", ctypes.c_float)]
+        ("skip_beta", ctypes.c_float), ("router_act", ctypes.c_int32), ("vote_renorm", ctypes.c_int32)]
 
 
 class DesError(RuntimeError):
@@ -74,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.des_pack_expert_weights.argtypes = [vp, vp, ctypes.c_int64, i32, i32, vp]
         L.des_hbm_read_probe.restype = ctypes.c_int
         L.des_hbm_read_probe.argtypes = [vp, sz, vp, vp]
+        L.des_coreset_from_beta.restype = i32
+        L.des_coreset_from_beta.argtypes = [ctypes.c_double, i32]
         L.des_strerror.restype = ctypes.c_char_p
         L.des_strerror.argtypes = [ctypes.c_int]
         L.des_last_hip_error.restype = ctypes.c_char_p
@@ -106,7 +112,7 @@ def _check(code: int) -> None:
 def make_shape(n_seqs: int, n_tokens: int, hidden: int, n_experts: int, ffn: int, top_k: int,
                coreset: int, mode, dtype, ffn_shared: int = 0, k_seq: int = 0,
                weight_layout: int = DES_LAYOUT_ROWMAJOR, residual: int = 0, k_route: int = 0,
-               skip_beta: float = 0.0) -> DesShape:
+               skip_beta: float = 0.0, router_act=0, vote_renorm: int = 0) -> DesShape:
     if isinstance(mode, str):
         mode = MODES[mode]
     if isinstance(dtype, str):
@@ -114,7 +120,8 @@ def make_shape(n_seqs: int, n_tokens: int, hidden: int, n_experts: int, ffn: int
     elif isinstance(dtype, torch.dtype):
         dtype = {torch.float32: DES_F32, torch.bfloat16: DES_BF16}[dtype]
     return DesShape(n_seqs, n_tokens, hidden, n_experts, ffn, ffn_shared, top_k, coreset, k_seq,
-                    mode, dtype, weight_layout, residual, k_route, skip_beta)
+                    mode, dtype, weight_layout, residual, k_route, skip_beta,
+                    ROUTER_ACTS[router_act] if isinstance(router_act, str) else router_act, vote_renorm)
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -241,6 +248,11 @@ def des_hbm_read_probe(src: torch.Tensor, n_bytes: int, sink: torch.Tensor) -> N
     if n_bytes > src.numel() * src.element_size() or sink.numel() * sink.element_size() < 16:
         raise ValueError("read probe: n_bytes exceeds src, or sink smaller than 16 bytes")
     _check(lib().des_hbm_read_probe(_ptr(src), n_bytes, _ptr(sink), _stream()))
+
+
+def des_coreset_from_beta(beta: float, n_experts: int) -> int:
+    """floor(beta * M): the coreset size for a budget given as a fraction (Table 1)."""
+    return int(lib().des_coreset_from_beta(float(beta), int(n_experts)))
 
 
 def des_kernel_timing_enable(enable: bool) -> None:

@@ -6,6 +6,8 @@
 #include <atomic>
 #include <vector>
 
+#include <math.h>
+
 #include "des_common.h"
 
 namespace des {
@@ -83,6 +85,8 @@ static int check_shape(const des_shape_t* s, bool need_ffn) {
   if (s->residual != 0 && s->residual != 1) return DES_ERR_SHAPE;
   if (s->k_route < 0 || s->k_route > s->top_k) return DES_ERR_SHAPE;
   if (!(s->skip_beta >= 0.0f && s->skip_beta < 1.0f)) return DES_ERR_SHAPE;  // also rejects NaN
+  if (s->router_act != DES_ROUTER_SOFTMAX && s->router_act != DES_ROUTER_SIGMOID) return DES_ERR_MODE;
+  if (s->vote_renorm != 0 && s->vote_renorm != 1) return DES_ERR_SHAPE;
   const int align = s->dtype == DES_BF16 ? 32 : 4;
   if (s->hidden % align) return DES_ERR_SHAPE;
   if (need_ffn) {
@@ -250,6 +254,14 @@ int des_hbm_read_probe(const void* src, size_t bytes, void* sink, void* hip_stre
   if (bytes < 65536 || bytes % 65536 || bytes / 65536 > 0x7FFFFFFFull) return DES_ERR_SHAPE;
   if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(sink)) & 15) return DES_ERR_SHAPE;
   return launch_read_probe(src, bytes, sink, static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t des_coreset_from_beta(double beta, int32_t n_experts) {
+  if (!(beta > 0.0 && beta <= 1.0) || n_experts < 1) return 0;
+  // the small addend keeps decimal fractions whose product is an integer (0.3 * 10)
+  // from falling just below it in binary
+  const int32_t c = static_cast<int32_t>(floor(beta * n_experts + 1e-9));
+  return c < 1 ? 1 : c;
 }
 
 const char* des_strerror(int code) {

@@ -74,6 +74,8 @@ struct RoutingArgs {
   int groups;             // selector workgroups per sequence (each takes every groups-th pass)
   int k_route;            // experts per token in stage 2 (<= K)
   float skip_beta;        // > 0: cumulative-probability skipping of a token's weakest experts
+  int sigmoid;            // router weights are sigmoid(logit) instead of softmax over M
+  int vote_renorm;        // a token's K votes are divided by their sum
   int tiles_m, tiles_t;   // router tiles along experts / tokens
   int do_router, do_select, do_permute, use_flags, bf16;
 };
@@ -218,6 +220,11 @@ __device__ __forceinline__ float exp_neg(float x) {
   float r = fmaf(x, kL2eHi, -t);
   r = fmaf(x, kL2eLo, r);
   return __builtin_amdgcn_exp2f(t) * fmaf(r, 0.693147180559945f, 1.0f);
+}
+// logistic sigmoid, the same accuracy for both signs
+__device__ __forceinline__ float sigmoid_f(float x) {
+  const float t = exp_neg(-fabsf(x));
+  return (x >= 0.f ? 1.0f : t) / (1.0f + t);
 }
 __device__ __forceinline__ float key_to_f32(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
@@ -379,7 +386,10 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
       uint32_t key[kEpl];
       load_sort(n0 + slot, val, key);
       DES_STAMP(a, 15);
-      if (vote) {  // softmax over all M experts (Sec. 4.3), fp32
+      if (vote && a.sigmoid) {  // router weights of a sigmoid router
+#pragma unroll
+        for (int j = 0; j < kEpl; ++j) p[j] = key[j] ? sigmoid_f(val[j]) : 0.f;
+      } else if (vote) {  // softmax over all M experts (Sec. 4.3), fp32
         const float mx = key_to_f32(row_max_u32<LPT>(my_sorted[0]));
         float se = 0.f;
 #pragma unroll
@@ -413,8 +423,16 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
         }
       }
       if (vote) {
+        float scale = 1.0f;
+        if (a.vote_renorm) {  // the token's K weights sum to one
+          float mine_sum = 0.f;
 #pragma unroll
-        for (int j = 0; j < kEpl; ++j) vacc[j] += ((taken >> j) & 1u) ? p[j] : 0.f;  // Eq. 6
+          for (int j = 0; j < kEpl; ++j) mine_sum += ((taken >> j) & 1u) ? p[j] : 0.f;
+          const float tot = row_sum_f32<LPT>(mine_sum);
+          scale = tot > 0.f ? 1.0f / tot : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < kEpl; ++j) vacc[j] += ((taken >> j) & 1u) ? p[j] * scale : 0.f;  // Eq. 6
       }
     }
     DES_STAMP(a, 2);
@@ -614,7 +632,9 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
     float mye[NW], part = 0.f;
 #pragma unroll
     for (int q = 0; q < NW; ++q) {
-      mye[q] = mkey[q] ? exp_neg(key_to_f32(mkey[q]) - mx) : 0.f;
+      mye[q] = !mkey[q] ? 0.f
+               : a.sigmoid ? sigmoid_f(key_to_f32(mkey[q]))
+                           : exp_neg(key_to_f32(mkey[q]) - mx);
       part += mye[q];
     }
     float den = row_sum_f32<LPT>(part);
@@ -820,12 +840,17 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
   }
 }
 
-// probs[t][:] = softmax(logits[t][:]); one wavefront per token (des_route only).
+// probs[t][:] = router weights of token t (softmax of its logits, or their
+// sigmoids); one wavefront per token (des_route only).
 __global__ __launch_bounds__(64) void softmax_kernel(const float* __restrict__ logits,
-                                                     float* __restrict__ probs, int M) {
+                                                     float* __restrict__ probs, int M, int sigmoid) {
   const int lane = threadIdx.x;
   const float* row = logits + static_cast<size_t>(blockIdx.x) * M;
   float* out = probs + static_cast<size_t>(blockIdx.x) * M;
+  if (sigmoid) {
+    for (int i = lane; i < M; i += 64) out[i] = sigmoid_f(row[i]);
+    return;
+  }
   uint32_t mk = 0;
   for (int i = lane; i < M; i += 64) mk = max(mk, order_key(row[i]));
   const float mx = key_to_f32(wave_max_u32(mk));
@@ -876,6 +901,8 @@ static void fill_common(RoutingArgs& a, const des_shape_t& s) {
   a.groups = 1;
   a.k_route = s.k_route > 0 ? s.k_route : s.top_k;
   a.skip_beta = s.skip_beta;
+  a.sigmoid = s.router_act == DES_ROUTER_SIGMOID;
+  a.vote_renorm = s.vote_renorm;
 }
 
 int launch_router(const des_shape_t& s, const void* x, const void* w_router, const float* bias,
@@ -889,7 +916,8 @@ int launch_router(const des_shape_t& s, const void* x, const void* w_router, con
 
 int launch_softmax(const des_shape_t& s, const float* logits, float* probs, hipStream_t st) {
   const int T = s.n_seqs * s.n_tokens;
-  launch(kKSoftmax, softmax_kernel, dim3(T), dim3(64), 0, st, logits, probs, s.n_experts);
+  launch(kKSoftmax, softmax_kernel, dim3(T), dim3(64), 0, st, logits, probs, s.n_experts,
+         static_cast<int>(s.router_act == DES_ROUTER_SIGMOID));
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? DES_OK : hip_fail(e, "softmax launch");
 }

@@ -45,11 +45,11 @@ def layer_to_device(layer: Dict, device="cuda") -> Dict:
 
 def shape_of(cfg: W.LayerConfig, mode: str, C: Optional[int] = None, k_seq: int = 0,
              layout: int = B.DES_LAYOUT_ROWMAJOR, residual: int = 0, k_route: int = 0,
-             skip_beta: float = 0.0) -> B.DesShape:
+             skip_beta: float = 0.0, act: str = "softmax", renorm: bool = False) -> B.DesShape:
     return B.make_shape(cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k,
                         cfg.coreset if C is None else C, mode, cfg.dtype, ffn_shared=cfg.ffn_shared,
                         k_seq=k_seq, weight_layout=layout, residual=residual, k_route=k_route,
-                        skip_beta=skip_beta)
+                        skip_beta=skip_beta, router_act=act, vote_renorm=int(renorm))
 
 
 def oracle_inputs(layer: Dict) -> Dict:
@@ -62,8 +62,8 @@ def oracle_inputs(layer: Dict) -> Dict:
 
 
 def run_gpu(cfg, layer_dev, mode, C=None, k_seq=0, layout=B.DES_LAYOUT_ROWMAJOR, residual=0,
-            packed_weights=None, k_route=0, skip_beta=0.0):
-    shape = shape_of(cfg, mode, C, k_seq, layout, residual, k_route, skip_beta)
+            packed_weights=None, k_route=0, skip_beta=0.0, act="softmax", renorm=False):
+    shape = shape_of(cfg, mode, C, k_seq, layout, residual, k_route, skip_beta, act, renorm)
     wg, wu, wd = (layer_dev["w_gate"], layer_dev["w_up"], layer_dev["w_down"])
     sh = layer_dev["shared"]
     if packed_weights is not None:
@@ -75,7 +75,8 @@ def run_gpu(cfg, layer_dev, mode, C=None, k_seq=0, layout=B.DES_LAYOUT_ROWMAJOR,
 
 
 def check_against_oracle(cfg, layer, out, mode, C=None, k_seq=0, residual=False,
-                         only_tokens=None, label="", k_route=0, skip_beta=0.0):
+                         only_tokens=None, label="", k_route=0, skip_beta=0.0, act="softmax",
+                         renorm=False):
     """Teacher-forced parity: the oracle is fed the GPU's fp32 logits, so every
     index decision is a function of identical numbers and must match exactly."""
     C = cfg.coreset if C is None else C
@@ -90,7 +91,7 @@ def check_against_oracle(cfg, layer, out, mode, C=None, k_seq=0, residual=False,
     ref = O.moe_forward(oi["x"], oi["w_router"], oi["bias"], oi["w_gate"], oi["w_up"], oi["w_down"],
                         K, C, mode, k_seq=k_seq, shared=oi["shared"], logits_override=g_logits,
                         residual=residual, only_tokens=only_tokens, k_route=k_route,
-                        skip_beta=skip_beta)
+                        skip_beta=skip_beta, act=act, renorm=renorm)
     # a skipped tail decided in fp32 must not sit on the threshold
     assert ref["skip_margin"] > SKIP_MARGIN_MIN, f"{label}: a skip decision is too close to call"
     if mode == "vote":

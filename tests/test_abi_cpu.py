@@ -65,6 +65,8 @@ def test_workspace_and_capacity_are_host_only():
     (dict(skip_beta=1.0), -2),
     (dict(skip_beta=-0.1), -2),
     (dict(skip_beta=float("nan")), -2),
+    (dict(router_act=2), -3),
+    (dict(vote_renorm=2), -2),
 ])
 def test_bad_shapes_are_rejected_before_launch(kw, code):
     s = _shape(**kw)
@@ -101,3 +103,17 @@ def test_null_and_workspace_errors():
     alias = list(args)
     alias[9] = alias[0]
     assert L.des_moe_forward(ctypes.byref(s), *alias, ctypes.c_size_t(1 << 40), None) == -2
+
+
+def test_coreset_from_beta_matches_table_1_rounding():
+    """M_core = floor(beta * M): the sizes printed in Table 1 of the paper, and the
+    oracle's exact-fraction version on a grid of decimal budgets."""
+    from oracle import des_oracle as O
+    assert B.des_coreset_from_beta(0.15, 256) == 38 and B.des_coreset_from_beta(0.10, 256) == 25
+    assert B.des_coreset_from_beta(0.6, 64) == 38 and B.des_coreset_from_beta(0.4, 64) == 25
+    for M in (8, 10, 64, 100, 128, 256, 512):
+        for pct in range(1, 101):
+            beta = pct / 100.0
+            assert B.des_coreset_from_beta(beta, M) == max(1, O.coreset_size_from_beta(beta, M)), (beta, M)
+    assert B.des_coreset_from_beta(0.0, 64) == 0 and B.des_coreset_from_beta(1.5, 64) == 0
+    assert B.des_coreset_from_beta(0.5, 0) == 0

@@ -209,6 +209,37 @@ def test_routing_variants(mode):
         _say(f"  {r} experts per token {int(used.min())}..{int(used.max())}")
 
 
+@pytest.mark.parametrize("act,renorm", [("sigmoid", False), ("sigmoid", True), ("softmax", True)])
+def test_other_routers(act, renorm):
+    """Sigmoid router weights and renormalised votes (Sec. 4.1: sigma comes from the
+    model architecture; Sec. 4.2: the other reading of the vote), all three modes."""
+    cfg = MID["sel_groups"]
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    for mode in ("vanilla", "seq", "vote"):
+        _say(f"router {act} renorm={renorm} {mode}")
+        out = H.run_gpu(cfg, dev, mode, act=act, renorm=renorm)
+        r = H.check_against_oracle(cfg, layer, out, mode, act=act, renorm=renorm,
+                                   label=f"router {act} renorm={renorm} {mode}")
+        _say(f"  {r}")
+    if act == "sigmoid":   # des_route's weights
+        shape = H.shape_of(cfg, "vanilla", act=act)
+        logits, probs = B.des_route(shape, dev["x"], dev["w_router"], dev["bias"])
+        torch.cuda.synchronize()
+        ref = O.router_scores(logits.cpu().numpy().astype(np.float64), "sigmoid")
+        np.testing.assert_allclose(probs.cpu().numpy(), ref, rtol=1e-5, atol=1e-9)
+    # and combined with the other variants on the benchmark layer (sampled outputs)
+    if act == "sigmoid" and renorm:
+        cfg2 = W.CONFIGS["m128_zipf"]
+        layer2 = W.make_layer(cfg2)
+        dev2 = H.layer_to_device(layer2)
+        out = H.run_gpu(cfg2, dev2, "vote", act=act, renorm=renorm, k_route=6, skip_beta=0.1)
+        r = H.check_against_oracle(cfg2, layer2, out, "vote", act=act, renorm=renorm, k_route=6,
+                                   skip_beta=0.1, only_tokens=_sample_tokens(cfg2, 4, 3),
+                                   label="m128 sigmoid renorm k6 skip")
+        _say(f"  {r}")
+
+
 def test_skipping_on_the_128_expert_layer():
     """Vanilla routing with skipping (the baseline the paper compares against) and
     DES-Vote with k = 4 of 8 on the benchmark layer: routing exact, outputs sampled."""
