@@ -15,6 +15,8 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
     *(["-DDES_ROUTING_TIMESTAMPS"] if os.environ.get("DES_ROUTING_TIMESTAMPS") else []),
+    *(["-DDES_FFN_STAMPS"] if os.environ.get("DES_FFN_STAMPS") else []),
+    *(["-DDES_FFN_WAVES=" + os.environ["DES_FFN_WAVES"]] if os.environ.get("DES_FFN_WAVES") else []),
 ]
 
 

@@ -53,6 +53,15 @@ struct FfnArgs {
 
 constexpr int kFfnMaxWaitIters = 1 << 22;
 
+#ifdef DES_FFN_STAMPS  // development aid (build with DES_FFN_STAMPS=1): per-task 100 MHz
+                       // timestamps of the gate/up kernels, [start, task found, end, hardware id
+                       // or pairs], read back with des_debug_ffn_stamps()
+__device__ long long g_ffn_stamps[8192 * 4];
+#define DES_FSTAMP(task, i) do { if ((threadIdx.x & 63) == 0 && (task) < 8192) g_ffn_stamps[(task) * 4 + (i)] = wall_clock64(); } while (0)
+#else
+#define DES_FSTAMP(task, i) do { } while (0)
+#endif
+
 // Waits until f[0..n) all hold `epoch` (lanes poll in parallel); false if the
 // bounded wait ran out.  Ends with an acquire fence for the whole wavefront.
 __device__ __forceinline__ bool wait_flags(const unsigned long long* f, int n,
@@ -300,7 +309,10 @@ __device__ __forceinline__ FfnArgs shared_view(const FfnArgs& a, Task& t, size_t
   return v;
 }
 
-constexpr int kFfnWaves = 1;  // wavefronts per workgroup; each is an independent task
+#ifndef DES_FFN_WAVES
+#define DES_FFN_WAVES 1
+#endif
+constexpr int kFfnWaves = DES_FFN_WAVES;  // wavefronts per workgroup; each is an independent task
 constexpr int kGuTiles = 2;   // gate/up row tiles per task (F % 32 == 0, so F/16 is even)
 
 // MAXNT bounds the token tiles a task can have (the host knows T >= any expert's
@@ -317,8 +329,10 @@ __device__ __forceinline__ bool gateup_task(const FfnArgs& a, int task, int lane
   Task t;
   int ft;
   FfnArgs v = a;
+  DES_FSTAMP(task, 0);
   if (task < routed) {
     if (!make_task(a, task / tiles_r, false, false, t, lane)) return false;
+    DES_FSTAMP(task, 1);
     ft = (task % tiles_r) * GT;
   } else {
     make_task(a, 0, true, false, t, lane);
@@ -354,6 +368,12 @@ __device__ __forceinline__ bool gateup_task(const FfnArgs& a, int task, int lane
       for (int g0 = 0; g0 < t.count; g0 += 256)
         for (int f = 0; f < GT; ++f) gateup_group<1, 16, 1, PACKED, FUSED>(v, t, ft + f, g0, lane);
   }
+  DES_FSTAMP(task, 2);
+#ifdef DES_FFN_STAMPS
+  if ((threadIdx.x & 63) == 0 && task < 8192)
+    g_ffn_stamps[task * 4 + 3] = (static_cast<long long>(__builtin_amdgcn_s_getreg(20 | (31 << 11))) << 32) |
+                                 static_cast<unsigned>(__builtin_amdgcn_s_getreg(4 | (31 << 11)));
+#endif
   if (FUSED) publish_flag(a.h_ready + task, a.epoch, lane);
   return true;
 }
@@ -879,6 +899,7 @@ __global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void g
   const int per_r = (a.F / 16 + LW - 1) / LW;
   const int per_s = (a.Fs / 16 + LW - 1) / LW;
   if (static_cast<int>(blockIdx.x) >= a.n_slots * per_r + per_s) return;
+  DES_FSTAMP(blockIdx.x, 0);
   if (!lds_task<false>(a, per_r, group, t, v, lane)) return;  // uniform per workgroup
   const int tile = group * LW + wave;
   const bool active = tile < t.fdim / 16;
@@ -924,6 +945,10 @@ __global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void g
     else if (nt <= 6) run(std::integral_constant<int, MAXNT >= 8 ? 6 : 4>{});
     else run(std::integral_constant<int, MAXNT >= 8 ? 8 : 4>{});
   }
+#ifdef DES_FFN_STAMPS
+  DES_FSTAMP(blockIdx.x, 2);
+  if (threadIdx.x == 0 && blockIdx.x < 8192 && blockIdx.y == 0) g_ffn_stamps[blockIdx.x * 4 + 3] = t.count;
+#endif
 }
 
 template <bool PACKED, int MAXNT, int LW, int KD>
@@ -1444,3 +1469,10 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
 }
 
 }  // namespace des
+
+#ifdef DES_FFN_STAMPS
+extern "C" int des_debug_ffn_stamps(long long* host, int n) {
+  return hipMemcpyFromSymbol(host, HIP_SYMBOL(des::g_ffn_stamps), sizeof(long long) * n) == hipSuccess
+             ? 0 : -6;
+}
+#endif
