@@ -135,6 +135,10 @@ MID = dict(
     # ragged) that exchange their election partials; under DES-Seq one sequence fits
     # k=1 and the other overflows even at k=1 (top-1 nomination counts decide)
     sel_groups=W.LayerConfig("sel_groups", "bf16", 2, 150, 256, 100, 32, 0, 4, 16, 0.3, 19),
+    # the limits of the interface: 4096 tokens in 64 sequences (the routing runs as three
+    # launches, an expert can have hundreds of pairs), and 512 experts with K = 32
+    max_tokens=W.LayerConfig("max_tokens", "bf16", 64, 64, 64, 64, 32, 0, 4, 8, 0.5, 22),
+    max_experts=W.LayerConfig("max_experts", "bf16", 1, 8, 64, 512, 32, 32, 32, 40, 0.5, 23),
 )
 
 
