@@ -313,7 +313,8 @@ __device__ __forceinline__ uint32_t row_draw(const Head& hd, bool& mine) {
 // code into the instruction cache while it waits for the router tiles (every
 // index below derives from lane and slot numbers, never from the data read).
 template <int LPT>
-__device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, bool dry) {
+__device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, bool dry,
+                                bool wait_router) {
   using L = SelLds<LPT>;
   constexpr int MP = L::MP;
   constexpr int RPW = 64 / LPT;          // rows (tokens) per wave
@@ -345,7 +346,13 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
     s_core[e] = (a.mode == DES_VANILLA && e < M) ? 1 : 0;
   }
   if (threadIdx.x < 36) s_hist[threadIdx.x] = 0;
-  __syncthreads();
+  // the LDS set-up above does not need the logits: only now wait for the router
+  // tiles (the wait ends with a barrier of its own)
+  if (wait_router) {
+    if (!flags_wait(a.flags, a.tiles_m * a.tiles_t, a.epoch, false)) return false;
+  } else {
+    __syncthreads();
+  }
   DES_STAMP(a, 14);
 
   uint32_t sidx = 0;     // packed original slots of the sorted positions
@@ -797,12 +804,8 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
   const int n_flags = all_tiles + 2 * a.B * a.groups;
   if (blk < n_sel) {  // ---- role S
     DES_STAMP(a, 0);
-    if (a.use_flags && a.do_router && !flags_wait(a.flags, all_tiles, a.epoch, false)) {
-      if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
-      return;
-    }
-    DES_STAMP(a, 1);
-    if (!select_sequence<LPT>(a, blk / a.groups, blk % a.groups, smem, false)) {
+    if (!select_sequence<LPT>(a, blk / a.groups, blk % a.groups, smem, false,
+                              a.use_flags && a.do_router)) {
       if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
       return;
     }
