@@ -14,6 +14,8 @@ one passage of the paper:
   router_scores        the "routing function sigma from the model architecture"
                        (Sec. 4.1): softmax over the experts, or a per-expert sigmoid
   rank_order           TopK = "the K highest-scoring experts" (below Eq. 1)
+  group_limited        group-limited routers (another sigma of Sec. 4.1): the groups of
+                       experts a token may choose from
   coreset_seq          Eq. 5 / Alg. 2  (DES-Seq)
   coreset_vote         Eq. 6 / Alg. 3  (DES-Vote)
   constrained_topk     Alg. 1, stage 2, S_n
@@ -50,6 +52,13 @@ the design notes of the repository):
     gates is below beta times the sum of all k gates (strictly); the largest such
     suffix is taken, the best expert always stays, and the surviving gates are
     re-normalised over the survivors (the normalisation of Eq. 1);
+  * group-limited routing (n_group > 1): the M experts form n_group equal groups
+    of consecutive indices; a token scores each group by its best router weight
+    ("max") or by the sum of its two best ("top2sum"), keeps the topk_group best
+    groups (ties to the lowest group index) and never ranks an expert outside
+    them: neither in its own top-K that nominates and votes (stage 1) nor in
+    its choice inside the coreset (stage 2).  A token whose allowed groups hold
+    fewer than k coreset experts uses only those (none: it gets no routed expert);
   * DES-Seq with k_seq == 0 picks the largest k' <= K whose union has at most C
     members; if even k' = 1 overflows, the C most often top-1-nominated experts
     are kept (ties to the lowest index).
@@ -58,7 +67,8 @@ Pins: tests/test_oracle_pins.py (brute force over subsets, a hand-worked
 3-token x 5-expert example, the closed form for uniform routing, Table 1's
 rounding, reductions to a plain numpy MLP and to a dense one-hot einsum,
 the skipping rule on hand-computed gates and against enumeration of every cut,
-and the invariants the method fixes).  The token-level statistics the paper
+group limits against a scan of the global ranking, an enumeration of pairs and a
+hand-worked example, and the invariants the method fixes).  The token-level statistics the paper
 reports on trained routers (hit-rate cosine similarity, accuracy) are
 "parity unpinned": they need trained weights.
 """
@@ -121,44 +131,99 @@ def rank_order(row: Sequence[float]) -> List[int]:
     return sorted(range(len(vals)), key=lambda i: (-vals[i], i))
 
 
-def topk(row: Sequence[float], k: int) -> List[int]:
-    """TopK(row, k) in rank order."""
-    return rank_order(row)[:k]
+def topk(row: Sequence[float], k: int, allowed: Optional[Sequence[bool]] = None) -> List[int]:
+    """TopK(row, k) in rank order; with `allowed`, among the allowed experts only."""
+    order = rank_order(row)
+    if allowed is not None:
+        order = [i for i in order if allowed[i]]
+    return order[:k]
+
+
+GROUP_SCORES = ("max", "top2sum")
+
+
+def group_limited(scores: Sequence[float], n_group: int, topk_group: int,
+                  kind: str = "max") -> Tuple[List[bool], float]:
+    """Group-limited routing for one token (see the header).  scores: the token's
+    M router weights (router_scores).  Returns (allowed [M], margin) where margin
+    is the relative gap between the score of the last group kept and of the first
+    group left out (inf when every group is kept)."""
+    M = len(scores)
+    if n_group < 1 or M % n_group != 0:
+        raise ValueError("the experts must split into equal groups")
+    if not 1 <= topk_group <= n_group:
+        raise ValueError("1 <= topk_group <= n_group")
+    if kind not in GROUP_SCORES:
+        raise ValueError(f"unknown group score {kind!r}")
+    size = M // n_group
+    gscore = []
+    for g in range(n_group):
+        members = sorted((float(scores[i]) for i in range(g * size, (g + 1) * size)), reverse=True)
+        gscore.append(members[0] if kind == "max" else sum(members[:2]))
+    order = sorted(range(n_group), key=lambda g: (-gscore[g], g))
+    kept = set(order[:topk_group])
+    allowed = [(i // size) in kept for i in range(M)]
+    if topk_group < n_group:
+        last_in, first_out = gscore[order[topk_group - 1]], gscore[order[topk_group]]
+        margin = (last_in - first_out) / abs(last_in) if last_in != 0 else 0.0
+    else:
+        margin = math.inf
+    return allowed, float(margin)
+
+
+def allowed_experts(logits: np.ndarray, act: str, n_group: int, topk_group: int,
+                    kind: str) -> Tuple[Optional[np.ndarray], float]:
+    """group_limited for every token of a sequence.  Returns (allowed bool [N, M]
+    or None when there is no group limit, smallest margin)."""
+    if n_group <= 1:
+        return None, math.inf
+    P = router_scores(logits, act)
+    rows, margin = [], math.inf
+    for n in range(P.shape[0]):
+        a, m = group_limited(P[n], n_group, topk_group, kind)
+        rows.append(a)
+        margin = min(margin, m)
+    return np.array(rows, dtype=bool), margin
 
 
 # --------------------------------------------------------------------------
 # Coreset selection functions Phi
 # --------------------------------------------------------------------------
-def coreset_seq(logits: np.ndarray, k_seq: int) -> List[int]:
+def _row(allowed: Optional[np.ndarray], n: int):
+    return None if allowed is None else allowed[n]
+
+
+def coreset_seq(logits: np.ndarray, k_seq: int, allowed: Optional[np.ndarray] = None) -> List[int]:
     """Eq. 5 / Alg. 2: union over tokens of each token's top-k_seq experts."""
     core = set()
     for n in range(logits.shape[0]):
-        core |= set(topk(logits[n], k_seq))
+        core |= set(topk(logits[n], k_seq, _row(allowed, n)))
     return sorted(core)
 
 
-def coreset_seq_capped(logits: np.ndarray, K: int, C: int) -> Tuple[List[int], int]:
+def coreset_seq_capped(logits: np.ndarray, K: int, C: int,
+                       allowed: Optional[np.ndarray] = None) -> Tuple[List[int], int]:
     """DES-Seq under a size cap C (extension; see header).  Returns
     (coreset ascending, k_seq used); k_seq used is 0 in the overflow case."""
     best_k = 0
     for kp in range(1, K + 1):
-        if len(coreset_seq(logits, kp)) <= C:
+        if len(coreset_seq(logits, kp, allowed)) <= C:
             best_k = kp
         else:
             break  # union size is monotone in k'
     if best_k > 0:
-        return coreset_seq(logits, best_k), best_k
+        return coreset_seq(logits, best_k, allowed), best_k
     M = logits.shape[1]
     nominations = [0] * M
     for n in range(logits.shape[0]):
-        nominations[topk(logits[n], 1)[0]] += 1
+        nominations[topk(logits[n], 1, _row(allowed, n))[0]] += 1
     cand = [i for i in range(M) if nominations[i] > 0]
     cand.sort(key=lambda i: (-nominations[i], i))
     return sorted(cand[:C]), 0
 
 
-def vote_vector(logits: np.ndarray, K: int, act: str = "softmax",
-                renorm: bool = False) -> Tuple[np.ndarray, np.ndarray]:
+def vote_vector(logits: np.ndarray, K: int, act: str = "softmax", renorm: bool = False,
+                allowed: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
     """Alg. 3, lines 1-2: V_i = sum over tokens of the token's router weight
     for expert i, counted only where i is inside that token's own top-K.
     renorm: each token's K weights are first divided by their sum.
@@ -168,7 +233,7 @@ def vote_vector(logits: np.ndarray, K: int, act: str = "softmax",
     V = np.zeros(M, dtype=np.float64)
     nominated = np.zeros(M, dtype=bool)
     for n in range(N):
-        mine = topk(logits[n], K)
+        mine = topk(logits[n], K, _row(allowed, n))
         scale = 1.0 / sum(P[n, i] for i in mine) if renorm else 1.0
         for i in mine:
             V[i] += P[n, i] * scale
@@ -176,8 +241,8 @@ def vote_vector(logits: np.ndarray, K: int, act: str = "softmax",
     return V, nominated
 
 
-def coreset_vote(logits: np.ndarray, K: int, C: int, act: str = "softmax",
-                 renorm: bool = False) -> Tuple[List[int], np.ndarray, float]:
+def coreset_vote(logits: np.ndarray, K: int, C: int, act: str = "softmax", renorm: bool = False,
+                 allowed: Optional[np.ndarray] = None) -> Tuple[List[int], np.ndarray, float]:
     """Eq. 6 / Alg. 3: the C experts with the largest total vote among the
     nominated ones (ties to the lowest index).
 
@@ -185,7 +250,7 @@ def coreset_vote(logits: np.ndarray, K: int, C: int, act: str = "softmax",
     (V_(C) - V_(C+1)) / V_(C) between the last expert taken and the first one
     left out (inf when nothing was left out).
     """
-    V, nominated = vote_vector(logits, K, act, renorm)
+    V, nominated = vote_vector(logits, K, act, renorm, allowed)
     cand = [i for i in range(len(V)) if nominated[i]]
     cand.sort(key=lambda i: (-V[i], i))
     taken = cand[:C]
@@ -198,8 +263,10 @@ def coreset_vote(logits: np.ndarray, K: int, C: int, act: str = "softmax",
 
 
 def select_coreset(logits: np.ndarray, mode: str, K: int, C: int,
-                   k_seq: int = 0, act: str = "softmax", renorm: bool = False) -> Dict[str, object]:
-    """Stage 1 of Alg. 1 for one sequence: coreset = Phi(logits)."""
+                   k_seq: int = 0, act: str = "softmax", renorm: bool = False,
+                   allowed: Optional[np.ndarray] = None) -> Dict[str, object]:
+    """Stage 1 of Alg. 1 for one sequence: coreset = Phi(logits).  allowed
+    [N, M]: the experts each token may rank (group-limited routers)."""
     if mode not in MODES:
         raise ValueError(f"unknown mode {mode!r}")
     N, M = logits.shape
@@ -208,13 +275,13 @@ def select_coreset(logits: np.ndarray, mode: str, K: int, C: int,
         out["coreset"] = list(range(M))           # Eq. 1: no restriction
     elif mode == "seq":
         if k_seq > 0:
-            out["coreset"] = coreset_seq(logits, k_seq)
+            out["coreset"] = coreset_seq(logits, k_seq, allowed)
             out["k_seq_used"] = k_seq
         else:
-            core, used = coreset_seq_capped(logits, K, C)
+            core, used = coreset_seq_capped(logits, K, C, allowed)
             out["coreset"], out["k_seq_used"] = core, used
     else:
-        core, V, margin = coreset_vote(logits, K, C, act, renorm)
+        core, V, margin = coreset_vote(logits, K, C, act, renorm, allowed)
         out["coreset"], out["votes"], out["margin"] = core, V, margin
     return out
 
@@ -222,10 +289,12 @@ def select_coreset(logits: np.ndarray, mode: str, K: int, C: int,
 # --------------------------------------------------------------------------
 # Stage 2: constrained routing
 # --------------------------------------------------------------------------
-def constrained_topk(row: Sequence[float], coreset: Sequence[int], K: int) -> List[int]:
-    """Alg. 1 stage 2: S_n = TopK(row restricted to the coreset, K), rank order."""
+def constrained_topk(row: Sequence[float], coreset: Sequence[int], K: int,
+                     allowed: Optional[Sequence[bool]] = None) -> List[int]:
+    """Alg. 1 stage 2: S_n = TopK(row restricted to the coreset, K), rank order.
+    allowed: the experts this token may rank at all (group-limited routers)."""
     inside = set(int(c) for c in coreset)
-    return [i for i in rank_order(row) if i in inside][:K]
+    return [i for i in rank_order(row) if i in inside and (allowed is None or allowed[i])][:K]
 
 
 def gates(row: Sequence[float], selected: Sequence[int], act: str = "softmax") -> np.ndarray:
@@ -298,21 +367,24 @@ class _F64Cache:
 # --------------------------------------------------------------------------
 def route_block(logits: np.ndarray, mode: str, K: int, C: int, k_seq: int = 0,
                 k_route: int = 0, skip_beta: float = 0.0, act: str = "softmax",
-                renorm: bool = False) -> Dict[str, object]:
+                renorm: bool = False, n_group: int = 0, topk_group: int = 0,
+                group_score: str = "max") -> Dict[str, object]:
     """Routing part of Alg. 1 for ONE sequence given its logits [N, M]:
     coreset, per-token S_n (rank order, padded with -1) and gates (padded 0).
     k_route > 0: a token uses only its k_route best coreset experts (the
     election still uses K).  skip_beta > 0: cumulative_skip on every token.
-    act, renorm: router activation and vote normalisation (see the header)."""
+    act, renorm: router activation and vote normalisation; n_group, topk_group,
+    group_score: group-limited routing (see the header)."""
     logits = np.asarray(logits, dtype=np.float64)
     N, M = logits.shape
-    sel = select_coreset(logits, mode, K, C, k_seq, act, renorm)
+    allowed, group_margin = allowed_experts(logits, act, n_group, topk_group, group_score)
+    sel = select_coreset(logits, mode, K, C, k_seq, act, renorm, allowed)
     core = sel["coreset"]
     idx = -np.ones((N, K), dtype=np.int32)
     w = np.zeros((N, K), dtype=np.float64)
     skip_margin = math.inf
     for n in range(N):
-        s_n = constrained_topk(logits[n], core, k_route if k_route > 0 else K)
+        s_n = constrained_topk(logits[n], core, k_route if k_route > 0 else K, _row(allowed, n))
         g_n = gates(logits[n], s_n, act)
         if skip_beta > 0.0:
             keep, m = cumulative_skip(g_n, skip_beta)
@@ -321,7 +393,7 @@ def route_block(logits: np.ndarray, mode: str, K: int, C: int, k_seq: int = 0,
             g_n = gates(logits[n], s_n, act)
         idx[n, :len(s_n)] = s_n
         w[n, :len(s_n)] = g_n
-    sel.update(topk_idx=idx, topk_w=w, skip_margin=skip_margin)
+    sel.update(topk_idx=idx, topk_w=w, skip_margin=skip_margin, group_margin=group_margin)
     return sel
 
 
@@ -333,7 +405,8 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
                 compute_y: bool = True, residual: bool = False,
                 only_tokens: Optional[Sequence[Tuple[int, int]]] = None,
                 k_route: int = 0, skip_beta: float = 0.0, act: str = "softmax",
-                renorm: bool = False) -> Dict[str, object]:
+                renorm: bool = False, n_group: int = 0, topk_group: int = 0,
+                group_score: str = "max") -> Dict[str, object]:
     """Alg. 1 for B independent sequences.
 
     x: [B, N, D].  w_router [M, D]; w_gate, w_up [M, F, D]; w_down [M, D, F].
@@ -342,8 +415,8 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
     of computing them (the routing decisions are then a function of exactly
     these numbers).  Each sequence elects its own coreset.  only_tokens: compute
     y only for these (sequence, token) pairs (the rest of y stays NaN); routing
-    is always computed for every token.  k_route, skip_beta, act, renorm: see
-    route_block.
+    is always computed for every token.  k_route, skip_beta, act, renorm,
+    n_group, topk_group, group_score: see route_block.
     """
     x = np.asarray(x)
     B, N, D = x.shape
@@ -360,10 +433,12 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
     votes: List[Optional[np.ndarray]] = []
     margins: List[float] = []
     k_seq_used: List[int] = []
-    skip_margin = math.inf
+    skip_margin = group_margin = math.inf
     for b in range(B):
-        r = route_block(logits[b], mode, K, C, k_seq, k_route, skip_beta, act, renorm)
+        r = route_block(logits[b], mode, K, C, k_seq, k_route, skip_beta, act, renorm,
+                        n_group, topk_group, group_score)
         skip_margin = min(skip_margin, r["skip_margin"])
+        group_margin = min(group_margin, r["group_margin"])
         topk_idx[b], topk_w[b] = r["topk_idx"], r["topk_w"]
         coresets.append(r["coreset"])
         votes.append(r["votes"])
@@ -405,7 +480,7 @@ def moe_forward(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray],
                 y[b, n] = acc
     return dict(logits=logits, topk_idx=topk_idx, topk_w=topk_w, counts=counts,
                 n_unique=n_unique, coresets=coresets, votes=votes, margins=margins,
-                k_seq_used=k_seq_used, y=y, skip_margin=skip_margin)
+                k_seq_used=k_seq_used, y=y, skip_margin=skip_margin, group_margin=group_margin)
 
 
 def moe_stack_forward(x: np.ndarray, layers: Sequence[dict], K: int, C: int, mode: str,

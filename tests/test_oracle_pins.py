@@ -452,3 +452,105 @@ def test_sigmoid_router_and_renormalised_votes():
         for i, g in zip(sel, O.gates(L[n], sel)):
             want[i] += g
     np.testing.assert_allclose(V, want, rtol=1e-12)
+
+
+# -------------------------------- group-limited routers (Sec. 4.1, sigma)
+def test_group_limit_hand_worked():
+    """Six experts in three groups of two, two groups kept.  The two group
+    scores disagree on these numbers: by best member the groups score
+    (0.90, 0.50, 0.60), by the sum of the two best (0.95, 0.99, 0.90)."""
+    s = [0.90, 0.05, 0.50, 0.49, 0.60, 0.30]
+    a, m = O.group_limited(s, 3, 2, "max")
+    assert a == [True, True, False, False, True, True]
+    assert m == pytest.approx((0.60 - 0.50) / 0.60)
+    a, m = O.group_limited(s, 3, 2, "top2sum")
+    assert a == [True, True, True, True, False, False]
+    assert m == pytest.approx((0.95 - 0.90) / 0.95)
+    # equal group scores: the lower group index is kept
+    a, m = O.group_limited([1.0, 0.0, 0.0, 1.0, 0.5, 0.5], 3, 1, "max")
+    assert a == [True, True, False, False, False, False] and m == 0.0
+    # one group, or every group kept: no limit at all
+    assert O.group_limited(s, 1, 1, "max") == ([True] * 6, math.inf)
+    assert O.group_limited(s, 3, 3, "top2sum") == ([True] * 6, math.inf)
+    for n_group, topk_group in ((4, 1), (3, 0), (3, 4)):
+        with pytest.raises(ValueError):
+            O.group_limited(s, n_group, topk_group, "max")
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_group_limit_against_a_scan_of_the_ranking_and_pair_enumeration(seed):
+    """"max": walking the token's experts best first, the kept groups are the
+    first topk_group distinct groups met.  "top2sum": a group's score is the
+    largest sum over all pairs of its members (scores are positive), found here
+    by enumerating the pairs; the kept groups are then found by enumerating
+    every topk_group-subset of groups for the largest total."""
+    rng = np.random.default_rng(100 + seed)
+    n_group = int(rng.integers(2, 6))
+    size = int(rng.integers(2, 5))
+    topk_group = int(rng.integers(1, n_group))
+    M = n_group * size
+    s = rng.random(M) + 0.01
+    if seed % 3 == 0:   # exact ties between groups
+        s = np.round(s * 4) / 4 + 0.25
+    allowed, _ = O.group_limited(s, n_group, topk_group, "max")
+    seen = []
+    for i in sorted(range(M), key=lambda i: (-s[i], i)):
+        if i // size not in seen:
+            seen.append(i // size)
+    # equal best members: the lower group index first
+    best = [max(s[g * size:(g + 1) * size]) for g in range(n_group)]
+    seen.sort(key=lambda g: (-best[g], g))
+    assert allowed == [(i // size) in seen[:topk_group] for i in range(M)]
+
+    allowed, _ = O.group_limited(s, n_group, topk_group, "top2sum")
+    pair = [max(s[i] + s[j] for i, j in itertools.combinations(range(g * size, (g + 1) * size), 2))
+            for g in range(n_group)]
+    want = _best_subset(pair, range(n_group), topk_group)
+    assert allowed == [(i // size) in want for i in range(M)]
+
+
+def test_group_limit_in_the_layer():
+    L = W.make_logits(24, 64, seed=5, zipf_s=0.9, scale=1.5)
+    K, C = 4, 6
+    for act, kind in (("softmax", "max"), ("sigmoid", "top2sum")):
+        S = O.router_scores(L, act)
+        allowed = np.array([O.group_limited(S[n], 8, 2, kind)[0] for n in range(24)])
+        # vanilla: the architecture's own routing = top-K of the allowed experts
+        v = O.route_block(L, "vanilla", K, 64, act=act, n_group=8, topk_group=2, group_score=kind)
+        for n in range(24):
+            mine = [int(e) for e in v["topk_idx"][n]]
+            assert all(allowed[n, e] for e in mine)
+            assert len(set(e // 8 for e in mine)) <= 2
+            masked = np.where(allowed[n], L[n], -1e30)      # plain masked top-K
+            assert mine == [int(i) for i in np.argsort(-masked, kind="stable")[:K]]
+        # votes: explicit double loop over allowed nominations
+        V, nominated = O.vote_vector(L, K, act, False, allowed)
+        want = np.zeros(64)
+        for n in range(24):
+            order = [i for i in sorted(range(64), key=lambda i: (-L[n, i], i)) if allowed[n, i]][:K]
+            for i in order:
+                want[i] += S[n, i]
+        np.testing.assert_allclose(V, want, rtol=1e-13)
+        # DES: every token stays inside coreset AND its own groups; a token may be short
+        for mode in ("seq", "vote"):
+            r = O.route_block(L, mode, K, C, act=act, n_group=8, topk_group=2, group_score=kind)
+            core = set(r["coreset"])
+            short = 0
+            for n in range(24):
+                mine = [int(e) for e in r["topk_idx"][n] if e >= 0]
+                assert all(e in core and allowed[n, e] for e in mine)
+                room = sum(1 for e in core if allowed[n, e])
+                assert len(mine) == min(K, room)
+                short += len(mine) < K
+                if mine:
+                    assert r["topk_w"][n].sum() == pytest.approx(1.0)
+                else:
+                    assert r["topk_w"][n].sum() == 0.0
+            assert r["group_margin"] > 0
+            assert short > 0     # the case this test is about does occur
+    # no groups, one group, or all groups kept: identical to the unlimited layer
+    base = O.route_block(L, "vote", K, C)
+    for ng, tg in ((0, 0), (1, 1), (8, 8)):
+        r = O.route_block(L, "vote", K, C, n_group=ng, topk_group=tg)
+        assert r["coreset"] == base["coreset"] and np.array_equal(r["topk_idx"], base["topk_idx"])
+        np.testing.assert_array_equal(r["topk_w"], base["topk_w"])
