@@ -61,6 +61,15 @@ typedef enum { DES_LAYOUT_ROWMAJOR = 0, DES_LAYOUT_PACKED = 1 } des_layout_t;
  * ranking compares logits (both functions are monotone). */
 typedef enum { DES_ROUTER_SOFTMAX = 0, DES_ROUTER_SIGMOID = 1 } des_router_act_t;
 
+/* Group-limited routers (another sigma of Sec. 4.1): the M experts form n_group equal
+ * groups of consecutive indices; a token scores each group by the best router weight in
+ * it, or by the sum of its two best, keeps the topk_group best groups (ties to the lowest
+ * group index) and never ranks an expert outside them - not in its own top-K that
+ * nominates and votes (Alg. 1 stage 1), not in its choice inside the coreset (stage 2).
+ * A token whose groups hold fewer coreset experts than it may use takes only those
+ * (index -1, weight 0 in the other slots; none at all: no routed expert). */
+typedef enum { DES_GROUP_MAX = 1, DES_GROUP_TOP2SUM = 2 } des_group_score_t;
+
 typedef enum {
   DES_OK = 0,
   DES_ERR_NULL = -1,      /* a required pointer is NULL                          */
@@ -105,6 +114,12 @@ typedef struct {
                          /* token casts a total weight of one (the other reading   */
                          /* of "aggregate the router weights", Sec. 4.2); 0: as    */
                          /* Alg. 3 is written (mask, then sum)                     */
+  int32_t n_group;       /* > 1: group-limited routing over this many groups;      */
+                         /* 0 or 1 = off (topk_group, group_score then ignored)    */
+  int32_t topk_group;    /* groups a token keeps, 1..n_group                       */
+  int32_t group_score;   /* des_group_score_t.  "max" compares logits (exact);     */
+                         /* "top2sum" adds two fp32 router weights per group, and  */
+                         /* two groups within ~1e-6 (relative) may swap            */
 } des_shape_t;
 
 /*
@@ -112,6 +127,9 @@ typedef struct {
  *   B, N, D, M, F, K >= 1;  K <= M;  K <= 32;  M <= 512;  B*N <= 4096;
  *   M * ceil(B*N/64) <= 4096;  C >= 1 in seq / vote mode;  0 <= k_seq <= K;
  *   0 <= k_route <= K;  0 <= skip_beta < 1;  router_act, vote_renorm in {0, 1};
+ *   n_group > 1: M a multiple of n_group, the group size M/n_group a multiple of 8,
+ *   1 <= topk_group <= n_group, topk_group * (M/n_group) >= K (a token can always
+ *   nominate K experts), group_score a des_group_score_t (DES_ERR_MODE otherwise);
  *   seq mode with an explicit k_seq needs C >= min(M, N*k_seq) so that the
  *   union of Eq. 5 always fits the coreset_idx buffer;
  *   bf16: D, F, F_s multiples of 32 (matrix-core K step); fp32: multiples of 4.

@@ -31,13 +31,16 @@ EXPORTS = (
 
 DES_ROUTER_SOFTMAX, DES_ROUTER_SIGMOID = 0, 1
 ROUTER_ACTS = {"softmax": DES_ROUTER_SOFTMAX, "sigmoid": DES_ROUTER_SIGMOID}
+DES_GROUP_MAX, DES_GROUP_TOP2SUM = 1, 2
+GROUP_SCORES = {"max": DES_GROUP_MAX, "top2sum": DES_GROUP_TOP2SUM}
 
 
 class DesShape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "n_seqs", "n_tokens", "hidden", "n_experts", "ffn", "ffn_shared", "top_k", "coreset",
         "k_seq", "mode", "dtype", "weight_layout", "residual", "k_route")] + [
-        ("skip_beta", ctypes.c_float), ("router_act", ctypes.c_int32), ("vote_renorm", ctypes.c_int32)]
+        ("skip_beta", ctypes.c_float), ("router_act", ctypes.c_int32), ("vote_renorm", ctypes.c_int32),
+        ("n_group", ctypes.c_int32), ("topk_group", ctypes.c_int32), ("group_score", ctypes.c_int32)]
 
 
 class DesError(RuntimeError):
@@ -112,7 +115,8 @@ def _check(code: int) -> None:
 def make_shape(n_seqs: int, n_tokens: int, hidden: int, n_experts: int, ffn: int, top_k: int,
                coreset: int, mode, dtype, ffn_shared: int = 0, k_seq: int = 0,
                weight_layout: int = DES_LAYOUT_ROWMAJOR, residual: int = 0, k_route: int = 0,
-               skip_beta: float = 0.0, router_act=0, vote_renorm: int = 0) -> DesShape:
+               skip_beta: float = 0.0, router_act=0, vote_renorm: int = 0, n_group: int = 0,
+               topk_group: int = 0, group_score=DES_GROUP_MAX) -> DesShape:
     if isinstance(mode, str):
         mode = MODES[mode]
     if isinstance(dtype, str):
@@ -121,7 +125,9 @@ def make_shape(n_seqs: int, n_tokens: int, hidden: int, n_experts: int, ffn: int
         dtype = {torch.float32: DES_F32, torch.bfloat16: DES_BF16}[dtype]
     return DesShape(n_seqs, n_tokens, hidden, n_experts, ffn, ffn_shared, top_k, coreset, k_seq,
                     mode, dtype, weight_layout, residual, k_route, skip_beta,
-                    ROUTER_ACTS[router_act] if isinstance(router_act, str) else router_act, vote_renorm)
+                    ROUTER_ACTS[router_act] if isinstance(router_act, str) else router_act, vote_renorm,
+                    n_group, topk_group,
+                    GROUP_SCORES[group_score] if isinstance(group_score, str) else group_score)
 
 
 def _ptr(t: Optional[torch.Tensor]):

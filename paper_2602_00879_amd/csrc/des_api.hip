@@ -87,6 +87,15 @@ static int check_shape(const des_shape_t* s, bool need_ffn) {
   if (!(s->skip_beta >= 0.0f && s->skip_beta < 1.0f)) return DES_ERR_SHAPE;  // also rejects NaN
   if (s->router_act != DES_ROUTER_SOFTMAX && s->router_act != DES_ROUTER_SIGMOID) return DES_ERR_MODE;
   if (s->vote_renorm != 0 && s->vote_renorm != 1) return DES_ERR_SHAPE;
+  if (s->n_group < 0) return DES_ERR_SHAPE;
+  if (s->n_group > 1) {
+    if (s->n_experts % s->n_group) return DES_ERR_SHAPE;
+    const int gs = s->n_experts / s->n_group;
+    if (gs % 8) return DES_ERR_SHAPE;  // a selector lane owns 8 experts of one group
+    if (s->topk_group < 1 || s->topk_group > s->n_group) return DES_ERR_SHAPE;
+    if (static_cast<long long>(s->topk_group) * gs < s->top_k) return DES_ERR_SHAPE;
+    if (s->group_score != DES_GROUP_MAX && s->group_score != DES_GROUP_TOP2SUM) return DES_ERR_MODE;
+  }
   const int align = s->dtype == DES_BF16 ? 32 : 4;
   if (s->hidden % align) return DES_ERR_SHAPE;
   if (need_ffn) {

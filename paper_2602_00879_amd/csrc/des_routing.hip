@@ -76,6 +76,10 @@ struct RoutingArgs {
   float skip_beta;        // > 0: cumulative-probability skipping of a token's weakest experts
   int sigmoid;            // router weights are sigmoid(logit) instead of softmax over M
   int vote_renorm;        // a token's K votes are divided by their sum
+  int n_group;            // > 1: group-limited router over this many groups of experts
+  int group_lanes;        // selector lanes per group (group size / 8)
+  int topk_group;         // groups a token keeps
+  int group_top2;         // group score: sum of the two best router weights (else the best logit)
   int tiles_m, tiles_t;   // router tiles along experts / tokens
   int do_router, do_select, do_permute, use_flags, bf16;
 };
@@ -378,6 +382,37 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
     sort8_desc(sk, sidx);
 #pragma unroll
     for (int j = 0; j < kEpl; ++j) my_sorted[j * 64] = sk[j];
+    if (a.n_group > 1) {
+      // Group-limited router (a sigma of Sec. 4.1): a group is GL adjacent lanes
+      // of the row.  Its two best keys are merged from the lanes' sorted heads,
+      // its score is ranked against the other groups' (ties to the lowest group),
+      // and the lanes of a group that is not kept offer no candidate from here on.
+      const int GL = a.group_lanes, rowbase = lane - rl;
+      const int gidx = rl / GL, gsrc = min(gidx, a.n_group - 1);  // padding lanes read a real group
+      uint32_t b1 = 0u, b2 = 0u;
+      for (int i = 0; i < GL; ++i) {
+        const int src = rowbase + gsrc * GL + i;
+        const uint32_t k0 = static_cast<uint32_t>(__shfl(static_cast<int>(sk[0]), src));
+        const uint32_t k1 = static_cast<uint32_t>(__shfl(static_cast<int>(sk[1]), src));
+        if (k0 > b1) { b2 = max(b1, k1); b1 = k0; } else { b2 = max(b2, k0); }
+      }
+      uint32_t gs = b1;  // "max": the best logit's key, an exact integer comparison
+      if (a.group_top2) {
+        // sum of the two best router weights, fp32; positive floats order like their
+        // bit patterns.  The softmax denominator is the same for every group of a
+        // token, so the numerators suffice.
+        const float mx = a.sigmoid ? 0.f : key_to_f32(row_max_u32<LPT>(sk[0]));
+        const float s1 = !b1 ? 0.f : a.sigmoid ? sigmoid_f(key_to_f32(b1)) : exp_neg(key_to_f32(b1) - mx);
+        const float s2 = !b2 ? 0.f : a.sigmoid ? sigmoid_f(key_to_f32(b2)) : exp_neg(key_to_f32(b2) - mx);
+        gs = __float_as_uint(s1 + s2);
+      }
+      int grank = 0;
+      for (int j = 0; j < a.n_group; ++j) {
+        const uint32_t o = static_cast<uint32_t>(__shfl(static_cast<int>(gs), rowbase + j * GL));
+        grank += (o > gs || (o == gs && j < gidx)) ? 1 : 0;
+      }
+      if (gidx >= a.n_group || grank >= a.topk_group) nvalid = 0;
+    }
   };
 
   // ---------------------------------------------------------- stage 1: Phi
@@ -622,10 +657,12 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
     uint32_t mkey[NW], m0 = 0u;  // keys drawn at iterations rl, rl + LPT, ...; the first key
 #pragma unroll
     for (int q = 0; q < NW; ++q) mkey[q] = 0u;
+    int have = keff;  // experts this token found (fewer only under a group limit)
     for (int it = 0; it < keff; ++it) {  // S_n = TopK(I_n restricted to C, K), best first
       bool mine;
       const uint32_t m = row_draw<LPT>(hd, mine);  // every lane of the row sees the drawn key
       if (it == 0) m0 = m;
+      if (m == 0u) have = min(have, it);
 #pragma unroll
       for (int q = 0; q < NW; ++q)
         if (it == q * LPT + rl) mkey[q] = m;
@@ -646,7 +683,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
     }
     float den = row_sum_f32<LPT>(part);
     DES_STAMP(a, 17);
-    int keep = keff;
+    int keep = have;
     if (a.skip_beta > 0.f && keff > 1) {
       // Sec. 5.1 (Baselines), adapted NAEE rule: drop experts i..k when their
       // gates sum to less than beta of the total.  Tail sums from the weakest
@@ -662,7 +699,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
           if (it / LPT == q) v = c;
         }
         suf += v;
-        if (suf < thr) keep = it;
+        if (it < have && suf < thr) keep = it;
       }
       part = 0.f;
 #pragma unroll
@@ -906,6 +943,12 @@ static void fill_common(RoutingArgs& a, const des_shape_t& s) {
   a.skip_beta = s.skip_beta;
   a.sigmoid = s.router_act == DES_ROUTER_SIGMOID;
   a.vote_renorm = s.vote_renorm;
+  if (s.n_group > 1 && s.topk_group < s.n_group) {  // keeping every group is no limit
+    a.n_group = s.n_group;
+    a.group_lanes = s.n_experts / s.n_group / kEpl;
+    a.topk_group = s.topk_group;
+    a.group_top2 = s.group_score == DES_GROUP_TOP2SUM;
+  }
 }
 
 int launch_router(const des_shape_t& s, const void* x, const void* w_router, const float* bias,

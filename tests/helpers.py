@@ -21,6 +21,8 @@ LOGIT_ATOL = 5e-5
 GATE_RTOL, GATE_ATOL = 1e-5, 1e-7
 VOTE_MARGIN_MIN = 1e-5
 SKIP_MARGIN_MIN = 1e-5
+GROUP_MARGIN_MIN = 1e-5
+NO_GROUPS = (0, 0, "max")   # (n_group, topk_group, group score)
 
 
 def dev_tensor(a: Optional[np.ndarray], device="cuda") -> Optional[torch.Tensor]:
@@ -45,11 +47,13 @@ def layer_to_device(layer: Dict, device="cuda") -> Dict:
 
 def shape_of(cfg: W.LayerConfig, mode: str, C: Optional[int] = None, k_seq: int = 0,
              layout: int = B.DES_LAYOUT_ROWMAJOR, residual: int = 0, k_route: int = 0,
-             skip_beta: float = 0.0, act: str = "softmax", renorm: bool = False) -> B.DesShape:
+             skip_beta: float = 0.0, act: str = "softmax", renorm: bool = False,
+             groups=NO_GROUPS) -> B.DesShape:
     return B.make_shape(cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k,
                         cfg.coreset if C is None else C, mode, cfg.dtype, ffn_shared=cfg.ffn_shared,
                         k_seq=k_seq, weight_layout=layout, residual=residual, k_route=k_route,
-                        skip_beta=skip_beta, router_act=act, vote_renorm=int(renorm))
+                        skip_beta=skip_beta, router_act=act, vote_renorm=int(renorm),
+                        n_group=groups[0], topk_group=groups[1], group_score=groups[2])
 
 
 def oracle_inputs(layer: Dict) -> Dict:
@@ -62,8 +66,9 @@ def oracle_inputs(layer: Dict) -> Dict:
 
 
 def run_gpu(cfg, layer_dev, mode, C=None, k_seq=0, layout=B.DES_LAYOUT_ROWMAJOR, residual=0,
-            packed_weights=None, k_route=0, skip_beta=0.0, act="softmax", renorm=False):
-    shape = shape_of(cfg, mode, C, k_seq, layout, residual, k_route, skip_beta, act, renorm)
+            packed_weights=None, k_route=0, skip_beta=0.0, act="softmax", renorm=False,
+            groups=NO_GROUPS):
+    shape = shape_of(cfg, mode, C, k_seq, layout, residual, k_route, skip_beta, act, renorm, groups)
     wg, wu, wd = (layer_dev["w_gate"], layer_dev["w_up"], layer_dev["w_down"])
     sh = layer_dev["shared"]
     if packed_weights is not None:
@@ -76,7 +81,7 @@ def run_gpu(cfg, layer_dev, mode, C=None, k_seq=0, layout=B.DES_LAYOUT_ROWMAJOR,
 
 def check_against_oracle(cfg, layer, out, mode, C=None, k_seq=0, residual=False,
                          only_tokens=None, label="", k_route=0, skip_beta=0.0, act="softmax",
-                         renorm=False):
+                         renorm=False, groups=NO_GROUPS):
     """Teacher-forced parity: the oracle is fed the GPU's fp32 logits, so every
     index decision is a function of identical numbers and must match exactly."""
     C = cfg.coreset if C is None else C
@@ -91,7 +96,10 @@ def check_against_oracle(cfg, layer, out, mode, C=None, k_seq=0, residual=False,
     ref = O.moe_forward(oi["x"], oi["w_router"], oi["bias"], oi["w_gate"], oi["w_up"], oi["w_down"],
                         K, C, mode, k_seq=k_seq, shared=oi["shared"], logits_override=g_logits,
                         residual=residual, only_tokens=only_tokens, k_route=k_route,
-                        skip_beta=skip_beta, act=act, renorm=renorm)
+                        skip_beta=skip_beta, act=act, renorm=renorm, n_group=groups[0],
+                        topk_group=groups[1], group_score=groups[2])
+    # two groups ranked by fp32 sums must not be a near tie
+    assert ref["group_margin"] > GROUP_MARGIN_MIN, f"{label}: a group choice is too close to call"
     # a skipped tail decided in fp32 must not sit on the threshold
     assert ref["skip_margin"] > SKIP_MARGIN_MIN, f"{label}: a skip decision is too close to call"
     if mode == "vote":

@@ -67,6 +67,14 @@ def test_workspace_and_capacity_are_host_only():
     (dict(skip_beta=float("nan")), -2),
     (dict(router_act=2), -3),
     (dict(vote_renorm=2), -2),
+    (dict(n_group=-1), -2),
+    (dict(n_group=3, topk_group=1), -2),                 # 128 experts do not split into 3 groups
+    (dict(n_group=32, topk_group=4), -2),                # groups of 4 experts: not whole lanes
+    (dict(n_group=8, topk_group=0), -2),
+    (dict(n_group=8, topk_group=9), -2),
+    (dict(n_group=16, topk_group=1, top_k=9), -2),       # 8 allowed experts cannot fill K = 9
+    (dict(n_group=8, topk_group=4, group_score=0), -3),
+    (dict(n_group=8, topk_group=4, group_score=3), -3),
 ])
 def test_bad_shapes_are_rejected_before_launch(kw, code):
     s = _shape(**kw)

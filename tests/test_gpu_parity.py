@@ -244,6 +244,47 @@ def test_other_routers(act, renorm):
         _say(f"  {r}")
 
 
+GROUPED = dict(
+    # groups of 8 experts = one selector lane each; 24 experts = three lanes (not a power
+    # of two, and 96 experts leave padding lanes in the 128-wide row); 32 experts = four
+    # lanes, the 256-expert layer with 8 groups of which 4 are kept
+    g8=(W.LayerConfig("g8", "bf16", 2, 40, 128, 64, 64, 0, 4, 5, 0.3, 31), (8, 3)),
+    g24=(W.LayerConfig("g24", "bf16", 1, 70, 128, 96, 64, 32, 4, 5, 0.3, 32), (4, 2)),
+    g32=(W.LayerConfig("g32", "bf16", 3, 24, 256, 256, 128, 0, 8, 12, 0.3, 33), (8, 4)),
+)
+
+
+@pytest.mark.parametrize("name", list(GROUPED))
+@pytest.mark.parametrize("act,score", [("softmax", "max"), ("sigmoid", "top2sum"), ("softmax", "top2sum")])
+def test_group_limited_routers(name, act, score):
+    """Group-limited routers (Sec. 4.1: sigma comes from the model architecture): all
+    three modes; tokens whose groups hold fewer than K coreset experts use fewer."""
+    cfg, (n_group, topk_group) = GROUPED[name]
+    groups = (n_group, topk_group, score)
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    short = 0
+    for mode in ("vanilla", "seq", "vote"):
+        _say(f"{name} groups={groups} {act} {mode}")
+        out = H.run_gpu(cfg, dev, mode, act=act, groups=groups)
+        r = H.check_against_oracle(cfg, layer, out, mode, act=act, groups=groups,
+                                   label=f"{name} {groups} {act} {mode}")
+        used = (out.topk_idx >= 0).sum(dim=-1)
+        short += int((used < cfg.top_k).sum())
+        _say(f"  {r} experts per token {int(used.min())}..{int(used.max())}")
+        if mode == "vanilla":
+            assert int(used.min()) == cfg.top_k
+    assert short > 0, "no token ran short of coreset experts: the case is not covered"
+    # with skipping and fewer experts per token on top
+    out = H.run_gpu(cfg, dev, "vote", act=act, groups=groups, k_route=3, skip_beta=0.2)
+    H.check_against_oracle(cfg, layer, out, "vote", act=act, groups=groups, k_route=3, skip_beta=0.2,
+                           label=f"{name} {groups} {act} vote k3 skip")
+    # keeping every group is no limit at all
+    base = H.run_gpu(cfg, dev, "vote", act=act)
+    same = H.run_gpu(cfg, dev, "vote", act=act, groups=(n_group, n_group, score))
+    assert torch.equal(base.topk_idx, same.topk_idx) and torch.equal(base.y, same.y)
+
+
 def test_skipping_on_the_128_expert_layer():
     """Vanilla routing with skipping (the baseline the paper compares against) and
     DES-Vote with k = 4 of 8 on the benchmark layer: routing exact, outputs sampled."""
