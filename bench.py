@@ -281,25 +281,36 @@ def bench_selection(args, torch, B, W, dev):
     iters = max(args.steps, 200)
     outs = B.des_select_coreset(shape, logits)  # outputs allocated once, as a serving loop would
     hip_us = timed(lambda: B.des_select_coreset(shape, logits, out=outs), iters)
+    # the same launch with the votes added by floating-point LDS atomics (arrival order)
+    shape_at = B.make_shape(1, N, 32, M, 32, K, C, "vote", "f32", vote_atomic=1)
+    atomic_us = timed(lambda: B.des_select_coreset(shape_at, logits, out=outs), iters)
+    at = B.des_select_coreset(shape_at, logits)
     torch_us = timed(lambda: torch_select(logits[0]), iters)
     # same coreset (the torch version breaks exact ties arbitrarily; none occur here)
     ours = B.des_select_coreset(shape, logits)
     n = int(ours["coreset_size"][0])
     same = ours["coreset_idx"][0, :n].tolist() == torch_select(logits[0]).tolist()[:n]
-    B.des_kernel_timing_enable(True)
-    for _ in range(50):
-        B.des_select_coreset(shape, logits)
-    torch.cuda.synchronize()
-    kt = B.des_kernel_timing_read()
-    B.des_kernel_timing_enable(False)
+    same_atomic = torch.equal(at["coreset_idx"], ours["coreset_idx"])
+    kern = {}
+    for name, sh in (("fixed_order", shape), ("atomic", shape_at)):
+        B.des_kernel_timing_enable(True)
+        for _ in range(50):
+            B.des_select_coreset(sh, logits)
+        torch.cuda.synchronize()
+        kt = B.des_kernel_timing_read()
+        B.des_kernel_timing_enable(False)
+        kern[name] = kt["select"][0] * 1e3 / max(1, kt["select"][1])
     print(json.dumps({
         "metric": "DES-Vote coreset selection us per block (host wall-clock per call)",
         "value": hip_us, "unit": "us/block", "n_gpus": 1, "steps": iters, "higher_is_better": False,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"selection only: N={N} M={M} K={K} C={C} zipf_s={cfg.zipf_s}"},
-        "hip_launches": 1, "hip_kernel_us": kt["select"][0] * 1e3 / max(1, kt["select"][1]),
+        "hip_launches": 1, "hip_kernel_us": kern["fixed_order"],
         "torch_ops_us": torch_us, "speedup_vs_torch_ops": torch_us / hip_us,
         "same_coreset": bool(same),
+        "vote_reduction": {"fixed_order_us": hip_us, "atomic_us": atomic_us,
+                           "fixed_order_kernel_us": kern["fixed_order"], "atomic_kernel_us": kern["atomic"],
+                           "same_coreset": bool(same_atomic)},
     }))
 
 

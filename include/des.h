@@ -120,13 +120,18 @@ typedef struct {
   int32_t group_score;   /* des_group_score_t.  "max" compares logits (exact);     */
                          /* "top2sum" adds two fp32 router weights per group, and  */
                          /* two groups within ~1e-6 (relative) may swap            */
+  int32_t vote_atomic;   /* 1: the votes of Eq. 6 meet in floating-point atomic    */
+                         /* adds, in arrival order, as the selection kernels of    */
+                         /* Sec. 4.3 do: V may differ in its last bits from run to */
+                         /* run (and two experts within ~1e-6 of each other may    */
+                         /* swap).  0: fixed-order sum, bit-identical every run    */
 } des_shape_t;
 
 /*
  * Limits checked by every entry point (DES_ERR_SHAPE otherwise):
  *   B, N, D, M, F, K >= 1;  K <= M;  K <= 32;  M <= 512;  B*N <= 4096;
  *   M * ceil(B*N/64) <= 4096;  C >= 1 in seq / vote mode;  0 <= k_seq <= K;
- *   0 <= k_route <= K;  0 <= skip_beta < 1;  router_act, vote_renorm in {0, 1};
+ *   0 <= k_route <= K;  0 <= skip_beta < 1;  router_act, vote_renorm, vote_atomic in {0, 1};
  *   n_group > 1: M a multiple of n_group, the group size M/n_group a multiple of 8,
  *   1 <= topk_group <= n_group, topk_group * (M/n_group) >= K (a token can always
  *   nominate K experts), group_score a des_group_score_t (DES_ERR_MODE otherwise);

@@ -40,7 +40,8 @@ class DesShape(ctypes.Structure):
         "n_seqs", "n_tokens", "hidden", "n_experts", "ffn", "ffn_shared", "top_k", "coreset",
         "k_seq", "mode", "dtype", "weight_layout", "residual", "k_route")] + [
         ("skip_beta", ctypes.c_float), ("router_act", ctypes.c_int32), ("vote_renorm", ctypes.c_int32),
-        ("n_group", ctypes.c_int32), ("topk_group", ctypes.c_int32), ("group_score", ctypes.c_int32)]
+        ("n_group", ctypes.c_int32), ("topk_group", ctypes.c_int32), ("group_score", ctypes.c_int32),
+        ("vote_atomic", ctypes.c_int32)]
 
 
 class DesError(RuntimeError):
@@ -116,7 +117,7 @@ def make_shape(n_seqs: int, n_tokens: int, hidden: int, n_experts: int, ffn: int
                coreset: int, mode, dtype, ffn_shared: int = 0, k_seq: int = 0,
                weight_layout: int = DES_LAYOUT_ROWMAJOR, residual: int = 0, k_route: int = 0,
                skip_beta: float = 0.0, router_act=0, vote_renorm: int = 0, n_group: int = 0,
-               topk_group: int = 0, group_score=DES_GROUP_MAX) -> DesShape:
+               topk_group: int = 0, group_score=DES_GROUP_MAX, vote_atomic: int = 0) -> DesShape:
     if isinstance(mode, str):
         mode = MODES[mode]
     if isinstance(dtype, str):
@@ -127,7 +128,7 @@ def make_shape(n_seqs: int, n_tokens: int, hidden: int, n_experts: int, ffn: int
                     mode, dtype, weight_layout, residual, k_route, skip_beta,
                     ROUTER_ACTS[router_act] if isinstance(router_act, str) else router_act, vote_renorm,
                     n_group, topk_group,
-                    GROUP_SCORES[group_score] if isinstance(group_score, str) else group_score)
+                    GROUP_SCORES[group_score] if isinstance(group_score, str) else group_score, vote_atomic)
 
 
 def _ptr(t: Optional[torch.Tensor]):

@@ -87,6 +87,7 @@ static int check_shape(const des_shape_t* s, bool need_ffn) {
   if (!(s->skip_beta >= 0.0f && s->skip_beta < 1.0f)) return DES_ERR_SHAPE;  // also rejects NaN
   if (s->router_act != DES_ROUTER_SOFTMAX && s->router_act != DES_ROUTER_SIGMOID) return DES_ERR_MODE;
   if (s->vote_renorm != 0 && s->vote_renorm != 1) return DES_ERR_SHAPE;
+  if (s->vote_atomic != 0 && s->vote_atomic != 1) return DES_ERR_SHAPE;
   if (s->n_group < 0) return DES_ERR_SHAPE;
   if (s->n_group > 1) {
     if (s->n_experts % s->n_group) return DES_ERR_SHAPE;

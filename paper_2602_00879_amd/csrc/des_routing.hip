@@ -80,6 +80,8 @@ struct RoutingArgs {
   int group_lanes;        // selector lanes per group (group size / 8)
   int topk_group;         // groups a token keeps
   int group_top2;         // group score: sum of the two best router weights (else the best logit)
+  int vote_atomic;        // votes meet in floating-point LDS atomics (arrival order) instead of
+                          // the fixed-order reduction
   int tiles_m, tiles_t;   // router tiles along experts / tokens
   int do_router, do_select, do_permute, use_flags, bf16;
 };
@@ -348,6 +350,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
     s_rank[e] = 0;
     s_key[e] = 0u;
     s_core[e] = (a.mode == DES_VANILLA && e < M) ? 1 : 0;
+    s_vpart[e] = 0.f;  // the accumulator of the atomic vote variant
   }
   if (threadIdx.x < 36) s_hist[threadIdx.x] = 0;
   // the LDS set-up above does not need the logits: only now wait for the router
@@ -473,12 +476,20 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
           const float tot = row_sum_f32<LPT>(mine_sum);
           scale = tot > 0.f ? 1.0f / tot : 0.f;
         }
+        if (a.vote_atomic) {
+          // the variant Sec. 4.3 describes: every vote is an atomic add into the
+          // shared vector, in whatever order the lanes arrive
 #pragma unroll
-        for (int j = 0; j < kEpl; ++j) vacc[j] += ((taken >> j) & 1u) ? p[j] * scale : 0.f;  // Eq. 6
+          for (int j = 0; j < kEpl; ++j)
+            if ((taken >> j) & 1u) atomicAdd(&s_vpart[rl * kEpl + j], p[j] * scale);
+        } else {
+#pragma unroll
+          for (int j = 0; j < kEpl; ++j) vacc[j] += ((taken >> j) & 1u) ? p[j] * scale : 0.f;  // Eq. 6
+        }
       }
     }
     DES_STAMP(a, 2);
-    if (vote) {
+    if (vote && !a.vote_atomic) {
       // rows of a wave in a fixed pairwise order, then waves in order
 #pragma unroll
       for (int j = 0; j < kEpl; ++j) {
@@ -493,7 +504,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
     __syncthreads();
     DES_STAMP(a, 11);
 
-    if (vote) {  // this workgroup's votes: waves in order
+    if (vote && !a.vote_atomic) {  // this workgroup's votes: waves in order
       float vloc[(MP + kRtThreads - 1) / kRtThreads];
       int q = 0;
       for (int e = threadIdx.x; e < MP; e += kRtThreads, ++q) {
@@ -943,6 +954,7 @@ static void fill_common(RoutingArgs& a, const des_shape_t& s) {
   a.skip_beta = s.skip_beta;
   a.sigmoid = s.router_act == DES_ROUTER_SIGMOID;
   a.vote_renorm = s.vote_renorm;
+  a.vote_atomic = s.vote_atomic;
   if (s.n_group > 1 && s.topk_group < s.n_group) {  // keeping every group is no limit
     a.n_group = s.n_group;
     a.group_lanes = s.n_experts / s.n_group / kEpl;

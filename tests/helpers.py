@@ -48,12 +48,13 @@ def layer_to_device(layer: Dict, device="cuda") -> Dict:
 def shape_of(cfg: W.LayerConfig, mode: str, C: Optional[int] = None, k_seq: int = 0,
              layout: int = B.DES_LAYOUT_ROWMAJOR, residual: int = 0, k_route: int = 0,
              skip_beta: float = 0.0, act: str = "softmax", renorm: bool = False,
-             groups=NO_GROUPS) -> B.DesShape:
+             groups=NO_GROUPS, vote_atomic: int = 0) -> B.DesShape:
     return B.make_shape(cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k,
                         cfg.coreset if C is None else C, mode, cfg.dtype, ffn_shared=cfg.ffn_shared,
                         k_seq=k_seq, weight_layout=layout, residual=residual, k_route=k_route,
                         skip_beta=skip_beta, router_act=act, vote_renorm=int(renorm),
-                        n_group=groups[0], topk_group=groups[1], group_score=groups[2])
+                        n_group=groups[0], topk_group=groups[1], group_score=groups[2],
+                        vote_atomic=vote_atomic)
 
 
 def oracle_inputs(layer: Dict) -> Dict:
@@ -67,8 +68,9 @@ def oracle_inputs(layer: Dict) -> Dict:
 
 def run_gpu(cfg, layer_dev, mode, C=None, k_seq=0, layout=B.DES_LAYOUT_ROWMAJOR, residual=0,
             packed_weights=None, k_route=0, skip_beta=0.0, act="softmax", renorm=False,
-            groups=NO_GROUPS):
-    shape = shape_of(cfg, mode, C, k_seq, layout, residual, k_route, skip_beta, act, renorm, groups)
+            groups=NO_GROUPS, vote_atomic=0):
+    shape = shape_of(cfg, mode, C, k_seq, layout, residual, k_route, skip_beta, act, renorm, groups,
+                     vote_atomic)
     wg, wu, wd = (layer_dev["w_gate"], layer_dev["w_up"], layer_dev["w_down"])
     sh = layer_dev["shared"]
     if packed_weights is not None:

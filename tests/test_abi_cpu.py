@@ -67,6 +67,7 @@ def test_workspace_and_capacity_are_host_only():
     (dict(skip_beta=float("nan")), -2),
     (dict(router_act=2), -3),
     (dict(vote_renorm=2), -2),
+    (dict(vote_atomic=2), -2),
     (dict(n_group=-1), -2),
     (dict(n_group=3, topk_group=1), -2),                 # 128 experts do not split into 3 groups
     (dict(n_group=32, topk_group=4), -2),                # groups of 4 experts: not whole lanes

@@ -42,7 +42,7 @@ def test_route_logits_and_softmax(dtype, T, D, M, bias):
 
 
 # --------------------------------------------------------- des_select_coreset
-def _select_case(N, M, K, C, mode, k_seq, seed, B_=1, ties=False, zipf=0.0):
+def _select_case(N, M, K, C, mode, k_seq, seed, B_=1, ties=False, zipf=0.0, vote_atomic=0):
     Ls = []
     for b in range(B_):
         L = W.make_logits(N, M, seed * 31 + b, zipf_s=zipf, scale=2.0)
@@ -51,7 +51,7 @@ def _select_case(N, M, K, C, mode, k_seq, seed, B_=1, ties=False, zipf=0.0):
             L[L == 0] = np.where(np.arange((L == 0).sum()) % 2 == 0, 0.0, -0.0).astype(np.float32)
         Ls.append(L)
     logits = np.stack(Ls)
-    shape = B.make_shape(B_, N, 32, M, 32, K, C, mode, "f32", k_seq=k_seq)
+    shape = B.make_shape(B_, N, 32, M, 32, K, C, mode, "f32", k_seq=k_seq, vote_atomic=vote_atomic)
     out = B.des_select_coreset(shape, torch.from_numpy(logits).cuda())
     torch.cuda.synchronize()
     cap = B.des_coreset_capacity(shape)
@@ -85,6 +85,25 @@ def test_select_coreset_shapes(mode):
         _say(f"select {mode} N={N} M={M} K={K} C={C}")
         _select_case(N, M, K, C, mode, 0, seed=100 + i, B_=1 + (i % 3))
         _select_case(N, M, K, C, mode, 0, seed=200 + i, ties=True)
+
+
+def test_votes_added_with_atomics():
+    """The variant of the vote reduction that Sec. 4.3 describes (floating-point atomic
+    adds in arrival order): same coreset wherever the oracle's margin is clear, votes
+    equal to rounding; also over several selector workgroups and in the whole layer."""
+    for i, (N, M, K, C, B_) in enumerate([(32, 128, 8, 32, 1), (128, 128, 8, 32, 2), (32, 256, 8, 16, 3),
+                                          (150, 100, 5, 17, 2), (64, 512, 8, 48, 1), (7, 65, 3, 65, 1)]):
+        _say(f"atomic votes N={N} M={M} K={K} C={C} B={B_}")
+        _select_case(N, M, K, C, "vote", 0, seed=700 + i, B_=B_, vote_atomic=1)
+    cfg = W.CONFIGS["m128_zipf"]
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    out = H.run_gpu(cfg, dev, "vote", vote_atomic=1)
+    r = H.check_against_oracle(cfg, layer, out, "vote", only_tokens=_sample_tokens(cfg, 4, 9),
+                               label="m128 atomic votes")
+    _say(f"  {r}")
+    ref = H.run_gpu(cfg, dev, "vote")
+    assert torch.equal(out.topk_idx, ref.topk_idx) and torch.equal(out.y, ref.y)
 
 
 def test_select_seq_explicit_k_and_overflow():
