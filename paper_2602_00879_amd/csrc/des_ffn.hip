@@ -49,6 +49,7 @@ struct FfnArgs {
   const int32_t* slot_of;       // [M] slot of a live expert
   int32_t* n_unique;            // set to -1 if a bounded wait expires
   int n_waves;                  // wavefronts of the single-launch grid
+  int splits;                   // workgroups an expert's pairs are spread over (LDS kernels)
 };
 
 constexpr int kFfnMaxWaitIters = 1 << 22;
@@ -864,27 +865,35 @@ __device__ __forceinline__ void dma_stream_gemm(const uint16_t* a0, const uint16
 constexpr int kLdsBufElems = 8192;
 __host__ __device__ constexpr int lds_elems(int kd) { return (kd > 0 ? 3 : 2) * kLdsBufElems; }
 
-// Which expert and which pairs a workgroup works on (as Task), shared by the two kernels.
+// Which expert, which of its row groups and which pairs a workgroup works on,
+// shared by the two kernels.  The grid is one-dimensional and read in hand-out
+// order: the shared expert first (every token: the longest workgroups), then the
+// slots, which the permutation orders by falling pair count, each with its
+// `splits` token splits next to each other (they read the same weights) - when
+// the workgroups do not all fit on the chip at once, the long ones start first.
 template <bool DOWN>
-__device__ __forceinline__ bool lds_task(const FfnArgs& a, int per_expert, int& group, Task& t,
-                                         FfnArgs& v, int lane) {
-  const int routed = a.n_slots * per_expert;
-  const int task = blockIdx.x;
+__device__ __forceinline__ bool lds_task(const FfnArgs& a, int per_expert, int per_shared, int splits,
+                                         int& group, int& split, Task& t, FfnArgs& v, int lane) {
+  int bx = blockIdx.x;
   v = a;
-  if (task < routed) {
-    if (!make_task(a, task / per_expert, false, DOWN, t, lane)) return false;
-    group = task % per_expert;
-  } else {
+  if (bx < per_shared * splits) {
     make_task(a, 0, true, DOWN, t, lane);
     v = shared_view(a, t, 2);
-    group = task - routed;
+    split = bx / per_shared;
+    group = bx % per_shared;
+    return true;
   }
-  return true;
+  bx -= per_shared * splits;
+  const int slot = bx / (per_expert * splits), r = bx % (per_expert * splits);
+  if (slot >= a.n_slots) return false;
+  split = r / per_expert;
+  group = r % per_expert;
+  return make_task(a, slot, false, DOWN, t, lane);
 }
 
 // MAXNT = token tiles per workgroup pass (the LDS buffer holds 16*MAXNT rows);
 // LW = wavefronts per workgroup; KD = the reduction length when the host knows
-// it to be one of the unrolled cases, else 0.  blockIdx.y picks every gridDim.y-th group of
+// it to be one of the unrolled cases, else 0.  A split takes every splits-th group of
 // 16*MAXNT pairs of the expert: an expert with more pairs than one pass holds
 // is spread over several workgroups (its weights are then read once per pass).
 template <bool PACKED, int MAXNT, int LW, int KD>
@@ -895,12 +904,12 @@ __global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void g
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   Task t;
   FfnArgs v;
-  int group;
+  int group, split;
   const int per_r = (a.F / 16 + LW - 1) / LW;
   const int per_s = (a.Fs / 16 + LW - 1) / LW;
-  if (static_cast<int>(blockIdx.x) >= a.n_slots * per_r + per_s) return;
+  const int splits = a.splits;
   DES_FSTAMP(blockIdx.x, 0);
-  if (!lds_task<false>(a, per_r, group, t, v, lane)) return;  // uniform per workgroup
+  if (!lds_task<false>(a, per_r, per_s, splits, group, split, t, v, lane)) return;  // uniform per workgroup
   const int tile = group * LW + wave;
   const bool active = tile < t.fdim / 16;
   const uint16_t* w0 = uniform_ptr(t.w0);
@@ -909,7 +918,7 @@ __global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void g
   const uint32_t wlo = tile_lane_off<PACKED>(a.D, lane);
   const uint16_t* x = uniform_ptr(static_cast<const uint16_t*>(a.x));
   uint16_t* h = static_cast<uint16_t*>(v.h);
-  for (int g0 = blockIdx.y * kRows; g0 < t.count; g0 += gridDim.y * kRows) {
+  for (int g0 = split * kRows; g0 < t.count; g0 += splits * kRows) {
     const int rows = min(kRows, t.count - g0);
     const int nt = (rows + 15) / 16;
     auto row_off = [&](int r) {
@@ -947,7 +956,8 @@ __global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void g
   }
 #ifdef DES_FFN_STAMPS
   DES_FSTAMP(blockIdx.x, 2);
-  if (threadIdx.x == 0 && blockIdx.x < 8192 && blockIdx.y == 0) g_ffn_stamps[blockIdx.x * 4 + 3] = t.count;
+  if (threadIdx.x == 0 && blockIdx.x < 8192)  // pairs this workgroup worked on
+    g_ffn_stamps[blockIdx.x * 4 + 3] = max(0, min(static_cast<int>(t.count) - split * kRows, kRows));
 #endif
 }
 
@@ -959,11 +969,11 @@ __global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void d
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   Task t;
   FfnArgs v;
-  int group;
+  int group, split;
   const int dtiles = a.D / 16;                       // even: D is a multiple of 32
   const int per = (dtiles / 2 + LW - 1) / LW;        // a wavefront owns two row tiles
-  if (static_cast<int>(blockIdx.x) >= a.n_slots * per + (a.Fs > 0 ? per : 0)) return;
-  if (!lds_task<true>(a, per, group, t, v, lane)) return;
+  const int splits = a.splits;
+  if (!lds_task<true>(a, per, a.Fs > 0 ? per : 0, splits, group, split, t, v, lane)) return;
   const int dt0 = (group * LW + wave) * 2;
   const bool active = dt0 < dtiles;
   const int F = t.fdim;
@@ -973,7 +983,7 @@ __global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void d
   const uint32_t wlo = tile_lane_off<PACKED>(F, lane);
   const uint16_t* h = uniform_ptr(static_cast<const uint16_t*>(v.h));
   const size_t orow0 = t.shared ? static_cast<size_t>(a.T) * a.K : static_cast<size_t>(t.pair0);
-  for (int g0 = blockIdx.y * kRows; g0 < t.count; g0 += gridDim.y * kRows) {
+  for (int g0 = split * kRows; g0 < t.count; g0 += splits * kRows) {
     const int rows = min(kRows, t.count - g0);
     const int nt = (rows + 15) / 16;
     const int hrow0 = static_cast<int>(t.row_base) + g0;
@@ -1332,6 +1342,7 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
   a.D = s.hidden; a.M = s.n_experts; a.F = s.ffn; a.Fs = s.ffn_shared; a.K = s.top_k;
   a.n_slots = max_live_experts(s);
   a.residual = s.residual;
+  a.splits = 1;
   a.h_ready = reinterpret_cast<unsigned long long*>(ws + w.ffn_flags);
   a.o_ready = a.h_ready + ffn_h_flags(s);
   a.epoch = epoch;
@@ -1400,7 +1411,7 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     if (a.T > 32 && chunked && !fused_requested) {
       // Larger blocks: activations staged through LDS.  Token rows per workgroup
       // pass: 64 while no expert can have more, else 128; an expert with more
-      // pairs is spread over grid.y (at most 8 ways).  Wavefronts per workgroup:
+      // pairs is spread over up to 8 workgroups (splits).  Wavefronts per workgroup:
       // two give the finest spread of the weight bytes over the compute units;
       // four share the staged activations among more weight rows, which
       // measured better once experts have many tokens (48-layer stack: 7.7 ms
@@ -1414,7 +1425,8 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
       const int gu_lds = a.n_slots * ((a.F / 16 + gu_lw - 1) / gu_lw) + (a.Fs / 16 + gu_lw - 1) / gu_lw;
       const int per_dn = (a.D / 32 + dn_lw - 1) / dn_lw;
       const int dn_lds = a.n_slots * per_dn + (a.Fs > 0 ? per_dn : 0);
-      const dim3 gg(gu_lds, splits), dg(dn_lds, splits);
+      const dim3 gg(gu_lds * splits), dg(dn_lds * splits);
+      a.splits = splits;
       // unrolled reduction lengths (the shared expert shares the down launch)
       const int gu_kd = a.D == 2048 ? 2048 : 0;
       const int dn_kd = (a.Fs != 0 && a.Fs != a.F) ? 0 : (a.F == 768 || a.F == 512) ? a.F : 0;

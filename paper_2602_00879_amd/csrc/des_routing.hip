@@ -318,7 +318,10 @@ __device__ __forceinline__ uint32_t row_draw(const Head& hd, bool& mine) {
 // stores nothing to global memory: the selector workgroup uses it to pull its
 // code into the instruction cache while it waits for the router tiles (every
 // index below derives from lane and slot numbers, never from the data read).
-template <int LPT>
+// EXT = the variants few callers use (group-limited router, votes added with
+// floating-point atomics) are compiled in; the plain instantiation leaves them
+// out, so the common path pays nothing for them.
+template <int LPT, bool EXT>
 __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, bool dry,
                                 bool wait_router) {
   using L = SelLds<LPT>;
@@ -385,7 +388,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
     sort8_desc(sk, sidx);
 #pragma unroll
     for (int j = 0; j < kEpl; ++j) my_sorted[j * 64] = sk[j];
-    if (a.n_group > 1) {
+    if (EXT && a.n_group > 1) {
       // Group-limited router (a sigma of Sec. 4.1): a group is GL adjacent lanes
       // of the row.  Its two best keys are merged from the lanes' sorted heads,
       // its score is ranked against the other groups' (ties to the lowest group),
@@ -476,7 +479,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
           const float tot = row_sum_f32<LPT>(mine_sum);
           scale = tot > 0.f ? 1.0f / tot : 0.f;
         }
-        if (a.vote_atomic) {
+        if (EXT && a.vote_atomic) {
           // the variant Sec. 4.3 describes: every vote is an atomic add into the
           // shared vector, in whatever order the lanes arrive
 #pragma unroll
@@ -489,7 +492,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
       }
     }
     DES_STAMP(a, 2);
-    if (vote && !a.vote_atomic) {
+    if (vote && !(EXT && a.vote_atomic)) {
       // rows of a wave in a fixed pairwise order, then waves in order
 #pragma unroll
       for (int j = 0; j < kEpl; ++j) {
@@ -504,7 +507,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
     __syncthreads();
     DES_STAMP(a, 11);
 
-    if (vote && !a.vote_atomic) {  // this workgroup's votes: waves in order
+    if (vote && !(EXT && a.vote_atomic)) {  // this workgroup's votes: waves in order
       float vloc[(MP + kRtThreads - 1) / kRtThreads];
       int q = 0;
       for (int e = threadIdx.x; e < MP; e += kRtThreads, ++q) {
@@ -744,6 +747,7 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
   int* s_cnt = reinterpret_cast<int*>(member + static_cast<size_t>(M) * words);  // [M]
   int* s_off = s_cnt + M;                                          // [M+1]
   int* s_liv = s_off + M + 1;                                      // [M+1]
+  int* s_slot = s_liv + M + 1;                                     // [M] slot of a live expert
   const int tid = threadIdx.x;
   const int TK = T * K;
 
@@ -761,9 +765,32 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
     int c = 0;
     for (int w = 0; w < words; ++w) c += __popc(member[static_cast<size_t>(e) * words + w]);
     s_cnt[e] = c;
+    s_slot[e] = 0;
     a.expert_counts[e] = c;
   }
   __syncthreads();
+  // Slot order.  Up to 32 tokens every FFN task is on the chip at once and the
+  // order does not matter: live experts by index.  Longer blocks: most pairs
+  // first (ties to the lowest expert index), because the FFN launches hand out
+  // their workgroups in slot order and, when not all of them fit on the chip at
+  // once, the long ones must not be the ones that start last.  Rank by counting,
+  // the comparison range split over the threads that share an expert; the
+  // partial ranks meet in an integer LDS add.
+  const bool by_count = T > 32;
+  if (by_count) {
+    const int P = max(1, kRtThreads / M), CH = (M + P - 1) / P;
+    for (int t = tid; t < M * P; t += kRtThreads) {
+      const int e = t % M, j0 = (t / M) * CH, j1 = min(j0 + CH, M);
+      const int ce = s_cnt[e];
+      if (ce == 0) continue;
+      int r = 0;
+      for (int j = j0; j < j1; ++j) {
+        const int cj = s_cnt[j];
+        r += (cj > ce || (cj == ce && j < e)) ? 1 : 0;
+      }
+      if (r) atomicAdd(&s_slot[e], r);
+    }
+  }
   if (tid < 64) {  // exclusive scans of counts and of (count > 0), 64 experts at a time
     int base_c = 0, base_l = 0;
     for (int c0 = 0; c0 < M; c0 += 64) {
@@ -796,9 +823,10 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
   const int n_live = s_liv[M];
   for (int e = tid; e <= M; e += kRtThreads) a.offsets[e] = s_off[e];
   for (int e = tid; e < M; e += kRtThreads) {
-    const bool live = s_cnt[e] > 0 && s_liv[e] < a.n_slots;
-    if (live) a.slots[s_liv[e]] = make_int4(e, s_off[e], s_cnt[e], 0);
-    a.slot_of[e] = live ? s_liv[e] : -1;
+    const int sl = by_count ? s_slot[e] : s_liv[e];
+    const bool live = s_cnt[e] > 0 && sl < a.n_slots;
+    if (live) a.slots[sl] = make_int4(e, s_off[e], s_cnt[e], 0);
+    a.slot_of[e] = live ? sl : -1;
   }
   for (int i = tid; i < a.n_ffn_flags; i += kRtThreads) a.ffn_flags[i] = 0ull;
   for (int s = n_live + tid; s < a.n_slots; s += kRtThreads) a.slots[s] = make_int4(-1, 0, 0, 0);
@@ -817,18 +845,19 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
     a.pair_tok[r] = t;
     a.pos[p] = r;
     const int within = r - s_off[e];
-    if (within < kSlotToks && s_liv[e] < a.n_slots)
-      a.slot_tok[s_liv[e] * kSlotToks + within] = static_cast<uint16_t>(t);
+    const int sl = by_count ? s_slot[e] : s_liv[e];
+    if (within < kSlotToks && sl < a.n_slots)
+      a.slot_tok[sl * kSlotToks + within] = static_cast<uint16_t>(t);
   }
 }
 
 // ---------------------------------------------------------------- the kernel
 // LDS of the routing kernel: the selection's carve-up, but at least what the
 // router tile (16 KB) and the permutation (bitmap of at most 8192 words plus
-// 3M+2 counters, under 40 KB for every shape the library accepts) need.
-constexpr int kMinRoutingLds = 40 * 1024;
+// 4M+2 counters, under 42 KB for every shape the library accepts) need.
+constexpr int kMinRoutingLds = 42 * 1024;
 
-template <int LPT>
+template <int LPT, bool EXT>
 __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
   constexpr int kLds = SelLds<LPT>::total > kMinRoutingLds ? SelLds<LPT>::total : kMinRoutingLds;
   __shared__ __align__(16) char smem[kLds];
@@ -852,7 +881,7 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
   const int n_flags = all_tiles + 2 * a.B * a.groups;
   if (blk < n_sel) {  // ---- role S
     DES_STAMP(a, 0);
-    if (!select_sequence<LPT>(a, blk / a.groups, blk % a.groups, smem, false,
+    if (!select_sequence<LPT, EXT>(a, blk / a.groups, blk % a.groups, smem, false,
                               a.use_flags && a.do_router)) {
       if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
       return;
@@ -916,11 +945,17 @@ __global__ __launch_bounds__(64) void softmax_kernel(const float* __restrict__ l
 static int launch_routing_grid(const RoutingArgs& a, int grid, int kernel_id, hipStream_t st) {
   const int lanes = (a.M + kEpl - 1) / kEpl;  // lanes a token's experts need, 8 experts each
   const dim3 g(grid), b(kRtThreads);
-  if (lanes <= 4) launch(kernel_id, routing_kernel<4>, g, b, 0, st, a);
-  else if (lanes <= 8) launch(kernel_id, routing_kernel<8>, g, b, 0, st, a);
-  else if (lanes <= 16) launch(kernel_id, routing_kernel<16>, g, b, 0, st, a);
-  else if (lanes <= 32) launch(kernel_id, routing_kernel<32>, g, b, 0, st, a);
-  else launch(kernel_id, routing_kernel<64>, g, b, 0, st, a);
+#define DES_LAUNCH_ROUTING(EXT)                                                     \
+  do {                                                                             \
+    if (lanes <= 4) launch(kernel_id, routing_kernel<4, EXT>, g, b, 0, st, a);       \
+    else if (lanes <= 8) launch(kernel_id, routing_kernel<8, EXT>, g, b, 0, st, a);  \
+    else if (lanes <= 16) launch(kernel_id, routing_kernel<16, EXT>, g, b, 0, st, a); \
+    else if (lanes <= 32) launch(kernel_id, routing_kernel<32, EXT>, g, b, 0, st, a); \
+    else launch(kernel_id, routing_kernel<64, EXT>, g, b, 0, st, a);                 \
+  } while (0)
+  if (a.n_group > 1 || a.vote_atomic) DES_LAUNCH_ROUTING(true);
+  else DES_LAUNCH_ROUTING(false);
+#undef DES_LAUNCH_ROUTING
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? DES_OK : hip_fail(e, "routing launch");
 }
