@@ -105,6 +105,20 @@ inline size_t ffn_o_flags(const des_shape_t& s) {
 
 constexpr int kSlotToks = 32;  // tokens per slot kept in the slot-major token table
 
+// Blocks of more than 32 tokens: an expert's pairs are handed to the FFN
+// workgroups in units of this many token rows (what one workgroup pass holds),
+// at most kMaxSplits units per expert (an expert with more rows has each unit
+// take several passes).  The permutation lists the live units, longest expert
+// first; the FFN launches index that list, so no workgroup is spent on units
+// that do not exist and neighbouring workgroups have neighbouring units.
+inline int lds_rows_pass(int T) { return T <= 64 ? 64 : 128; }
+constexpr int kMaxSplits = 8;
+inline int max_units(const des_shape_t& s) {
+  const long long TK = static_cast<long long>(s.n_seqs) * s.n_tokens * s.top_k;
+  const int rows = lds_rows_pass(s.n_seqs * s.n_tokens);
+  return max_live_experts(s) + static_cast<int>((TK + rows - 1) / rows);
+}
+
 // The selector workgroup (1024 threads) gives a token max(4, next power of two of
 // ceil(M/8)) lanes, so it handles this many tokens at once; longer sequences are
 // spread over up to kMaxSelGroups selector workgroups (all sequences together),
@@ -126,9 +140,10 @@ struct WsLayout {
   size_t slot_tok;  // u16   [n_slots][kSlotToks]  tokens of each slot's first pairs
   size_t offsets;   // int32 [M + 1]   exclusive scan of expert_counts
   size_t slots;     // int4  [n_slots] {expert, first sorted pair, pairs, 0}; expert -1 = unused
-  size_t meta;      // int32 [64]      [0] live experts, [1] routed pairs
+  size_t meta;      // int32 [64]      [0] live experts, [1] routed pairs, [2] live units
   size_t pair_tok;  // int32 [T*K]     token of each pair, pairs sorted by (expert, token)
   size_t pos;       // int32 [T*K]     sorted position of pair t*K+j; -1 for unused slots
+  size_t units;     // int32 [max_units]  slot | split << 16 | splits of that slot << 24
   size_t h;         // act   [(T*K + Ts) * max(F, Fs)]   SwiGLU activations
   size_t o;         // f32   [(T*K + Ts) * D]            per-pair expert outputs
   size_t total;
@@ -156,6 +171,7 @@ inline WsLayout ws_layout(const des_shape_t& s) {
   w.meta = p;     p = align256(p + 4 * 64);
   w.pair_tok = p; p = align256(p + 4 * TK);
   w.pos = p;      p = align256(p + 4 * TK);
+  w.units = p;    p = align256(p + 4 * static_cast<size_t>(max_units(s)));
   w.h = p;        p = align256(p + act * (TK + Ts) * Fm);
   w.o = p;        p = align256(p + 4 * (TK + Ts) * static_cast<size_t>(s.hidden));
   w.total = p;

@@ -49,7 +49,9 @@ struct FfnArgs {
   const int32_t* slot_of;       // [M] slot of a live expert
   int32_t* n_unique;            // set to -1 if a bounded wait expires
   int n_waves;                  // wavefronts of the single-launch grid
-  int splits;                   // workgroups an expert's pairs are spread over (LDS kernels)
+  int splits;                   // units the shared expert's rows are spread over (LDS kernels)
+  const int32_t* units;         // live units of the routed experts, longest expert first:
+                                // slot | split << 16 | splits of that slot << 24; meta[2] of them
 };
 
 constexpr int kFfnMaxWaitIters = 1 << 22;
@@ -867,28 +869,35 @@ __host__ __device__ constexpr int lds_elems(int kd) { return (kd > 0 ? 3 : 2) * 
 
 // Which expert, which of its row groups and which pairs a workgroup works on,
 // shared by the two kernels.  The grid is one-dimensional and read in hand-out
-// order: the shared expert first (every token: the longest workgroups), then the
-// slots, which the permutation orders by falling pair count, each with its
-// `splits` token splits next to each other (they read the same weights) - when
-// the workgroups do not all fit on the chip at once, the long ones start first.
+// order: the shared expert first (every token: the longest workgroups), then
+// the live units of the routed experts as the permutation lists them - longest
+// expert first, an expert's units next to each other (they read the same
+// weights).  So when the workgroups do not all fit on the chip at once the long
+// ones start first, consecutive workgroups (which the hardware deals out to the
+// XCDs in turn) carry similar work, and the grid's tail beyond the live units
+// exits on one scalar load.  `split` of `nsplit`: this workgroup takes every
+// nsplit-th group of rows of the expert, starting with group `split`.
 template <bool DOWN>
-__device__ __forceinline__ bool lds_task(const FfnArgs& a, int per_expert, int per_shared, int splits,
-                                         int& group, int& split, Task& t, FfnArgs& v, int lane) {
+__device__ __forceinline__ bool lds_task(const FfnArgs& a, int per_expert, int per_shared, int& group,
+                                         int& split, int& nsplit, Task& t, FfnArgs& v, int lane) {
   int bx = blockIdx.x;
   v = a;
-  if (bx < per_shared * splits) {
+  if (bx < per_shared * a.splits) {
     make_task(a, 0, true, DOWN, t, lane);
     v = shared_view(a, t, 2);
     split = bx / per_shared;
+    nsplit = a.splits;
     group = bx % per_shared;
     return true;
   }
-  bx -= per_shared * splits;
-  const int slot = bx / (per_expert * splits), r = bx % (per_expert * splits);
-  if (slot >= a.n_slots) return false;
-  split = r / per_expert;
-  group = r % per_expert;
-  return make_task(a, slot, false, DOWN, t, lane);
+  bx -= per_shared * a.splits;
+  const int u = bx / per_expert;
+  if (u >= a.meta[2]) return false;
+  const int rec = a.units[u];
+  split = (rec >> 16) & 0xff;
+  nsplit = rec >> 24;
+  group = bx % per_expert;
+  return make_task(a, rec & 0xffff, false, DOWN, t, lane);
 }
 
 // MAXNT = token tiles per workgroup pass (the LDS buffer holds 16*MAXNT rows);
@@ -904,12 +913,11 @@ __global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void g
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   Task t;
   FfnArgs v;
-  int group, split;
+  int group, split, splits;
   const int per_r = (a.F / 16 + LW - 1) / LW;
   const int per_s = (a.Fs / 16 + LW - 1) / LW;
-  const int splits = a.splits;
   DES_FSTAMP(blockIdx.x, 0);
-  if (!lds_task<false>(a, per_r, per_s, splits, group, split, t, v, lane)) return;  // uniform per workgroup
+  if (!lds_task<false>(a, per_r, per_s, group, split, splits, t, v, lane)) return;  // uniform per workgroup
   const int tile = group * LW + wave;
   const bool active = tile < t.fdim / 16;
   const uint16_t* w0 = uniform_ptr(t.w0);
@@ -956,8 +964,12 @@ __global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void g
   }
 #ifdef DES_FFN_STAMPS
   DES_FSTAMP(blockIdx.x, 2);
-  if (threadIdx.x == 0 && blockIdx.x < 8192)  // pairs this workgroup worked on
+  if (threadIdx.x == 0 && blockIdx.x < 8192) {  // pairs this workgroup worked on, where it ran
     g_ffn_stamps[blockIdx.x * 4 + 3] = max(0, min(static_cast<int>(t.count) - split * kRows, kRows));
+    g_ffn_stamps[blockIdx.x * 4 + 1] =
+        (static_cast<long long>(__builtin_amdgcn_s_getreg(20 | (31 << 11))) << 32) |
+        static_cast<unsigned>(__builtin_amdgcn_s_getreg(4 | (31 << 11)));
+  }
 #endif
 }
 
@@ -969,11 +981,10 @@ __global__ __launch_bounds__(LW* kWave, ((KD > 0 || MAXNT <= 4) ? 2 : 1)) void d
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   Task t;
   FfnArgs v;
-  int group, split;
+  int group, split, splits;
   const int dtiles = a.D / 16;                       // even: D is a multiple of 32
   const int per = (dtiles / 2 + LW - 1) / LW;        // a wavefront owns two row tiles
-  const int splits = a.splits;
-  if (!lds_task<true>(a, per, a.Fs > 0 ? per : 0, splits, group, split, t, v, lane)) return;
+  if (!lds_task<true>(a, per, a.Fs > 0 ? per : 0, group, split, splits, t, v, lane)) return;
   const int dt0 = (group * LW + wave) * 2;
   const bool active = dt0 < dtiles;
   const int F = t.fdim;
@@ -1334,6 +1345,7 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
   a.meta = reinterpret_cast<const int32_t*>(ws + w.meta);
   a.pair_tok = reinterpret_cast<const int32_t*>(ws + w.pair_tok);
   a.slot_tok = reinterpret_cast<const uint16_t*>(ws + w.slot_tok);
+  a.units = reinterpret_cast<const int32_t*>(ws + w.units);
   a.pos = reinterpret_cast<const int32_t*>(ws + w.pos);
   a.h = ws + w.h;
   a.o = reinterpret_cast<float*>(ws + w.o);
@@ -1411,21 +1423,22 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     if (a.T > 32 && chunked && !fused_requested) {
       // Larger blocks: activations staged through LDS.  Token rows per workgroup
       // pass: 64 while no expert can have more, else 128; an expert with more
-      // pairs is spread over up to 8 workgroups (splits).  Wavefronts per workgroup:
+      // pairs is spread over up to kMaxSplits workgroups (the unit list).  Wavefronts per workgroup:
       // two give the finest spread of the weight bytes over the compute units;
       // four share the staged activations among more weight rows, which
       // measured better once experts have many tokens (48-layer stack: 7.7 ms
       // against 8.0 ms; down projection at T = 128: 23 us against 27 us).
-      const bool small = a.T <= 64;
-      const int rows_pass = small ? 64 : 128;
-      int splits = (a.T + rows_pass - 1) / rows_pass;
-      if (splits > 8) splits = 8;
+      const int rows_pass = lds_rows_pass(a.T);
+      const bool small = rows_pass == 64;
+      int splits = (a.T + rows_pass - 1) / rows_pass;  // of the shared expert (all T rows)
+      if (splits > kMaxSplits) splits = kMaxSplits;
+      const int n_units = max_units(s);
       const int gu_lw = a.T <= 128 ? 2 : 4;
       const int dn_lw = a.T <= 64 ? 2 : 4;
-      const int gu_lds = a.n_slots * ((a.F / 16 + gu_lw - 1) / gu_lw) + (a.Fs / 16 + gu_lw - 1) / gu_lw;
+      const int gu_lds = n_units * ((a.F / 16 + gu_lw - 1) / gu_lw) + splits * ((a.Fs / 16 + gu_lw - 1) / gu_lw);
       const int per_dn = (a.D / 32 + dn_lw - 1) / dn_lw;
-      const int dn_lds = a.n_slots * per_dn + (a.Fs > 0 ? per_dn : 0);
-      const dim3 gg(gu_lds * splits), dg(dn_lds * splits);
+      const int dn_lds = n_units * per_dn + (a.Fs > 0 ? splits * per_dn : 0);
+      const dim3 gg(gu_lds), dg(dn_lds);
       a.splits = splits;
       // unrolled reduction lengths (the shared expert shares the down launch)
       const int gu_kd = a.D == 2048 ? 2048 : 0;

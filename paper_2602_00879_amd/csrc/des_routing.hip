@@ -59,7 +59,9 @@ struct RoutingArgs {
   int32_t* n_unique;      // [1]
   int32_t* offsets;       // [M+1]
   int4* slots;            // [n_slots] {expert, first sorted pair, pairs, 0}; expert -1 = unused
-  int32_t* meta;          // [8]: [0] live experts, [1] routed pairs
+  int32_t* meta;          // [8]: [0] live experts, [1] routed pairs, [2] live units
+  int32_t* units;         // [max units] slot | split << 16 | splits of the slot << 24
+  int rows_shift;         // log2 of the token rows per unit (blocks of more than 32 tokens)
   int32_t* pair_tok;      // [T*K] token of each sorted pair
   int32_t* pos;           // [T*K] sorted position of pair (t*K+j), -1 = unused slot
   unsigned long long* flags;  // [n_tiles + 2*B*groups] epoch flags: router tiles, selector
@@ -748,6 +750,7 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
   int* s_off = s_cnt + M;                                          // [M+1]
   int* s_liv = s_off + M + 1;                                      // [M+1]
   int* s_slot = s_liv + M + 1;                                     // [M] slot of a live expert
+  int* s_uoff = s_slot + M;                                        // [M] its first unit
   const int tid = threadIdx.x;
   const int TK = T * K;
 
@@ -766,6 +769,7 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
     for (int w = 0; w < words; ++w) c += __popc(member[static_cast<size_t>(e) * words + w]);
     s_cnt[e] = c;
     s_slot[e] = 0;
+    s_uoff[e] = 0;
     a.expert_counts[e] = c;
   }
   __syncthreads();
@@ -775,20 +779,29 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
   // their workgroups in slot order and, when not all of them fit on the chip at
   // once, the long ones must not be the ones that start last.  Rank by counting,
   // the comparison range split over the threads that share an expert; the
-  // partial ranks meet in an integer LDS add.
+  // partial ranks meet in an integer LDS add.  The same pass counts the units
+  // (groups of 2^rows_shift pairs, at most kMaxSplits per expert) of the experts
+  // ahead: the expert's place in the unit list.
   const bool by_count = T > 32;
+  const int rsh = a.rows_shift;
+  auto units_of = [&](int c) { return min((c + (1 << rsh) - 1) >> rsh, kMaxSplits); };
   if (by_count) {
     const int P = max(1, kRtThreads / M), CH = (M + P - 1) / P;
     for (int t = tid; t < M * P; t += kRtThreads) {
       const int e = t % M, j0 = (t / M) * CH, j1 = min(j0 + CH, M);
       const int ce = s_cnt[e];
       if (ce == 0) continue;
-      int r = 0;
+      int r = 0, uo = 0;
       for (int j = j0; j < j1; ++j) {
         const int cj = s_cnt[j];
-        r += (cj > ce || (cj == ce && j < e)) ? 1 : 0;
+        const bool ahead = cj > ce || (cj == ce && j < e);
+        r += ahead ? 1 : 0;
+        uo += ahead ? units_of(cj) : 0;
       }
-      if (r) atomicAdd(&s_slot[e], r);
+      if (r) {
+        atomicAdd(&s_slot[e], r);
+        atomicAdd(&s_uoff[e], uo);
+      }
     }
   }
   if (tid < 64) {  // exclusive scans of counts and of (count > 0), 64 experts at a time
@@ -816,6 +829,7 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
       s_liv[M] = base_l;
       a.meta[0] = base_l;
       a.meta[1] = base_c;
+      a.meta[2] = 0;  // live units: set after the barrier by the last slot's expert, if any
       a.n_unique[0] = base_l;
     }
   }
@@ -827,6 +841,11 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
     const bool live = s_cnt[e] > 0 && sl < a.n_slots;
     if (live) a.slots[sl] = make_int4(e, s_off[e], s_cnt[e], 0);
     a.slot_of[e] = live ? sl : -1;
+    if (live && by_count) {
+      const int nu = units_of(s_cnt[e]);
+      for (int k = 0; k < nu; ++k) a.units[s_uoff[e] + k] = sl | (k << 16) | (nu << 24);
+      if (sl == n_live - 1) a.meta[2] = s_uoff[e] + nu;  // the last slot closes the list
+    }
   }
   for (int i = tid; i < a.n_ffn_flags; i += kRtThreads) a.ffn_flags[i] = 0ull;
   for (int s = n_live + tid; s < a.n_slots; s += kRtThreads) a.slots[s] = make_int4(-1, 0, 0, 0);
@@ -854,8 +873,8 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
 // ---------------------------------------------------------------- the kernel
 // LDS of the routing kernel: the selection's carve-up, but at least what the
 // router tile (16 KB) and the permutation (bitmap of at most 8192 words plus
-// 4M+2 counters, under 42 KB for every shape the library accepts) need.
-constexpr int kMinRoutingLds = 42 * 1024;
+// 5M+2 counters, under 44 KB for every shape the library accepts) need.
+constexpr int kMinRoutingLds = 44 * 1024;
 
 template <int LPT, bool EXT>
 __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
@@ -1047,6 +1066,8 @@ int launch_routing(const des_shape_t& s, const void* x, const void* w_router, co
   a.ffn_flags = reinterpret_cast<unsigned long long*>(ws + w.ffn_flags);
   a.n_ffn_flags = static_cast<int>(ffn_h_flags(s) + ffn_o_flags(s));
   a.slot_of = reinterpret_cast<int32_t*>(ws + w.slot_of);
+  a.units = reinterpret_cast<int32_t*>(ws + w.units);
+  a.rows_shift = lds_rows_pass(s.n_seqs * s.n_tokens) == 64 ? 6 : 7;
   a.slot_tok = reinterpret_cast<uint16_t*>(ws + w.slot_tok);
   a.sel_part = reinterpret_cast<uint32_t*>(ws + w.sel_part);
   const int n_tiles = a.tiles_m * a.tiles_t;
