@@ -649,6 +649,14 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
 
   DES_STAMP(a, 4);
   // ------------------------------ stage 2: constrained local routing + gates
+  // With several selector workgroups the permutation runs in a workgroup of its own
+  // and reads S_n from memory: the indices then travel with device-scope stores
+  // and loads, like the logits, so the hand-off needs no fence.
+  const bool idx_dev = a.use_flags && a.B * a.groups > 1;
+  auto put_idx = [&](int32_t* p, int v) {
+    if (idx_dev) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+  };
   const int keff = min(a.k_route, s_hist[34]);  // experts per token: Alg. 1 stage 2 with k <= K
   const bool reuse_sort = single_pass && a.mode != DES_VANILLA;  // stage 1 sorted this token
 
@@ -683,7 +691,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
       for (int q = 0; q < NW; ++q)
         if (it == q * LPT + rl) mkey[q] = m;
       if (mine) {
-        if (live) a.topk_idx[o + it] = rl * kEpl + static_cast<int>((sidx >> (3 * hd.h)) & 7u);
+        if (live) put_idx(a.topk_idx + o + it, rl * kEpl + static_cast<int>((sidx >> (3 * hd.h)) & 7u));
         head_set(hd, hd.mask & (hd.mask - 1u), my_sorted);
       }
     }
@@ -729,7 +737,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
         const int it = q * LPT + rl;
         if (it < K) {
           a.topk_w[o + it] = it < keep ? mye[q] / den : 0.f;
-          if (it >= keep) a.topk_idx[o + it] = -1;
+          if (it >= keep) put_idx(a.topk_idx + o + it, -1);
         }
       }
     }
@@ -742,7 +750,9 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
 // by (token, slot) are ordered by token alone, so a per-expert bitmap over the
 // tokens gives every pair's sorted position with popcounts: no sort, no float,
 // integer LDS atomics only (their result does not depend on arrival order).
-__device__ void permute_all(const RoutingArgs& a, char* smem) {
+// idx_dev: S_n was written by other workgroups of this launch with device-scope
+// stores (read it the same way).
+__device__ void permute_all(const RoutingArgs& a, char* smem, bool idx_dev) {
   const int T = a.B * a.N, K = a.K, M = a.M;
   const int words = (T + 31) / 32;
   uint32_t* member = reinterpret_cast<uint32_t*>(smem);           // [M][words]
@@ -754,15 +764,26 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
   const int tid = threadIdx.x;
   const int TK = T * K;
 
+  auto get_idx = [&](int p) {
+    return idx_dev ? __hip_atomic_load(a.topk_idx + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                   : a.topk_idx[p];
+  };
+  constexpr int kKeep = 2;  // a thread's first pairs stay in registers for the second pass
+  int kept[kKeep];
   for (int i = tid; i < M * words; i += kRtThreads) member[i] = 0u;
+#pragma unroll
+  for (int i = 0; i < kKeep; ++i) kept[i] = tid + i * kRtThreads < TK ? get_idx(tid + i * kRtThreads) : -1;
   __syncthreads();
-  for (int p = tid; p < TK; p += kRtThreads) {
-    const int e = a.topk_idx[p];
+  auto mark = [&](int p, int e) {
     if (e >= 0) {
       const int t = p / K;
       atomicOr(&member[static_cast<size_t>(e) * words + (t >> 5)], 1u << (t & 31));
     }
-  }
+  };
+#pragma unroll
+  for (int i = 0; i < kKeep; ++i)
+    if (tid + i * kRtThreads < TK) mark(tid + i * kRtThreads, kept[i]);
+  for (int p = tid + kKeep * kRtThreads; p < TK; p += kRtThreads) mark(p, get_idx(p));
   __syncthreads();
   for (int e = tid; e < M; e += kRtThreads) {
     int c = 0;
@@ -853,9 +874,8 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
   // valid token: clear the table, then (after the barrier) fill it
   for (int i = tid; i < a.n_slots * kSlotToks; i += kRtThreads) a.slot_tok[i] = 0;
   __syncthreads();
-  for (int p = tid; p < TK; p += kRtThreads) {
-    const int e = a.topk_idx[p];
-    if (e < 0) { a.pos[p] = -1; continue; }
+  auto place = [&](int p, int e) {
+    if (e < 0) { a.pos[p] = -1; return; }
     const int t = p / K;
     const uint32_t* mrow = member + static_cast<size_t>(e) * words;
     int r = s_off[e];
@@ -867,7 +887,11 @@ __device__ void permute_all(const RoutingArgs& a, char* smem) {
     const int sl = by_count ? s_slot[e] : s_liv[e];
     if (within < kSlotToks && sl < a.n_slots)
       a.slot_tok[sl * kSlotToks + within] = static_cast<uint16_t>(t);
-  }
+  };
+#pragma unroll
+  for (int i = 0; i < kKeep; ++i)
+    if (tid + i * kRtThreads < TK) place(tid + i * kRtThreads, kept[i]);
+  for (int p = tid + kKeep * kRtThreads; p < TK; p += kRtThreads) place(p, get_idx(p));
 }
 
 // ---------------------------------------------------------------- the kernel
@@ -912,7 +936,7 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
       // stores before the loads below, no device-scope fence needed
       __syncthreads();
       DES_STAMP(a, 6);
-      permute_all(a, smem);
+      permute_all(a, smem, false);
       DES_STAMP(a, 7);
       // every flag of this call has been consumed: clear them, so that a replay
       // of a captured launch (same epoch) cannot be satisfied by stale flags
@@ -921,19 +945,20 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
       return;
     }
     if (a.use_flags) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's index stores have been acknowledged
       __syncthreads();
-      if (threadIdx.x == 0) flag_publish(a.flags + all_tiles + n_sel + blk, a.epoch, true);
+      if (threadIdx.x == 0) flag_publish(a.flags + all_tiles + n_sel + blk, a.epoch, false);
     }
     return;
   }
   blk -= n_sel;
   if (blk == 0 && a.do_permute && a.B * a.groups > 1) {  // ---- role P
     if (a.use_flags && a.do_select &&
-        !flags_wait(a.flags + all_tiles + a.B * a.groups, a.B * a.groups, a.epoch, true)) {
+        !flags_wait(a.flags + all_tiles + a.B * a.groups, a.B * a.groups, a.epoch, false)) {
       if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
       return;
     }
-    permute_all(a, smem);
+    permute_all(a, smem, a.use_flags && a.do_select);
     if (a.use_flags)  // all selectors have consumed the other flags and published theirs
       for (int i = threadIdx.x; i < n_flags; i += kRtThreads) a.flags[i] = 0ull;
   }
