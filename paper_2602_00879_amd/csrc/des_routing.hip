@@ -605,11 +605,18 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
         const uint32_t ke = s_key[e];
         if (ke == 0u) continue;
         const int j0 = part * CH;
+        // key j beats key e if it is larger, or equal with j < e: kj >= ke for j < e,
+        // kj >= ke + 1 for j >= e (a candidate's key is never the largest integer).
+        // A chunk that lies wholly on one side of e needs one threshold.
+        const int d = e - j0;
         int rank = 0;
+        if (d <= 0 || d >= CH) {
+          const uint32_t thr = ke + (d <= 0 ? 1u : 0u);
 #pragma unroll
-        for (int jj = 0; jj < CH; ++jj) {
-          const uint32_t kj = s_key[j0 + jj];
-          rank += (kj > ke || (kj == ke && j0 + jj < e)) ? 1 : 0;
+          for (int jj = 0; jj < CH; ++jj) rank += s_key[j0 + jj] >= thr ? 1 : 0;
+        } else {
+#pragma unroll
+          for (int jj = 0; jj < CH; ++jj) rank += s_key[j0 + jj] >= ke + (jj >= d ? 1u : 0u) ? 1 : 0;
         }
         if (rank) atomicAdd(&s_rank[e], rank);
       }
