@@ -158,6 +158,9 @@ MID = dict(
     # launches, an expert can have hundreds of pairs), and 512 experts with K = 32
     max_tokens=W.LayerConfig("max_tokens", "bf16", 64, 64, 64, 64, 32, 0, 4, 8, 0.5, 22),
     max_experts=W.LayerConfig("max_experts", "bf16", 1, 8, 64, 512, 32, 32, 32, 40, 0.5, 23),
+    # 4096 tokens on 8 experts: an expert has far more than 8 x 128 pairs, so each of its
+    # eight token units takes several passes (and the shared expert all 4096 rows)
+    max_rows=W.LayerConfig("max_rows", "bf16", 64, 64, 128, 8, 128, 128, 2, 3, 0.8, 24),
 )
 
 
