@@ -1116,15 +1116,30 @@ __global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
   if (d >= a.D) return;
   const int K = a.K;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int j = 0; j < K; ++j) {
-    const int r = a.pos[t * K + j];
-    if (r < 0) continue;
-    const float w = a.topk_w[t * K + j];
-    const float4 v = *reinterpret_cast<const float4*>(a.o + static_cast<size_t>(r) * a.D + d);
-    acc.x = fmaf(w, v.x, acc.x);
-    acc.y = fmaf(w, v.y, acc.y);
-    acc.z = fmaf(w, v.z, acc.z);
-    acc.w = fmaf(w, v.w, acc.w);
+  // eight slots at a time: their position, gate and output-row loads are all in
+  // flight together; the sum still runs in slot order
+  for (int j0 = 0; j0 < K; j0 += 8) {
+    int r[8];
+    float w[8];
+    float4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const bool in = j0 + u < K;
+      r[u] = in ? a.pos[t * K + j0 + u] : -1;
+      w[u] = in ? a.topk_w[t * K + j0 + u] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      v[u] = r[u] >= 0 ? *reinterpret_cast<const float4*>(a.o + static_cast<size_t>(r[u]) * a.D + d)
+                       : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (r[u] < 0) continue;
+      acc.x = fmaf(w[u], v[u].x, acc.x);
+      acc.y = fmaf(w[u], v[u].y, acc.y);
+      acc.z = fmaf(w[u], v[u].z, acc.z);
+      acc.w = fmaf(w[u], v[u].w, acc.w);
+    }
   }
   if (a.Fs > 0) {
     const size_t r = static_cast<size_t>(a.T) * K + t;
