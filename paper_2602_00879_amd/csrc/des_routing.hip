@@ -134,6 +134,10 @@ __device__ __forceinline__ void router_tile_bf16(const RoutingArgs& a, int tile_
   const uint16_t* bp = static_cast<const uint16_t*>(a.x) + static_cast<size_t>(ti) * D + kq;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   const int nks = D / 32;
+  // the bias of the expert this thread will finish (below), fetched now so that its
+  // latency is not added after the reduction
+  const int er_fin = threadIdx.x & 15;
+  const float bias_fin = (threadIdx.x < 256 && a.bias && i0 + er_fin < M) ? a.bias[i0 + er_fin] : 0.f;
   // four k-steps per trip, all eight loads in flight before the first MFMA
   for (int ks = wave; ks < nks; ks += 4 * kRtWaves) {
     bf16x8 av[4], bv[4];
@@ -152,9 +156,9 @@ __device__ __forceinline__ void router_tile_bf16(const RoutingArgs& a, int tile_
   for (int q = 0; q < 4; ++q) part[wave * 256 + (4 * (lane >> 4) + q) * 16 + r] = acc[q];
   __syncthreads();
   if (threadIdx.x < 256) {
-    const int er = threadIdx.x & 15, tc = threadIdx.x >> 4;
+    const int er = er_fin, tc = threadIdx.x >> 4;
     float s = 0.f;
-    const float bias_e = (a.bias && i0 + er < M) ? a.bias[i0 + er] : 0.f;
+    const float bias_e = bias_fin;
 #pragma unroll
     for (int w = 0; w < kRtWaves; ++w) s += part[w * 256 + er * 16 + tc];  // fixed order
     const int e = i0 + er, t = t0 + tc;
