@@ -763,15 +763,18 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
 // integer LDS atomics only (their result does not depend on arrival order).
 // idx_dev: S_n was written by other workgroups of this launch with device-scope
 // stores (read it the same way).
+// MP = the kernel's padded expert count (M <= MP): the counters are kept for MP
+// experts (zero past M) so that the ranking below has compile-time trip counts.
+template <int MP>
 __device__ void permute_all(const RoutingArgs& a, char* smem, bool idx_dev) {
   const int T = a.B * a.N, K = a.K, M = a.M;
   const int words = (T + 31) / 32;
   uint32_t* member = reinterpret_cast<uint32_t*>(smem);           // [M][words]
-  int* s_cnt = reinterpret_cast<int*>(member + static_cast<size_t>(M) * words);  // [M]
-  int* s_off = s_cnt + M;                                          // [M+1]
+  int* s_cnt = reinterpret_cast<int*>(member + static_cast<size_t>(M) * words);  // [MP]
+  int* s_off = s_cnt + MP;                                         // [M+1]
   int* s_liv = s_off + M + 1;                                      // [M+1]
-  int* s_slot = s_liv + M + 1;                                     // [M] slot of a live expert
-  int* s_uoff = s_slot + M;                                        // [M] its first unit
+  int* s_slot = s_liv + M + 1;                                     // [MP] slot of a live expert
+  int* s_uoff = s_slot + MP;                                       // [MP] its first unit
   const int tid = threadIdx.x;
   const int TK = T * K;
 
@@ -796,13 +799,14 @@ __device__ void permute_all(const RoutingArgs& a, char* smem, bool idx_dev) {
     if (tid + i * kRtThreads < TK) mark(tid + i * kRtThreads, kept[i]);
   for (int p = tid + kKeep * kRtThreads; p < TK; p += kRtThreads) mark(p, get_idx(p));
   __syncthreads();
-  for (int e = tid; e < M; e += kRtThreads) {
+  for (int e = tid; e < MP; e += kRtThreads) {
     int c = 0;
-    for (int w = 0; w < words; ++w) c += __popc(member[static_cast<size_t>(e) * words + w]);
+    if (e < M)
+      for (int w = 0; w < words; ++w) c += __popc(member[static_cast<size_t>(e) * words + w]);
     s_cnt[e] = c;
     s_slot[e] = 0;
     s_uoff[e] = 0;
-    a.expert_counts[e] = c;
+    if (e < M) a.expert_counts[e] = c;
   }
   __syncthreads();
   // Slot order.  Up to 32 tokens every FFN task is on the chip at once and the
@@ -818,15 +822,15 @@ __device__ void permute_all(const RoutingArgs& a, char* smem, bool idx_dev) {
   const int rsh = a.rows_shift;
   auto units_of = [&](int c) { return min((c + (1 << rsh) - 1) >> rsh, kMaxSplits); };
   if (by_count) {
-    const int P = max(1, kRtThreads / M), CH = (M + P - 1) / P;
-    for (int t = tid; t < M * P; t += kRtThreads) {
-      const int e = t % M, j0 = (t / M) * CH, j1 = min(j0 + CH, M);
-      const int ce = s_cnt[e];
-      if (ce == 0) continue;
+    constexpr int P = kRtThreads / MP, CH = MP / P;  // MP * P threads: each one expert, CH rivals
+    const int e = tid % MP, j0 = (tid / MP) * CH;
+    const int ce = s_cnt[e];
+    if (ce > 0) {
       int r = 0, uo = 0;
-      for (int j = j0; j < j1; ++j) {
-        const int cj = s_cnt[j];
-        const bool ahead = cj > ce || (cj == ce && j < e);
+#pragma unroll
+      for (int jj = 0; jj < CH; ++jj) {  // counts past M are zero: never ahead of a live expert
+        const int cj = s_cnt[j0 + jj];
+        const bool ahead = cj > ce || (cj == ce && j0 + jj < e);
         r += ahead ? 1 : 0;
         uo += ahead ? units_of(cj) : 0;
       }
@@ -908,7 +912,7 @@ __device__ void permute_all(const RoutingArgs& a, char* smem, bool idx_dev) {
 // ---------------------------------------------------------------- the kernel
 // LDS of the routing kernel: the selection's carve-up, but at least what the
 // router tile (16 KB) and the permutation (bitmap of at most 8192 words plus
-// 5M+2 counters, under 44 KB for every shape the library accepts) need.
+// at most 5 * 512 + 2 counters, under 44 KB for every shape the library accepts) need.
 constexpr int kMinRoutingLds = 44 * 1024;
 
 template <int LPT, bool EXT>
@@ -947,7 +951,7 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
       // stores before the loads below, no device-scope fence needed
       __syncthreads();
       DES_STAMP(a, 6);
-      permute_all(a, smem, false);
+      permute_all<SelLds<LPT>::MP>(a, smem, false);
       DES_STAMP(a, 7);
       // every flag of this call has been consumed: clear them, so that a replay
       // of a captured launch (same epoch) cannot be satisfied by stale flags
@@ -969,7 +973,7 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
       if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
       return;
     }
-    permute_all(a, smem, a.use_flags && a.do_select);
+    permute_all<SelLds<LPT>::MP>(a, smem, a.use_flags && a.do_select);
     if (a.use_flags)  // all selectors have consumed the other flags and published theirs
       for (int i = threadIdx.x; i < n_flags; i += kRtThreads) a.flags[i] = 0ull;
   }
