@@ -402,7 +402,9 @@ def bench_variants(args, torch, B, W, dev):
     """Routing variants that reuse the same FFN kernels, on the 128-expert layer
     (N = 32): the top-k baseline (fewer experts per token, Table 1 of the paper),
     cumulative-probability skipping (Sec. 5.1, Baselines), and DES-Vote with
-    k = 8 against k = 4 experts per token inside the same coreset (Sec. 5.3).
+    k = 8 against k = 4 experts per token inside the same coreset (Sec. 5.3),
+    and a sigmoid router limited to 4 of 8 expert groups (another routing function
+    sigma of Sec. 4.1) under vanilla, DES-Vote and DES-Seq.
     Latency and expert counts only: accuracy needs trained weights."""
     cfg = W.CONFIGS["m128_zipf"]
     layer = W.make_layer(cfg)
@@ -418,17 +420,23 @@ def bench_variants(args, torch, B, W, dev):
     replicas = [base] + [[t.clone() for t in base] for _ in range(max(1, args.replicas) - 1)]
     steps, warm = min(args.steps, 200), min(args.warmup, 20)
     rows = []
-    for name, mode, k_route, beta in (("vanilla K=8", "vanilla", 0, 0.0),
-                                      ("top-k baseline k=4", "vanilla", 4, 0.0),
-                                      ("vanilla + skipping beta=0.1", "vanilla", 0, 0.1),
-                                      ("vanilla + skipping beta=0.2", "vanilla", 0, 0.2),
-                                      ("vanilla + skipping beta=0.3", "vanilla", 0, 0.3),
-                                      ("DES-Vote C=32 k=8", "vote", 0, 0.0),
-                                      ("DES-Vote C=32 k=4 (same coreset)", "vote", 4, 0.0),
-                                      ("DES-Vote C=32 + skipping beta=0.2", "vote", 0, 0.2)):
+    plain = dict(router_act="softmax", n_group=0, topk_group=0, group_score="max")
+    grouped = dict(router_act="sigmoid", n_group=8, topk_group=4, group_score="top2sum")
+    for name, mode, k_route, beta, router in (
+            ("vanilla K=8", "vanilla", 0, 0.0, plain),
+            ("top-k baseline k=4", "vanilla", 4, 0.0, plain),
+            ("vanilla + skipping beta=0.1", "vanilla", 0, 0.1, plain),
+            ("vanilla + skipping beta=0.2", "vanilla", 0, 0.2, plain),
+            ("vanilla + skipping beta=0.3", "vanilla", 0, 0.3, plain),
+            ("DES-Vote C=32 k=8", "vote", 0, 0.0, plain),
+            ("DES-Vote C=32 k=4 (same coreset)", "vote", 4, 0.0, plain),
+            ("DES-Vote C=32 + skipping beta=0.2", "vote", 0, 0.2, plain),
+            ("sigmoid router, 8 groups keep 4: vanilla K=8", "vanilla", 0, 0.0, grouped),
+            ("sigmoid router, 8 groups keep 4: DES-Vote C=32", "vote", 0, 0.0, grouped),
+            ("sigmoid router, 8 groups keep 4: DES-Seq C=32", "seq", 0, 0.0, grouped)):
         shape = B.make_shape(1, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k, cfg.coreset,
                              mode, cfg.dtype, weight_layout=B.DES_LAYOUT_PACKED, k_route=k_route,
-                             skip_beta=beta)
+                             skip_beta=beta, **router)
         bufs = B.MoeBuffers(shape, dev, x.dtype)
 
         def step(i):
