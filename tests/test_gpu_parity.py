@@ -422,12 +422,15 @@ def test_m128_block_size_sweep():
     assert uniq[(128, "vanilla")] > uniq[(32, "vanilla")] > uniq[(4, "vanilla")]
 
 
-def test_graph_replay_matches_eager():
+@pytest.mark.parametrize("name", ["mid_bf16", "sel_groups"])
+def test_graph_replay_matches_eager(name):
     """A captured des_moe_forward (kernels only, no memset nodes) replayed several
     times with new inputs, eager calls and synchronisations in between, must equal
     the eager result every time (the routing flags are cleared by their consumer,
-    so a replay with the captured epoch cannot be satisfied by stale flags)."""
-    cfg = MID["mid_bf16"]
+    so a replay with the captured epoch cannot be satisfied by stale flags).
+    mid_bf16: two selector workgroups and a permutation workgroup; sel_groups: six
+    selectors that also exchange their election partials."""
+    cfg = MID[name]
     layer = W.make_layer(cfg)
     dev = H.layer_to_device(layer)
     shape = H.shape_of(cfg, "vote")
