@@ -20,7 +20,14 @@
  *   - Router logits must be finite; behaviour is unspecified otherwise.
  *   - Every TopK breaks ties towards the lowest expert index and compares
  *     values as numbers (+0 equals -0).
- *   - Results are run-to-run bit-identical: no floating-point atomics are used.
+ *   - Results are run-to-run bit-identical: no floating-point atomics are used,
+ *     unless the caller asks for them with vote_atomic = 1 (see des_shape_t).
+ *   - Expert weights are streamed from HBM straight into matrix-core operand
+ *     registers, not staged through LDS: a weight element is used by exactly
+ *     one matrix instruction of one wavefront, so a stop in LDS would add a hop
+ *     and no reuse (measured slower).  LDS holds what IS shared: the router's
+ *     partial tiles, the selection state, the token rows of long blocks and the
+ *     partial sums that the wavefronts of a workgroup exchange.
  *
  * Tensor layouts ("rows contiguous along the reduction dimension"):
  *   x          [B][N][D]       hidden states, dtype
@@ -55,7 +62,7 @@ typedef enum { DES_F32 = 0, DES_BF16 = 1 } des_dtype_t;
 
 typedef enum { DES_LAYOUT_ROWMAJOR = 0, DES_LAYOUT_PACKED = 1 } des_layout_t;
 
-/* The routing function sigma "from the model architecture" (Sec. 4.1): router weight of
+/* The routing function sigma, which Sec. 4.1 leaves to the model: router weight of
  * expert i for a token = softmax over the M logits, or sigmoid of its own logit.  Either
  * way a token's gates are its selected weights divided by their sum (Eq. 1), and every
  * ranking compares logits (both functions are monotone). */
@@ -112,8 +119,8 @@ typedef struct {
                          /* and turned into gates (Alg. 1 stage 2)                 */
   int32_t vote_renorm;   /* 1: a token's K votes are divided by their sum, so each */
                          /* token casts a total weight of one (the other reading   */
-                         /* of "aggregate the router weights", Sec. 4.2); 0: as    */
-                         /* Alg. 3 is written (mask, then sum)                     */
+                         /* of how Sec. 4.2 adds up the votes); 0: as Alg. 3 is    */
+                         /* written (mask, then sum)                               */
   int32_t n_group;       /* > 1: group-limited routing over this many groups;      */
                          /* 0 or 1 = off (topk_group, group_score then ignored)    */
   int32_t topk_group;    /* groups a token keeps, 1..n_group                       */
@@ -191,10 +198,18 @@ int des_select_coreset(const des_shape_t* shape, const float* logits, int32_t* c
  * topk_idx [B][N][K] int32 in rank order, unused slots -1; topk_w [B][N][K]
  * fp32, unused slots 0; expert_counts [M] int32 = pairs routed to each expert
  * summed over sequences (cnt_i of Eq. 2); n_unique [1] int32 = experts with a
- * non-zero count (|union S_n|), or -1 if an internal bounded wait between the
- * routing stages expired (a fault of the device or of a concurrent misuse of
- * the workspace; the other outputs are then undefined); coreset_idx /
- * coreset_size as above.
+ * non-zero count (|union S_n|); coreset_idx / coreset_size as above.
+ * n_unique = -1 reports that a bounded wait between the stages of a launch ran
+ * out.  The routing stages hand their results to each other inside one launch
+ * and wait for each other there; that is only safe while every workgroup of
+ * the launch is on the chip at once (checked against the device's compute-unit
+ * count), so the call assumes that NO OTHER KERNEL occupies the device while it
+ * runs.  If a wait does run out - another stream's kernel kept a producer off
+ * the chip, or the workspace was shared with an overlapping call - every kernel
+ * still exits normally: a routing stage that gives up leaves an empty work list
+ * (expert_counts all zero; the expert FFN then reads no weights and y holds
+ * only the shared expert's output, plus x under `residual`), an FFN stage that
+ * gives up leaves y undefined but touches nothing outside the caller's buffers.
  * ws_gate / ws_up / ws_down: the shared expert ([Fs][D], [Fs][D], [D][Fs], same
  * dtype and layout rule), required iff ffn_shared > 0.
  * y must not alias x.  workspace: >= des_workspace_bytes(shape), 256-byte
@@ -237,7 +252,19 @@ int des_pack_expert_weights(const void* src, void* dst, int64_t n_mats, int32_t 
                             int32_t cols, void* hip_stream);
 
 /*
- * Measurement aid, not part of the hot path: one launch that reads `bytes`
+ * Coreset size for a budget given as a fraction of the experts, M_core = beta * M
+ * (Sec. 5.1), rounded down as the sizes printed in Table 1 imply (0.15 * 256 -> 38,
+ * 0.6 * 64 -> 38).  Host only.  Returns 0 for beta outside (0, 1] or n_experts < 1;
+ * at least 1 otherwise.
+ */
+int32_t des_coreset_from_beta(double beta, int32_t n_experts);
+
+/* ------------------------------------------------------------------------
+ * Measurement and test aids.  None of them is part of the hot path.
+ * ------------------------------------------------------------------------ */
+
+/*
+ * Measurement aid: one launch that reads `bytes`
  * bytes at `src` from HBM once (each wavefront streams one contiguous 64 KB
  * chunk) and computes nothing.  Its duration is the practical ceiling of a
  * weight scan of that size on this machine, against which the expert FFN of
@@ -265,12 +292,16 @@ const char* des_kernel_timing_name(int kernel_id);
 int des_kernel_timing_read(int kernel_id, double* total_ms, int64_t* launches);
 
 /*
- * Coreset size for a budget given as a fraction of the experts, M_core = beta * M
- * (Sec. 5.1), rounded down as the sizes printed in Table 1 imply (0.15 * 256 -> 38,
- * 0.6 * 64 -> 38).  Host only.  Returns 0 for beta outside (0, 1] or n_experts < 1;
- * at least 1 otherwise.
+ * Test aid: forces the give-up path of the bounded waits from the host, so that a
+ * test can check it without faulting or hanging anything.  skip_router = 1: the
+ * fused routing launch runs without its router workgroups (nobody produces the
+ * logits the selectors wait for); skip_router = 2: the same for the next such
+ * launch only, after which both hooks reset themselves (one layer of a stack);
+ * max_wait_iters > 0: a wait gives up after that many polls instead of after
+ * seconds.  (0, 0) restores normal operation.
+ * Process-wide, not thread-safe.
  */
-int32_t des_coreset_from_beta(double beta, int32_t n_experts);
+int des_test_hooks(int skip_router, int max_wait_iters);
 
 const char* des_strerror(int code);
 /* Text of the last HIP error seen by this thread's DES_ERR_HIP ("" if none). */

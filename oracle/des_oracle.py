@@ -9,11 +9,11 @@ Everything is numpy in float64 on the exact input values (bf16 / fp32 inputs
 are upcast by the caller; nothing is rounded in here).  Each function follows
 one passage of the paper:
 
-  router_logits        Background, "Efficient Mixture-of-Experts": G: R^D -> R^M
+  router_logits        Background (efficient MoE): the router G maps R^D to R^M
   softmax_rows         Sec. 4.3 (per-token softmax of the selection kernel)
-  router_scores        the "routing function sigma from the model architecture"
-                       (Sec. 4.1): softmax over the experts, or a per-expert sigmoid
-  rank_order           TopK = "the K highest-scoring experts" (below Eq. 1)
+  router_scores        the routing function sigma, which Sec. 4.1 leaves to the model:
+                       softmax over the experts, or a per-expert sigmoid
+  rank_order           TopK of Eq. 1: the K experts with the best scores
   group_limited        group-limited routers (another sigma of Sec. 4.1): the groups of
                        experts a token may choose from
   coreset_seq          Eq. 5 / Alg. 2  (DES-Seq)
@@ -42,10 +42,10 @@ the design notes of the repository):
   * act = "sigmoid": the router weight of an expert is sigmoid(logit); votes add
     these scores and a token's gates are its selected scores divided by their
     sum; rankings still compare logits (the sigmoid is monotone);
-  * renorm = True (the alternative reading of "aggregate the router weights",
-    Sec. 4.2): a token's K votes are divided by their sum, so every token casts
-    a total weight of one;
-  * k_route (Sec. 5.3, "Effect of active expert count"): the coreset is elected
+  * renorm = True (the alternative reading of how Sec. 4.2 adds up the votes):
+    a token's K votes are divided by their sum, so every token casts a total
+    weight of one;
+  * k_route (Sec. 5.3, the study of the active expert count): the coreset is elected
     with the model's K, then each token uses only its k_route < K best coreset
     experts; gates are normalised over those;
   * cumulative_skip: experts i..k (rank order) are dropped when the sum of their
@@ -224,7 +224,7 @@ def coreset_seq_capped(logits: np.ndarray, K: int, C: int,
 
 def vote_vector(logits: np.ndarray, K: int, act: str = "softmax", renorm: bool = False,
                 allowed: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
-    """Alg. 3, lines 1-2: V_i = sum over tokens of the token's router weight
+    """Alg. 3, the masking and the summing step: V_i = sum over tokens of the token's router weight
     for expert i, counted only where i is inside that token's own top-K.
     renorm: each token's K weights are first divided by their sum.
     Returns (V float64 [M], nominated bool [M])."""

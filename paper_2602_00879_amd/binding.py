@@ -25,7 +25,7 @@ EXPORTS = (
     "des_moe_forward", "des_stack_workspace_bytes", "des_moe_stack_forward",
     "des_pack_expert_weights", "des_strerror", "des_last_hip_error",
     "des_kernel_timing_enable", "des_kernel_timing_count", "des_kernel_timing_name",
-    "des_kernel_timing_read", "des_hbm_read_probe", "des_coreset_from_beta",
+    "des_kernel_timing_read", "des_hbm_read_probe", "des_coreset_from_beta", "des_test_hooks",
 )
 
 
@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.des_hbm_read_probe.argtypes = [vp, sz, vp, vp]
         L.des_coreset_from_beta.restype = i32
         L.des_coreset_from_beta.argtypes = [ctypes.c_double, i32]
+        L.des_test_hooks.restype = ctypes.c_int
+        L.des_test_hooks.argtypes = [ctypes.c_int, ctypes.c_int]
         L.des_strerror.restype = ctypes.c_char_p
         L.des_strerror.argtypes = [ctypes.c_int]
         L.des_last_hip_error.restype = ctypes.c_char_p
@@ -260,6 +262,12 @@ def des_hbm_read_probe(src: torch.Tensor, n_bytes: int, sink: torch.Tensor) -> N
 def des_coreset_from_beta(beta: float, n_experts: int) -> int:
     """floor(beta * M): the coreset size for a budget given as a fraction (Table 1)."""
     return int(lib().des_coreset_from_beta(float(beta), int(n_experts)))
+
+
+def des_test_hooks(skip_router, max_wait_iters: int) -> None:
+    """Test aid: forces the give-up path of the bounded waits ((0, 0) = normal;
+    skip_router = 2: for the next fused routing launch only)."""
+    _check(lib().des_test_hooks(int(skip_router), int(max_wait_iters)))
 
 
 def des_kernel_timing_enable(enable: bool) -> None:

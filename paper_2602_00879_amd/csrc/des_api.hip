@@ -165,7 +165,7 @@ int des_moe_forward(const des_shape_t* s, const void* x, const void* w_router,
   char* ws = static_cast<char*>(workspace);
   const unsigned long long epoch = next_epoch();
   rc = launch_routing(*s, x, w_router, router_bias, logits, coreset_idx, coreset_size, topk_idx,
-                      topk_w, expert_counts, n_unique, ws, epoch, st);
+                      topk_w, expert_counts, n_unique, nullptr, ws, epoch, st);
   if (rc != DES_OK) return rc;
   return launch_ffn(*s, x, w_gate, w_up, w_down, ws_gate, ws_up, ws_down, topk_idx, topk_w,
                     n_unique, y, ws, epoch, st);
@@ -210,6 +210,7 @@ int des_moe_stack_forward(const des_shape_t* s_in, int32_t n_layers, const void*
   if (!x || !w_router || !w_gate || !w_up || !w_down || !y || !expert_counts || !n_unique ||
       !workspace)
     return DES_ERR_NULL;
+  if (x == y) return DES_ERR_SHAPE;
   des_shape_t s = *s_in;
   s.residual = 1;
   if (s.ffn_shared > 0 && (!ws_gate || !ws_up || !ws_down)) return DES_ERR_NULL;
@@ -241,7 +242,8 @@ int des_moe_stack_forward(const des_shape_t* s_in, int32_t n_layers, const void*
     const unsigned long long epoch = next_epoch();
     rc = launch_routing(s, cur, wr, rb, logits, reinterpret_cast<int32_t*>(ws + l.core_idx),
                         reinterpret_cast<int32_t*>(ws + l.core_size), tidx, tw,
-                        expert_counts + li * M, n_unique + li, lws, epoch, st);
+                        expert_counts + li * M, n_unique + li,
+                        layer > 0 ? n_unique + li - 1 : nullptr, lws, epoch, st);
     if (rc != DES_OK) return rc;
     rc = launch_ffn(s, cur, wg, wu, wd, sg, su, sd, tidx, tw, n_unique + li, out, lws, epoch, st);
     if (rc != DES_OK) return rc;
@@ -272,6 +274,13 @@ int32_t des_coreset_from_beta(double beta, int32_t n_experts) {
   // from falling just below it in binary
   const int32_t c = static_cast<int32_t>(floor(beta * n_experts + 1e-9));
   return c < 1 ? 1 : c;
+}
+
+int des_test_hooks(int skip_router, int max_wait_iters) {
+  if (max_wait_iters < 0) return DES_ERR_SHAPE;
+  g_test_skip_router = skip_router < 0 ? 0 : (skip_router > 2 ? 1 : skip_router);
+  g_test_max_wait = max_wait_iters;
+  return DES_OK;
 }
 
 const char* des_strerror(int code) {

@@ -94,15 +94,6 @@ inline int max_live_experts(const des_shape_t& s) {
 // unit, and never more than this.
 constexpr int kMaxFusedRoutingBlocks = 256;
 
-// Readiness flags of the single-launch FFN: one per gate/up task (2 row tiles
-// of 16 intermediate units) and one per down task (64 output rows).
-inline size_t ffn_h_flags(const des_shape_t& s) {
-  return static_cast<size_t>(max_live_experts(s)) * (s.ffn / 32) + s.ffn_shared / 32;
-}
-inline size_t ffn_o_flags(const des_shape_t& s) {
-  return (static_cast<size_t>(max_live_experts(s)) + 1) * ((s.hidden / 16 + 3) / 4);
-}
-
 constexpr int kSlotToks = 32;  // tokens per slot kept in the slot-major token table
 
 // Blocks of more than 32 tokens: an expert's pairs are handed to the FFN
@@ -135,7 +126,6 @@ inline int selector_tokens_per_pass(int n_experts) {
 struct WsLayout {
   size_t flags;     // u64   [router tiles + 2 * max(B, kMaxSelGroups)]  epoch flags of the routing launch
   size_t sel_part;  // u32   [kMaxSelGroups][3][kSelPartStride]  selectors' election partials
-  size_t ffn_flags; // u64   [ffn_h_flags + ffn_o_flags]  cleared by the routing launch
   size_t slot_of;   // int32 [M]       slot of each live expert
   size_t slot_tok;  // u16   [n_slots][kSlotToks]  tokens of each slot's first pairs
   size_t offsets;   // int32 [M + 1]   exclusive scan of expert_counts
@@ -163,7 +153,6 @@ inline WsLayout ws_layout(const des_shape_t& s) {
   const size_t nsel = static_cast<size_t>(s.n_seqs) > kMaxSelGroups ? s.n_seqs : kMaxSelGroups;
   w.flags = p;    p = align256(p + 8 * (tiles + 2 * nsel));
   w.sel_part = p; p = align256(p + 4 * static_cast<size_t>(kMaxSelGroups) * 3 * kSelPartStride);
-  w.ffn_flags = p; p = align256(p + 8 * (ffn_h_flags(s) + ffn_o_flags(s)));
   w.slot_of = p;  p = align256(p + 4 * static_cast<size_t>(s.n_experts));
   w.slot_tok = p; p = align256(p + 2 * static_cast<size_t>(max_live_experts(s)) * kSlotToks);
   w.offsets = p;  p = align256(p + 4 * (static_cast<size_t>(s.n_experts) + 1));
@@ -187,8 +176,11 @@ int launch_select(const des_shape_t& s, const float* logits, int32_t* coreset_id
 // router + election + re-routing + permutation (one launch when it fits)
 int launch_routing(const des_shape_t& s, const void* x, const void* w_router, const float* bias,
                    float* logits, int32_t* coreset_idx, int32_t* coreset_size, int32_t* topk_idx,
-                   float* topk_w, int32_t* expert_counts, int32_t* n_unique, char* ws,
-                   unsigned long long epoch, hipStream_t st);
+                   float* topk_w, int32_t* expert_counts, int32_t* n_unique,
+                   const int32_t* prev_n_unique, char* ws, unsigned long long epoch,
+                   hipStream_t st);
+// Test hooks of the routing launch (des_test_hooks).
+extern int g_test_max_wait, g_test_skip_router;
 int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const void* w_up,
                const void* w_down, const void* ws_gate, const void* ws_up, const void* ws_down,
                const int32_t* topk_idx, const float* topk_w, int32_t* n_unique, void* y, char* ws,

@@ -18,8 +18,6 @@
 // Nothing is accumulated with floating-point atomics: gate/up writes the
 // SwiGLU activations H, down writes one fp32 row per (token, expert) pair, and
 // the combine adds a token's K rows in slot order.
-#include <stdlib.h>
-
 #include <type_traits>
 
 #include "des_common.h"
@@ -42,19 +40,10 @@ struct FfnArgs {
   float* o;                     // [(TK + T) x D]
   void* y;                      // [T][D]
   int T, D, M, F, Fs, K, n_slots, residual;
-  // single-launch form: readiness flags between the phases (see ffn_fused_kernel)
-  unsigned long long* h_ready;  // [n_slots * gate/up tasks per expert + shared gate/up tasks]
-  unsigned long long* o_ready;  // [(n_slots + 1) * row groups]
-  unsigned long long epoch;
-  const int32_t* slot_of;       // [M] slot of a live expert
-  int32_t* n_unique;            // set to -1 if a bounded wait expires
-  int n_waves;                  // wavefronts of the single-launch grid
   int splits;                   // units the shared expert's rows are spread over (LDS kernels)
   const int32_t* units;         // live units of the routed experts, longest expert first:
                                 // slot | split << 16 | splits of that slot << 24; meta[2] of them
 };
-
-constexpr int kFfnMaxWaitIters = 1 << 22;
 
 #ifdef DES_FFN_STAMPS  // development aid (build with DES_FFN_STAMPS=1): per-task 100 MHz
                        // timestamps of the gate/up kernels, [start, task found, end, hardware id
@@ -64,60 +53,6 @@ __device__ long long g_ffn_stamps[8192 * 4];
 #else
 #define DES_FSTAMP(task, i) do { } while (0)
 #endif
-
-// Waits until f[0..n) all hold `epoch` (lanes poll in parallel); false if the
-// bounded wait ran out.  Ends with an acquire fence for the whole wavefront.
-__device__ __forceinline__ bool wait_flags(const unsigned long long* f, int n,
-                                           unsigned long long epoch, int lane) {
-  bool ok = true;
-  for (int i = lane; i < n; i += 64) {
-    int it = 0;
-    // relaxed polls (an acquire here would invalidate the L2 on every iteration)
-    while (__hip_atomic_load(f + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
-      __builtin_amdgcn_s_sleep(8);
-      if (++it > kFfnMaxWaitIters) { ok = false; break; }
-    }
-  }
-  ok = __all(ok ? 1 : 0) != 0;
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // orders the reads below; data reads
-  return ok;                                              // are device-scope themselves
-}
-// Data that crosses from one wavefront to another inside the single-launch FFN
-// (H, O) is written and read with device-scope accesses, which go through to
-// the level all compute units share, instead of ordinary accesses bracketed by
-// device-scope fences: a fence writes back or invalidates a whole L2, and ~2000
-// wavefronts doing that was measured to cost 5x the kernel's run time.
-__device__ __forceinline__ void st_dev_u64(void* p, unsigned long long v) {
-  __hip_atomic_store(static_cast<unsigned long long*>(p), v, __ATOMIC_RELAXED,
-                     __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ unsigned long long ld_dev_u64(const void* p) {
-  return __hip_atomic_load(static_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
-}
-struct U64x2 { unsigned long long a, b; };
-__device__ __forceinline__ bf16x8 ld8_dev(const uint16_t* p) {
-  U64x2 v{ld_dev_u64(p), ld_dev_u64(p + 4)};
-  return __builtin_bit_cast(bf16x8, v);
-}
-__device__ __forceinline__ float4 ld_f4_dev(const float* p) {
-  U64x2 v{ld_dev_u64(p), ld_dev_u64(p + 2)};
-  return __builtin_bit_cast(float4, v);
-}
-// The wavefront's device-scope stores have completed (the workgroup-scope
-// release waits for them without touching the L2), then the flag goes up.
-__device__ __forceinline__ void publish_flag(unsigned long long* f, unsigned long long epoch,
-                                             int lane) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  if (lane == 0) st_dev_u64(f, epoch);
-}
-// What a down task must wait for before it may read H (null flags = nothing).
-struct HWait {
-  const unsigned long long* flags;
-  int n;
-  unsigned long long epoch;
-  bool* failed;
-};
 
 // Work item of one wavefront: which expert's rows, which pairs.
 struct Task {
@@ -166,7 +101,7 @@ __device__ __forceinline__ bf16x8 zero8() {
 
 // gate/up for pairs [g0, g0 + 16*NT) of the task, intermediate rows
 // (ft0 .. ft0+FT-1)*16..+15.  The FT row tiles share every token fragment.
-template <int FT, int NT, int U, bool PACKED, bool COH>
+template <int FT, int NT, int U, bool PACKED>
 __device__ __forceinline__ void gateup_group(const FfnArgs& a, const Task& t, int ft0, int g0,
                                              int lane) {
   const int D = a.D;
@@ -252,8 +187,7 @@ __device__ __forceinline__ void gateup_group(const FfnArgs& a, const Task& t, in
 #pragma unroll
         for (int q = 0; q < 4; ++q) v[q] = f32_to_bf16_bits(silu_f(accg[f][i][q]) * accu[f][i][q]);
         uint16_t* dst = h + (t.row_base + pi) * t.fdim + (ft0 + f) * 16 + 4 * (lane >> 4);
-        if (COH) st_dev_u64(dst, __builtin_bit_cast(unsigned long long, v));
-        else *reinterpret_cast<u16x4*>(dst) = v;
+        *reinterpret_cast<u16x4*>(dst) = v;
       }
     }
   }
@@ -271,7 +205,11 @@ __device__ __forceinline__ bool make_task(const FfnArgs& a, int slot_or_shared, 
       t.pre_tok[0] = st[0];
       t.pre_tok[1] = st[16];
     }
-    if (sl.x < 0) return false;
+    // an unused slot; also refuses a record that does not fit the problem (the
+    // workspace is the caller's memory: never index weights or pairs with it blindly)
+    if (sl.x < 0 || sl.x >= a.M || sl.y < 0 || sl.z < 1 ||
+        static_cast<long long>(sl.y) + sl.z > static_cast<long long>(a.T) * a.K)
+      return false;
     const int e = sl.x;
     const int off = sl.y;
     t.slot = slot_or_shared;
@@ -324,8 +262,7 @@ constexpr int kGuTiles = 2;   // gate/up row tiles per task (F % 32 == 0, so F/1
 // stages of two k-steps measured best on the 128-expert layer (34.3 us against
 // 36.2 us for four and 34.5 us for one).
 // One gate/up task (see the kernel comment): returns false if the slot is unused.
-// `fused`: publish the task's readiness flag when its H rows are stored.
-template <int MAXNT, bool PACKED, bool FUSED, int U1 = 2, int U2 = 2, int GT = kGuTiles>
+template <int MAXNT, bool PACKED, int U1 = 2, int U2 = 2, int GT = kGuTiles>
 __device__ __forceinline__ bool gateup_task(const FfnArgs& a, int task, int lane) {
   const int tiles_r = a.F / (16 * GT);
   const int routed = a.n_slots * tiles_r;
@@ -345,31 +282,31 @@ __device__ __forceinline__ bool gateup_task(const FfnArgs& a, int task, int lane
   const int nt = (t.count + 15) / 16;
   bool done = false;
   if (MAXNT == 1 || nt <= 1) {
-    gateup_group<GT, 1, U1, PACKED, FUSED>(v, t, ft, 0, lane);
+    gateup_group<GT, 1, U1, PACKED>(v, t, ft, 0, lane);
     done = true;
   }
   if constexpr (MAXNT >= 2) {
     if (!done && (MAXNT == 2 || nt <= 2)) {
-      gateup_group<GT, 2, U2, PACKED, FUSED>(v, t, ft, 0, lane);
+      gateup_group<GT, 2, U2, PACKED>(v, t, ft, 0, lane);
       done = true;
     }
   }
   if constexpr (MAXNT >= 4) {
     if (!done && (MAXNT == 4 || nt <= 4)) {
-      gateup_group<GT, 4, 2, PACKED, FUSED>(v, t, ft, 0, lane);
+      gateup_group<GT, 4, 2, PACKED>(v, t, ft, 0, lane);
       done = true;
     }
   }
   if constexpr (MAXNT >= 8) {
     if (!done && (MAXNT == 8 || nt <= 8)) {
-      gateup_group<GT, 8, 1, PACKED, FUSED>(v, t, ft, 0, lane);
+      gateup_group<GT, 8, 1, PACKED>(v, t, ft, 0, lane);
       done = true;
     }
   }
   if constexpr (MAXNT >= 16) {
     if (!done)
       for (int g0 = 0; g0 < t.count; g0 += 256)
-        for (int f = 0; f < GT; ++f) gateup_group<1, 16, 1, PACKED, FUSED>(v, t, ft + f, g0, lane);
+        for (int f = 0; f < GT; ++f) gateup_group<1, 16, 1, PACKED>(v, t, ft + f, g0, lane);
   }
   DES_FSTAMP(task, 2);
 #ifdef DES_FFN_STAMPS
@@ -377,7 +314,6 @@ __device__ __forceinline__ bool gateup_task(const FfnArgs& a, int task, int lane
     g_ffn_stamps[task * 4 + 3] = (static_cast<long long>(__builtin_amdgcn_s_getreg(20 | (31 << 11))) << 32) |
                                  static_cast<unsigned>(__builtin_amdgcn_s_getreg(4 | (31 << 11)));
 #endif
-  if (FUSED) publish_flag(a.h_ready + task, a.epoch, lane);
   return true;
 }
 
@@ -393,13 +329,13 @@ __global__ __launch_bounds__(kFfnWaves* kWave) void gateup_bf16_kernel(FfnArgs a
   const int lane = threadIdx.x & 63;
   const int task = blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
   const int tasks = a.n_slots * (a.F / (16 * GT)) + a.Fs / (16 * GT);
-  if (task < tasks) gateup_task<MAXNT, PACKED, false, U1, U2, GT>(a, task, lane);
+  if (task < tasks) gateup_task<MAXNT, PACKED, U1, U2, GT>(a, task, lane);
 }
 
 // down for pairs [g0, g0+16*NT), output rows (dt0 .. dt0+RT-1)*16
-template <int RT, int NT, int U, bool PACKED, bool COH>
+template <int RT, int NT, int U, bool PACKED>
 __device__ __forceinline__ void down_group(const FfnArgs& a, const Task& t, int dt0, int g0,
-                                           int lane, HWait* hw = nullptr) {
+                                           int lane) {
   const int F = t.fdim;
   const int nks = F / 32;
   const uint16_t* h = static_cast<const uint16_t*>(a.h);
@@ -435,7 +371,7 @@ __device__ __forceinline__ void down_group(const FfnArgs& a, const Task& t, int 
     for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int i = 0; i < NT; ++i)
-        bh[s][u][i] = (ks + u < nks) ? (COH ? ld8_dev(hp[i] + (ks + u) * 32) : ld8(hp[i] + (ks + u) * 32))
+        bh[s][u][i] = (ks + u < nks) ? ld8(hp[i] + (ks + u) * 32)
                                      : zero8();
     }
   };
@@ -454,14 +390,7 @@ __device__ __forceinline__ void down_group(const FfnArgs& a, const Task& t, int 
           acc[r][i] =
               __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw[s][u][r], bh[s][u][i], acc[r][i], 0, 0, 0);
   };
-  // The weights do not depend on H: their first fragments are already in
-  // flight while the wavefront waits for the expert's activations.
-  load_w(0, S0{});
-  if (hw != nullptr && hw->flags != nullptr) {
-    if (!wait_flags(hw->flags, hw->n, hw->epoch, lane)) *hw->failed = true;
-    hw->flags = nullptr;  // a task waits once
-  }
-  load_h(0, S0{});
+  load(0, S0{});
   for (int ks = 0; ks < nks; ks += 2 * U) {
     load(ks + U, S1{});
     compute(S0{});
@@ -476,43 +405,29 @@ __device__ __forceinline__ void down_group(const FfnArgs& a, const Task& t, int 
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
         float* dst = a.o + (orow0 + pi) * a.D + (dt0 + r) * 16 + 4 * (lane >> 4);
-        if (COH) {
-          const U64x2 v = __builtin_bit_cast(U64x2, acc[r][i]);
-          st_dev_u64(dst, v.a);
-          st_dev_u64(dst + 2, v.b);
-        } else {
-          *reinterpret_cast<f32x4*>(dst) = acc[r][i];
-        }
+        *reinterpret_cast<f32x4*>(dst) = acc[r][i];
       }
     }
   }
 }
 
 // One down task: 64 output rows of one expert for all of its pairs.
-template <int MAXNT, bool PACKED, bool FUSED, int U1 = 2, int U2 = 2, int RTG = 4>
+template <int MAXNT, bool PACKED, int U1 = 2, int U2 = 2, int RTG = 4>
 __device__ __forceinline__ bool down_task(const FfnArgs& a, int task, int lane) {
   const int dtiles = a.D / 16;
   const int groups = (dtiles + RTG - 1) / RTG;  // 16 * RTG output rows per task
   const int routed = a.n_slots * groups;
-  const int tiles_r = a.F / (16 * kGuTiles);
   Task t;
   int dg;
   FfnArgs v = a;
-  bool failed = false;
-  HWait hw{nullptr, 0, a.epoch, &failed};
   if (task < routed) {
     const int slot = task / groups;
     if (!make_task(a, slot, false, true, t, lane)) return false;
     dg = task % groups;
-    if (FUSED) { hw.flags = a.h_ready + static_cast<size_t>(slot) * tiles_r; hw.n = tiles_r; }
   } else {
     make_task(a, 0, true, true, t, lane);
     v = shared_view(a, t, 2);
     dg = task - routed;
-    if (FUSED) {
-      hw.flags = a.h_ready + static_cast<size_t>(a.n_slots) * tiles_r;
-      hw.n = a.Fs / (16 * kGuTiles);
-    }
   }
   const int dt_begin = dg * RTG;
   const int dt_end = min(dt_begin + RTG, dtiles);
@@ -520,25 +435,25 @@ __device__ __forceinline__ bool down_task(const FfnArgs& a, int task, int lane) 
   bool done = false;
   if (dt_end - dt_begin == RTG) {
     if (MAXNT == 1 || nt <= 1) {
-      down_group<RTG, 1, U1, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
+      down_group<RTG, 1, U1, PACKED>(v, t, dt_begin, 0, lane);
       done = true;
     }
     if constexpr (MAXNT >= 2) {
       if (!done && (MAXNT == 2 || nt <= 2)) {
-        down_group<RTG, 2, U2, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
+        down_group<RTG, 2, U2, PACKED>(v, t, dt_begin, 0, lane);
         done = true;
       }
     }
     if constexpr (MAXNT >= 4) {
       if (!done && (MAXNT == 4 || nt <= 4)) {
-        down_group<RTG, 4, 1, PACKED, FUSED>(v, t, dt_begin, 0, lane, &hw);
+        down_group<RTG, 4, 1, PACKED>(v, t, dt_begin, 0, lane);
         done = true;
       }
     }
     if constexpr (MAXNT >= 8) {
       if (!done && (MAXNT == 8 || nt <= 8)) {
         for (int r2 = 0; r2 < RTG; r2 += 2)
-          down_group<2, 8, 1, PACKED, FUSED>(v, t, dt_begin + r2, 0, lane, &hw);
+          down_group<2, 8, 1, PACKED>(v, t, dt_begin + r2, 0, lane);
         done = true;
       }
     }
@@ -546,18 +461,11 @@ __device__ __forceinline__ bool down_task(const FfnArgs& a, int task, int lane) 
   if (!done) {  // ragged row group, or more than 128 pairs: one row tile at a time
     for (int dt = dt_begin; dt < dt_end; ++dt) {
       if constexpr (MAXNT <= 4) {
-        down_group<1, MAXNT, 2, PACKED, FUSED>(v, t, dt, 0, lane, &hw);
+        down_group<1, MAXNT, 2, PACKED>(v, t, dt, 0, lane);
       } else {
         for (int g0 = 0; g0 < t.count; g0 += 16 * MAXNT)
-          down_group<1, MAXNT, 1, PACKED, FUSED>(v, t, dt, g0, lane, &hw);
+          down_group<1, MAXNT, 1, PACKED>(v, t, dt, g0, lane);
       }
-    }
-  }
-  if (FUSED) {
-    if (failed) {
-      if (lane == 0) a.n_unique[0] = -1;  // a bounded wait expired: results undefined
-    } else {
-      publish_flag(a.o_ready + task, a.epoch, lane);
     }
   }
   return true;
@@ -569,7 +477,7 @@ __global__ __launch_bounds__(kFfnWaves* kWave) void down_bf16_kernel(FfnArgs a) 
   const int task = blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
   const int groups = (a.D / 16 + RTG - 1) / RTG;
   const int tasks = a.n_slots * groups + (a.Fs > 0 ? groups : 0);
-  if (task < tasks) down_task<MAXNT, PACKED, false, U1, U2, RTG>(a, task, lane);
+  if (task < tasks) down_task<MAXNT, PACKED, U1, U2, RTG>(a, task, lane);
 }
 
 // ------------------------------------------ larger blocks: activations via LDS
@@ -894,6 +802,7 @@ __device__ __forceinline__ bool lds_task(const FfnArgs& a, int per_expert, int p
   const int u = bx / per_expert;
   if (u >= a.meta[2]) return false;
   const int rec = a.units[u];
+  if ((rec & 0xffff) >= a.n_slots || (rec >> 24) < 1 || (rec >> 24) > kMaxSplits) return false;
   split = (rec >> 16) & 0xff;
   nsplit = rec >> 24;
   group = bx % per_expert;
@@ -1166,124 +1075,6 @@ __global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
   }
 }
 
-// ----------------------------------------------------- single-launch FFN
-// Combine task of the single-launch form: 64 output columns (row group dg) of
-// 8 tokens.  It waits for the down tasks that produce exactly the O rows it
-// reads: (slot of expert S_n[j], dg) for its tokens, plus the shared expert's.
-template <bool BF16>
-__device__ __forceinline__ void combine_task(const FfnArgs& a, int task, int lane) {
-  const int groups = (a.D / 16 + 3) / 4;
-  const int dg = task % groups, tg = task / groups;
-  const int K = a.K;
-  bool ok = true;
-  for (int i = lane; i < 8 * K + 1; i += 64) {
-    const unsigned long long* f = nullptr;
-    if (i < 8 * K) {
-      const int t = tg * 8 + i / K;
-      if (t < a.T) {
-        const int e = a.topk_idx[t * K + i % K];
-        if (e >= 0) f = a.o_ready + static_cast<size_t>(a.slot_of[e]) * groups + dg;
-      }
-    } else if (a.Fs > 0) {
-      f = a.o_ready + static_cast<size_t>(a.n_slots) * groups + dg;
-    }
-    if (f != nullptr) {
-      int it = 0;
-      while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch) {
-        __builtin_amdgcn_s_sleep(8);
-        if (++it > kFfnMaxWaitIters) { ok = false; break; }
-      }
-    }
-  }
-  ok = __all(ok ? 1 : 0) != 0;
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-  if (!ok) {
-    if (lane == 0) a.n_unique[0] = -1;
-    return;
-  }
-  const int d = dg * 64 + (lane & 15) * 4;
-  if (d >= a.D) return;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int t = tg * 8 + (lane >> 4) + 4 * i;
-    if (t >= a.T) continue;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int j = 0; j < K; ++j) {  // slot order: fixed
-      const int r = a.pos[t * K + j];
-      if (r < 0) continue;
-      const float w = a.topk_w[t * K + j];
-      const float4 v = ld_f4_dev(a.o + static_cast<size_t>(r) * a.D + d);
-      acc.x = fmaf(w, v.x, acc.x);
-      acc.y = fmaf(w, v.y, acc.y);
-      acc.z = fmaf(w, v.z, acc.z);
-      acc.w = fmaf(w, v.w, acc.w);
-    }
-    if (a.Fs > 0) {
-      const size_t r = static_cast<size_t>(a.T) * K + t;
-      const float4 v = ld_f4_dev(a.o + r * a.D + d);
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-    }
-    const size_t xo = static_cast<size_t>(t) * a.D + d;
-    if (BF16) {
-      if (a.residual) {
-        const u16x4 xv = *reinterpret_cast<const u16x4*>(static_cast<const uint16_t*>(a.x) + xo);
-        acc.x += bf16_bits_to_f32(xv[0]); acc.y += bf16_bits_to_f32(xv[1]);
-        acc.z += bf16_bits_to_f32(xv[2]); acc.w += bf16_bits_to_f32(xv[3]);
-      }
-      u16x4 out;
-      out[0] = f32_to_bf16_bits(acc.x); out[1] = f32_to_bf16_bits(acc.y);
-      out[2] = f32_to_bf16_bits(acc.z); out[3] = f32_to_bf16_bits(acc.w);
-      *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(a.y) + xo) = out;
-    } else {
-      if (a.residual) {
-        const float4 xv = *reinterpret_cast<const float4*>(static_cast<const float*>(a.x) + xo);
-        acc.x += xv.x; acc.y += xv.y; acc.z += xv.z; acc.w += xv.w;
-      }
-      *reinterpret_cast<float4*>(static_cast<float*>(a.y) + xo) = acc;
-    }
-  }
-}
-
-// gate/up, down and combine in ONE launch.  The grid is a fixed number of
-// wavefronts, all resident at once; wavefront w takes the tasks w, w + n_waves,
-// ... of the list [gate/up tasks][down tasks][combine tasks].  A down task
-// waits for the gate/up tasks of its expert (one flag each), a combine task for
-// the down tasks whose rows it reads; gate/up tasks never wait, and since a
-// wavefront's own tasks are in list order no wait can depend on itself: every
-// wait ends.  Flags are 64-bit words set to the call's epoch by their one
-// producer (no read-modify-write) and cleared by the routing launch of the
-// same call.  What this buys over three launches: no launch gaps, the down
-// tasks' first weight fragments are in flight while gate/up still runs, and
-// the combine starts per row group as soon as its rows exist.
-template <int MAXNT, bool PACKED>
-__global__ __launch_bounds__(kWave, (MAXNT <= 2 ? 2 : 1)) void ffn_fused_kernel(FfnArgs a) {
-  const int lane = threadIdx.x;
-  const int groups = (a.D / 16 + 3) / 4;
-  const int gu = a.n_slots * (a.F / (16 * kGuTiles)) + a.Fs / (16 * kGuTiles);
-  const int dn = a.n_slots * groups + (a.Fs > 0 ? groups : 0);
-  const int cb = groups * ((a.T + 7) / 8);
-  for (int task = blockIdx.x; task < gu + dn + cb; task += a.n_waves) {
-    if (task < gu) gateup_task<MAXNT, PACKED, true>(a, task, lane);
-    else if (task < gu + dn) down_task<MAXNT, PACKED, true>(a, task - gu, lane);
-    else combine_task<true>(a, task - gu - dn, lane);
-  }
-}
-
-// Resident wavefronts the device can hold of a kernel (64-thread workgroups), cached.
-template <typename Kern>
-static int resident_waves(Kern kernel) {
-  static int cached = -1;
-  if (cached < 0) {
-    int per_cu = 0, dev = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kWave, 0) != hipSuccess ||
-        hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-      return 0;
-    cached = per_cu * cus;
-  }
-  return cached;
-}
-
 // ------------------------------------------------------------------ packing
 // dst tile layout documented in des.h (des_pack_expert_weights).
 __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ src,
@@ -1370,12 +1161,6 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
   a.n_slots = max_live_experts(s);
   a.residual = s.residual;
   a.splits = 1;
-  a.h_ready = reinterpret_cast<unsigned long long*>(ws + w.ffn_flags);
-  a.o_ready = a.h_ready + ffn_h_flags(s);
-  a.epoch = epoch;
-  a.slot_of = reinterpret_cast<const int32_t*>(ws + w.slot_of);
-  a.n_unique = n_unique;
-  a.n_waves = 0;
   const int TK = a.T * a.K;
 
   if (s.dtype == DES_BF16) {
@@ -1388,23 +1173,6 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     // an expert serves a token at most once, so no task has more than T pairs
     const int maxnt = (a.T + 15) / 16;
     const dim3 blk(kFfnWaves * kWave);
-    const int total_tasks = gu_tasks + dn_tasks + groups * ((a.T + 7) / 8);
-    // The single-launch form is correct but measured slower than three launches
-    // (67 vs 60 us on the 128-expert layer: a flag handshake through device-scope
-    // memory costs about as much as a launch, and all experts finish gate/up at
-    // the same time, so there is little to overlap); it stays selectable for study.
-    static const bool fused_requested = getenv("DES_FFN_SINGLE_LAUNCH") != nullptr;
-    // single launch: only as many wavefronts as are certainly resident together
-#define DES_TRY_FUSED(NTV, PK)                                                              \
-  do {                                                                                      \
-    const int cap = resident_waves(ffn_fused_kernel<NTV, PK>) / 4 * 3;                      \
-    if (cap >= 64) {                                                                        \
-      a.n_waves = total_tasks < cap ? total_tasks : cap;                                    \
-      launch(kKFfn, ffn_fused_kernel<NTV, PK>, dim3(a.n_waves), dim3(kWave), 0, st, a);     \
-      const hipError_t fe = hipGetLastError();                                              \
-      return fe == hipSuccess ? DES_OK : hip_fail(fe, "ffn launch");                        \
-    }                                                                                       \
-  } while (0)
     // Few experts (small coreset): halve the task size so that enough wavefronts
     // keep bytes in flight.  Measured: gate/up gains below ~512 tasks (18.4 vs
     // 20.5 us at 272) and loses above (36.4 vs 34.4 us at 768); the down projection
@@ -1416,7 +1184,6 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     const int dn_fine_tasks = a.n_slots * dn_fine_groups + (a.Fs > 0 ? dn_fine_groups : 0);
 #define DES_LAUNCH_FFN(NTV, PK)                                                             \
   do {                                                                                      \
-    if (fused_requested) DES_TRY_FUSED(NTV, PK);                                            \
     if (gu_fine && NTV <= 2)                                                                \
       launch(kKGateUp, gateup_bf16_kernel<NTV, PK, 4, 4, 1>, dim3(gu_fine_tasks), blk, 0, st, a); \
     else                                                                                    \
@@ -1435,7 +1202,7 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     else DES_LAUNCH_FFN(16, PK);                                                            \
   } while (0)
     const bool chunked = a.D % kKC == 0 && a.F % kKC == 0 && a.Fs % kKC == 0;
-    if (a.T > 32 && chunked && !fused_requested) {
+    if (a.T > 32 && chunked) {
       // Larger blocks: activations staged through LDS.  Token rows per workgroup
       // pass: 64 while no expert can have more, else 128; an expert with more
       // pairs is spread over up to kMaxSplits workgroups (the unit list).  Wavefronts per workgroup:
@@ -1491,7 +1258,6 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     }
 #undef DES_LAUNCH_BY_NT
 #undef DES_LAUNCH_FFN
-#undef DES_TRY_FUSED
     dim3 cg(a.T, (a.D / 4 + 255) / 256);
     launch(kKCombine, combine_kernel<true>, cg, dim3(256), 0, st, a);
   } else {

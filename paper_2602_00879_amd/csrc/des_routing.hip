@@ -34,6 +34,8 @@ namespace des {
 constexpr int kRtWaves = 16;
 constexpr int kRtThreads = kRtWaves * kWave;  // 1024
 constexpr int kMaxWaitIters = 1 << 22;        // bounded waits (~ seconds), then give up
+int g_test_max_wait = 0;     // test hooks (des_test_hooks): a tiny wait bound, and a fused
+int g_test_skip_router = 0;  // routing launch without its router tiles, so that a wait expires
 
 #ifdef DES_ROUTING_TIMESTAMPS  // development aid: 100 MHz timestamps into meta[16..]
 #define DES_STAMP(a, i) do { if (threadIdx.x == 0 && (a).meta != nullptr) reinterpret_cast<long long*>((a).meta + 16)[i] = wall_clock64(); } while (0)
@@ -68,8 +70,6 @@ struct RoutingArgs {
                               // partials published, selectors done
   uint32_t* sel_part;         // [B*groups][3][kSelPartStride] per-group election partials
   unsigned long long epoch;
-  unsigned long long* ffn_flags;  // readiness flags of the FFN launch, cleared here
-  int n_ffn_flags;
   int32_t* slot_of;       // [M] slot of each live expert, -1 otherwise
   uint16_t* slot_tok;     // [n_slots][kSlotToks] tokens of each slot's first pairs
   int B, N, M, K, C, k_seq, mode, cap, D, n_slots;
@@ -85,7 +85,11 @@ struct RoutingArgs {
   int vote_atomic;        // votes meet in floating-point LDS atomics (arrival order) instead of
                           // the fixed-order reduction
   int tiles_m, tiles_t;   // router tiles along experts / tokens
+  int max_wait;           // polls before a wait gives up
+  const int32_t* prev_n_unique;  // the previous layer's n_unique (a stack), or null: a negative
+                                 // value there is carried into this layer's n_unique
   int do_router, do_select, do_permute, use_flags, bf16;
+  int skip_router_tiles;  // test hook: the fused launch runs without its router tiles
 };
 
 // ------------------------------------------------------------------ flags
@@ -94,23 +98,25 @@ struct RoutingArgs {
 // and the waiter ends with one too.  Unfenced: the data itself is written and
 // read with device-scope accesses (the logits), which reach the level all
 // compute units share on their own, so the flag only has to follow them.
+// A workgroup barrier does not wait for outstanding stores: every thread that
+// stored data the flag stands for must have waited for its own stores
+// (stores_done()) BEFORE the barrier that precedes the publishing thread's call.
+__device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void flag_publish(unsigned long long* f, unsigned long long epoch,
                                              bool fenced) {
-  // all threads of the workgroup have passed a barrier (their stores have
-  // completed); one thread publishes
   if (fenced) __threadfence();
   __hip_atomic_store(f, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // Every thread polls a subset of the flags; returns false if a wait ran out.
 __device__ __forceinline__ bool flags_wait(const unsigned long long* f, int n,
-                                           unsigned long long epoch, bool fenced) {
+                                           unsigned long long epoch, bool fenced, int max_wait) {
   bool ok = true;
   for (int i = threadIdx.x; i < n; i += blockDim.x) {
     int it = 0;
     // relaxed polls; the fence after the barrier below is the acquire
     while (__hip_atomic_load(f + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
       __builtin_amdgcn_s_sleep(4);
-      if (++it > kMaxWaitIters) { ok = false; break; }
+      if (++it > max_wait) { ok = false; break; }
     }
   }
   const int all = __syncthreads_and(ok ? 1 : 0);
@@ -365,7 +371,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
   // the LDS set-up above does not need the logits: only now wait for the router
   // tiles (the wait ends with a barrier of its own)
   if (wait_router) {
-    if (!flags_wait(a.flags, a.tiles_m * a.tiles_t, a.epoch, false)) return false;
+    if (!flags_wait(a.flags, a.tiles_m * a.tiles_t, a.epoch, false, a.max_wait)) return false;
   } else {
     __syncthreads();
   }
@@ -542,11 +548,11 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
         __hip_atomic_store(mine + 2 * kSelPartStride + e, static_cast<uint32_t>(s_cnt1[e]),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's stores have been acknowledged
+      stores_done();
       __syncthreads();
       unsigned long long* pf = a.flags + a.tiles_m * a.tiles_t + b * G;
       if (threadIdx.x == 0) flag_publish(pf + g, a.epoch, false);
-      if (!flags_wait(pf, G, a.epoch, false)) return false;
+      if (!flags_wait(pf, G, a.epoch, false, a.max_wait)) return false;
       for (int e = threadIdx.x; e < MP; e += kRtThreads) {
         float v = 0.f;
         int lvl = K, c1 = 0;
@@ -866,7 +872,7 @@ __device__ void permute_all(const RoutingArgs& a, char* smem, bool idx_dev) {
       a.meta[0] = base_l;
       a.meta[1] = base_c;
       a.meta[2] = 0;  // live units: set after the barrier by the last slot's expert, if any
-      a.n_unique[0] = base_l;
+      a.n_unique[0] = (a.prev_n_unique != nullptr && a.prev_n_unique[0] < 0) ? -1 : base_l;
     }
   }
   __syncthreads();
@@ -883,7 +889,6 @@ __device__ void permute_all(const RoutingArgs& a, char* smem, bool idx_dev) {
       if (sl == n_live - 1) a.meta[2] = s_uoff[e] + nu;  // the last slot closes the list
     }
   }
-  for (int i = tid; i < a.n_ffn_flags; i += kRtThreads) a.ffn_flags[i] = 0ull;
   for (int s = n_live + tid; s < a.n_slots; s += kRtThreads) a.slots[s] = make_int4(-1, 0, 0, 0);
   // entries of the slot-major token table past a slot's count must still name a
   // valid token: clear the table, then (after the barrier) fill it
@@ -909,6 +914,30 @@ __device__ void permute_all(const RoutingArgs& a, char* smem, bool idx_dev) {
   for (int p = tid + kKeep * kRtThreads; p < TK; p += kRtThreads) place(p, get_idx(p));
 }
 
+// A bounded wait ran out (a fault of the device, or another kernel keeps this
+// launch's producers off the chip): leave an EMPTY work list, so that the FFN
+// launches that follow find no expert, index nothing and the combine adds no
+// routed row - y is then the shared expert's output (+ x under `residual`), and
+// n_unique = -1 says so.  Every workgroup that gives up writes the same values.
+__device__ void publish_empty(const RoutingArgs& a, int n_flags) {
+  const int tid = threadIdx.x;
+  if (a.slots != nullptr) {
+    for (int s = tid; s < a.n_slots; s += kRtThreads) a.slots[s] = make_int4(-1, 0, 0, 0);
+    for (int i = tid; i < a.B * a.N * a.K; i += kRtThreads) a.pos[i] = -1;
+    for (int e = tid; e <= a.M; e += kRtThreads) a.offsets[e] = 0;
+    for (int e = tid; e < a.M; e += kRtThreads) {
+      a.slot_of[e] = -1;
+      a.expert_counts[e] = 0;
+    }
+    if (tid < 3) a.meta[tid] = 0;
+  }
+  // the flags of this call are abandoned: clear them, so that a replay of a
+  // captured launch (same epoch) starts from flags that no producer has set
+  if (a.use_flags)
+    for (int i = tid; i < n_flags; i += kRtThreads) a.flags[i] = 0ull;
+  if (tid == 0 && a.n_unique) a.n_unique[0] = -1;
+}
+
 // ---------------------------------------------------------------- the kernel
 // LDS of the routing kernel: the selection's carve-up, but at least what the
 // router tile (16 KB) and the permutation (bitmap of at most 8192 words plus
@@ -919,7 +948,7 @@ template <int LPT, bool EXT>
 __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
   constexpr int kLds = SelLds<LPT>::total > kMinRoutingLds ? SelLds<LPT>::total : kMinRoutingLds;
   __shared__ __align__(16) char smem[kLds];
-  const int n_tiles = a.do_router ? a.tiles_m * a.tiles_t : 0;
+  const int n_tiles = (a.do_router && !a.skip_router_tiles) ? a.tiles_m * a.tiles_t : 0;
   int blk = blockIdx.x;
   if (blk < n_tiles) {  // ---- role R
     if (blk == 0) DES_STAMP(a, 8);
@@ -927,6 +956,7 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
     else router_tile_f32(a, blk % a.tiles_m, blk / a.tiles_m);
     if (blk == 0) DES_STAMP(a, 9);
     if (a.use_flags) {
+      stores_done();  // this thread's logits have reached the level all compute units share
       __syncthreads();
       if (threadIdx.x == 0) flag_publish(a.flags + blk, a.epoch, false);
     }
@@ -941,7 +971,7 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
     DES_STAMP(a, 0);
     if (!select_sequence<LPT, EXT>(a, blk / a.groups, blk % a.groups, smem, false,
                               a.use_flags && a.do_router)) {
-      if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
+      publish_empty(a, n_flags);  // a bounded wait expired
       return;
     }
     DES_STAMP(a, 5);
@@ -960,7 +990,7 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
       return;
     }
     if (a.use_flags) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's index stores have been acknowledged
+      stores_done();
       __syncthreads();
       if (threadIdx.x == 0) flag_publish(a.flags + all_tiles + n_sel + blk, a.epoch, false);
     }
@@ -969,8 +999,9 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
   blk -= n_sel;
   if (blk == 0 && a.do_permute && a.B * a.groups > 1) {  // ---- role P
     if (a.use_flags && a.do_select &&
-        !flags_wait(a.flags + all_tiles + a.B * a.groups, a.B * a.groups, a.epoch, false)) {
-      if (threadIdx.x == 0 && a.n_unique) a.n_unique[0] = -1;  // a bounded wait expired
+        !flags_wait(a.flags + all_tiles + a.B * a.groups, a.B * a.groups, a.epoch, false,
+                    a.max_wait)) {
+      publish_empty(a, n_flags);  // a bounded wait expired
       return;
     }
     permute_all<SelLds<LPT>::MP>(a, smem, a.use_flags && a.do_select);
@@ -1044,6 +1075,7 @@ static void fill_common(RoutingArgs& a, const des_shape_t& s) {
   a.tiles_t = (s.n_seqs * s.n_tokens + 15) / 16;
   a.bf16 = s.dtype == DES_BF16;
   a.groups = 1;
+  a.max_wait = g_test_max_wait > 0 ? g_test_max_wait : kMaxWaitIters;
   a.k_route = s.k_route > 0 ? s.k_route : s.top_k;
   a.skip_beta = s.skip_beta;
   a.sigmoid = s.router_act == DES_ROUTER_SIGMOID;
@@ -1087,11 +1119,13 @@ int launch_select(const des_shape_t& s, const float* logits, int32_t* coreset_id
 
 int launch_routing(const des_shape_t& s, const void* x, const void* w_router, const float* bias,
                    float* logits, int32_t* coreset_idx, int32_t* coreset_size, int32_t* topk_idx,
-                   float* topk_w, int32_t* expert_counts, int32_t* n_unique, char* ws,
-                   unsigned long long epoch, hipStream_t st) {
+                   float* topk_w, int32_t* expert_counts, int32_t* n_unique,
+                   const int32_t* prev_n_unique, char* ws, unsigned long long epoch,
+                   hipStream_t st) {
   const WsLayout w = ws_layout(s);
   RoutingArgs a;
   fill_common(a, s);
+  a.prev_n_unique = prev_n_unique;
   a.x = x; a.w_router = w_router; a.bias = bias; a.logits = logits;
   a.coreset_idx = coreset_idx; a.coreset_size = coreset_size;
   a.topk_idx = topk_idx; a.topk_w = topk_w;
@@ -1103,8 +1137,6 @@ int launch_routing(const des_shape_t& s, const void* x, const void* w_router, co
   a.pos = reinterpret_cast<int32_t*>(ws + w.pos);
   a.flags = reinterpret_cast<unsigned long long*>(ws + w.flags);
   a.epoch = epoch;
-  a.ffn_flags = reinterpret_cast<unsigned long long*>(ws + w.ffn_flags);
-  a.n_ffn_flags = static_cast<int>(ffn_h_flags(s) + ffn_o_flags(s));
   a.slot_of = reinterpret_cast<int32_t*>(ws + w.slot_of);
   a.units = reinterpret_cast<int32_t*>(ws + w.units);
   a.rows_shift = lds_rows_pass(s.n_seqs * s.n_tokens) == 64 ? 6 : 7;
@@ -1124,6 +1156,11 @@ int launch_routing(const des_shape_t& s, const void* x, const void* w_router, co
     a.groups = groups;
     a.do_router = a.do_select = a.do_permute = 1;
     a.use_flags = 1;
+    if (g_test_skip_router) {  // test hook: nobody computes the logits, the selectors' wait expires
+      a.skip_router_tiles = 1;
+      if (g_test_skip_router == 2) g_test_skip_router = g_test_max_wait = 0;  // one launch only
+      return launch_routing_grid(a, roles - n_tiles, kKRouting, st);
+    }
     return launch_routing_grid(a, roles, kKRouting, st);
   }
   // too large to wait inside one launch: the same roles as three launches

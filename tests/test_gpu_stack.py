@@ -57,8 +57,9 @@ def _run_stack_case(cfg, oracle_layers, n_tok_samples):
             def __getitem__(self, e):
                 return self.t[e].float().cpu().numpy().astype(np.float64)
 
-        ref = O.moe_forward(x64, st["w_router"][l].float().cpu().numpy().astype(np.float64),
-                            None if bias_l is None else bias_l.cpu().numpy().astype(np.float64),
+        wr64 = st["w_router"][l].float().cpu().numpy().astype(np.float64)
+        b64 = None if bias_l is None else bias_l.cpu().numpy().astype(np.float64)
+        ref = O.moe_forward(x64, wr64, b64,
                             Lazy(st["w_gate"][l]), Lazy(st["w_up"][l]), Lazy(st["w_down"][l]),
                             K, cfg.coreset, "vote", logits_override=g_logits, residual=True,
                             compute_y=want_y, only_tokens=toks)
@@ -87,6 +88,21 @@ def _run_stack_case(cfg, oracle_layers, n_tok_samples):
             assert max_abs <= H.BF16_MAX_ABS + 2.0 ** -8 * np.abs(ref["y"][sel]).max() and rel <= H.BF16_REL_L2, \
                 f"layer {l}: max_abs {max_abs:.3e} rel_l2 {rel:.3e}"
             _say(f"  layer {l}: unique={uniq[-1]} max_abs={max_abs:.2e} rel_l2={rel:.2e}")
+            # the MoE increment alone (no residual stream to hide behind), every token, at
+            # the plain tolerance: the same layer, same input, residual switched off
+            shape0 = B.make_shape(Bq, N, cfg.hidden, M, cfg.ffn, K, cfg.coreset, "vote", "bf16", residual=0)
+            r0 = B.des_moe_forward(shape0, cur, st["w_router"][l], bias_l, st["w_gate"][l], st["w_up"][l],
+                                   st["w_down"][l])
+            torch.cuda.synchronize()
+            assert torch.equal(r0.topk_idx, r.topk_idx)
+            ref0 = O.moe_forward(x64, wr64, b64, Lazy(st["w_gate"][l]), Lazy(st["w_up"][l]),
+                                 Lazy(st["w_down"][l]), K, cfg.coreset, "vote",
+                                 logits_override=g_logits, residual=False)
+            d0 = r0.y.float().cpu().numpy().astype(np.float64) - ref0["y"]
+            rel0 = np.sqrt((d0 ** 2).sum() / (ref0["y"] ** 2).sum())
+            assert np.abs(d0).max() <= H.BF16_MAX_ABS and rel0 <= H.BF16_REL_L2, \
+                f"layer {l} without residual: max_abs {np.abs(d0).max():.3e} rel_l2 {rel0:.3e}"
+            _say(f"  layer {l} MoE output alone, all tokens: max_abs={np.abs(d0).max():.2e} rel_l2={rel0:.2e}")
         cur = r.y.clone()
     assert torch.equal(cur, out.y), "stack output differs from the per-layer loop"
     _say(f"  unique experts per layer: min {min(uniq)} max {max(uniq)} mean {np.mean(uniq):.1f}")
@@ -105,3 +121,29 @@ def test_stack48_full_size():
     cfg = W.CONFIGS["stack48"]
     uniq = _run_stack_case(cfg, oracle_layers={0, 24, 47}, n_tok_samples=6)
     assert all(32 <= u <= 128 for u in uniq)
+
+
+def test_stack_carries_a_given_up_layer_forward():
+    """Layer 0's routing is made to give up from the host (one launch only): its
+    n_unique is -1 and every later layer, which runs normally, reports -1 as well, so a
+    caller that looks only at the last entry still learns that the step is invalid."""
+    cfg = W.LayerConfig("stack_small", "bf16", 3, 20, 128, 24, 64, 0, 4, 6, 1.1, 21, n_layers=4)
+    st = DW.make_stack(cfg)
+    shape = B.make_shape(cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k,
+                         cfg.coreset, "vote", "bf16", residual=1)
+    args = (shape, cfg.n_layers, st["x"], st["w_router"], st["bias"], st["w_gate"], st["w_up"], st["w_down"])
+    good = B.des_moe_stack_forward(*args)
+    torch.cuda.synchronize()
+    assert (good.n_unique > 0).all()
+    B.des_test_hooks(2, 16)
+    try:
+        out = B.des_moe_stack_forward(*args)
+        torch.cuda.synchronize()
+    finally:
+        B.des_test_hooks(0, 0)
+    assert out.n_unique.cpu().tolist() == [-1] * cfg.n_layers
+    assert int(out.expert_counts[0].abs().sum()) == 0 and int(out.expert_counts[1].sum()) > 0
+    again = B.des_moe_stack_forward(*args)
+    torch.cuda.synchronize()
+    assert torch.equal(again.y, good.y) and torch.equal(again.n_unique, good.n_unique)
+

@@ -416,7 +416,7 @@ def test_skip_in_route_block():
 
 # ------------------------------------------- other routers (Sec. 4.1, sigma)
 def test_sigmoid_router_and_renormalised_votes():
-    """sigma "from the model architecture": with a sigmoid router the weights are
+    """A sigma other than softmax (Sec. 4.1 leaves it to the model): with a sigmoid router the weights are
     logistic scores; rankings (and therefore DES-Seq and every top-K) do not
     change because the sigmoid is monotone; votes and gates do."""
     L = W.make_logits(20, 24, seed=3, zipf_s=0.7, scale=1.5)
