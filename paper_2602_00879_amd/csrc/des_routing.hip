@@ -881,7 +881,8 @@ __device__ void permute_all(const RoutingArgs& a, char* smem, bool idx_dev) {
   for (int e = tid; e < M; e += kRtThreads) {
     const int sl = by_count ? s_slot[e] : s_liv[e];
     const bool live = s_cnt[e] > 0 && sl < a.n_slots;
-    if (live) a.slots[sl] = make_int4(e, s_off[e], s_cnt[e], 0);
+    // (up to 32 tokens the expert's bitmap row is one word: the tokens routed to it)
+    if (live) a.slots[sl] = make_int4(e, s_off[e], s_cnt[e], words == 1 ? static_cast<int>(member[e]) : 0);
     a.slot_of[e] = live ? sl : -1;
     if (live && by_count) {
       const int nu = units_of(s_cnt[e]);
@@ -1053,7 +1054,7 @@ static int launch_routing_grid(const RoutingArgs& a, int grid, int kernel_id, hi
 // Compute units of the current device (cached).  A routing workgroup fills a
 // whole compute unit (16 wavefronts at up to 128 registers), so the fused
 // launch may use at most this many workgroups if all are to be resident.
-static int device_compute_units() {
+int device_compute_units() {
   static int cached_dev = -1, cached_cus = 0;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;

@@ -141,6 +141,15 @@ MID = dict(
     mid_f32=W.LayerConfig("mid_f32", "f32", 2, 9, 72, 24, 20, 12, 3, 6, 1.1, 12),
     wide_tok=W.LayerConfig("wide_tok", "bf16", 1, 150, 128, 12, 64, 0, 4, 3, 0.0, 13),
     many_tok=W.LayerConfig("many_tok", "bf16", 3, 100, 64, 8, 32, 32, 2, 2, 0.0, 14),
+    # blocks of at most 32 tokens in the shapes of the persistent short-block launch (one
+    # workgroup per compute unit, reduction split over its four wavefronts): a shared
+    # expert with F = 128 (one k-step per wavefront); two sequences, F = 256; 300 experts
+    # for 5 tokens (most workgroups get one tile or none, ragged tile pairs); exactly 32
+    # tokens (a full token bitmap) with few experts (several tiles of one expert per workgroup)
+    short_a=W.LayerConfig("short_a", "bf16", 1, 20, 256, 40, 128, 128, 4, 10, 1.1, 25),
+    short_b=W.LayerConfig("short_b", "bf16", 2, 13, 256, 24, 256, 0, 3, 6, 0.5, 26),
+    short_c=W.LayerConfig("short_c", "bf16", 1, 5, 256, 300, 128, 0, 8, 40, 0.3, 27),
+    short_d=W.LayerConfig("short_d", "bf16", 1, 32, 256, 16, 256, 256, 2, 4, 1.1, 28),
     # blocks of more than 32 tokens with D, F multiples of 128: the kernels that stage
     # the activations through LDS.  lds_64: one 64-row pass, a single 128-wide chunk in
     # the down projection; lds_128: 128-row passes, shared expert; lds_split: experts
@@ -409,14 +418,15 @@ def test_m128_block_size_sweep():
     assert uniq[(128, "vanilla")] > uniq[(32, "vanilla")] > uniq[(4, "vanilla")]
 
 
-@pytest.mark.parametrize("name", ["mid_bf16", "sel_groups"])
+@pytest.mark.parametrize("name", ["mid_bf16", "sel_groups", "short_a"])
 def test_graph_replay_matches_eager(name):
     """A captured des_moe_forward (kernels only, no memset nodes) replayed several
     times with new inputs, eager calls and synchronisations in between, must equal
     the eager result every time (the routing flags are cleared by their consumer,
     so a replay with the captured epoch cannot be satisfied by stale flags).
     mid_bf16: two selector workgroups and a permutation workgroup; sel_groups: six
-    selectors that also exchange their election partials."""
+    selectors that also exchange their election partials; short_a: the persistent
+    short-block launch, whose workgroups wait for each other's flags."""
     cfg = MID[name]
     layer = W.make_layer(cfg)
     dev = H.layer_to_device(layer)
@@ -529,7 +539,7 @@ def test_stale_scratch_cannot_leak_into_a_call():
     read the previous call's logits, indices, activations or expert outputs instead of
     waiting for this call's would change the result.  Short and long blocks, several
     selector workgroups, different inputs from call to call."""
-    for name in ("mid_bf16", "sel_groups", "lds_128"):
+    for name in ("mid_bf16", "sel_groups", "lds_128", "short_a", "short_b"):
         cfg = MID[name]
         layer = W.make_layer(cfg)
         dev = H.layer_to_device(layer)
