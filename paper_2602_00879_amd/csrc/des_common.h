@@ -95,9 +95,7 @@ inline int max_live_experts(const des_shape_t& s) {
 constexpr int kMaxFusedRoutingBlocks = 256;
 
 constexpr int kSlotToks = 32;  // tokens per slot kept in the slot-major token table
-constexpr int kShortMaxSlots = 512;  // live experts the short-block FFN launch can index
 int device_compute_units();          // of the current device (cached)
-int short_ffn_grid(const des_shape_t& s);
 
 // Blocks of more than 32 tokens: an expert's pairs are handed to the FFN
 // workgroups in units of this many token rows (what one workgroup pass holds),
@@ -129,7 +127,6 @@ inline int selector_tokens_per_pass(int n_experts) {
 struct WsLayout {
   size_t flags;     // u64   [router tiles + 2 * max(B, kMaxSelGroups)]  epoch flags of the routing launch
   size_t sel_part;  // u32   [kMaxSelGroups][3][kSelPartStride]  selectors' election partials
-  size_t h_flags;   // u64   [(n_slots + 1) * max(F, Fs)/16]  short-block FFN: H rows of a tile exist
   size_t slot_of;   // int32 [M]       slot of each live expert
   size_t slot_tok;  // u16   [n_slots][kSlotToks]  tokens of each slot's first pairs
   size_t offsets;   // int32 [M + 1]   exclusive scan of expert_counts
@@ -158,7 +155,6 @@ inline WsLayout ws_layout(const des_shape_t& s) {
   const size_t nsel = static_cast<size_t>(s.n_seqs) > kMaxSelGroups ? s.n_seqs : kMaxSelGroups;
   w.flags = p;    p = align256(p + 8 * (tiles + 2 * nsel));
   w.sel_part = p; p = align256(p + 4 * static_cast<size_t>(kMaxSelGroups) * 3 * kSelPartStride);
-  w.h_flags = p;  p = align256(p + 8 * (static_cast<size_t>(max_live_experts(s)) + 1) * (Fm / 16 + 1));
   w.slot_of = p;  p = align256(p + 4 * static_cast<size_t>(s.n_experts));
   w.slot_tok = p; p = align256(p + 2 * static_cast<size_t>(max_live_experts(s)) * kSlotToks);
   w.offsets = p;  p = align256(p + 4 * (static_cast<size_t>(s.n_experts) + 1));

@@ -43,13 +43,6 @@ struct FfnArgs {
   int splits;                   // units the shared expert's rows are spread over (LDS kernels)
   const int32_t* units;         // live units of the routed experts, longest expert first:
                                 // slot | split << 16 | splits of that slot << 24; meta[2] of them
-  // short blocks (ffn_short_kernel): one persistent launch for gate/up and down
-  unsigned long long* h_flags;  // [(n_slots + 1) * F/16] one per gate/up row tile: its H rows exist
-  unsigned long long epoch;     // the call's flag value
-  int max_wait;                 // polls before a wait gives up
-  int32_t* n_unique;            // set to -1 if a wait gives up
-  int packed;                   // weight layout (the short-block kernel takes it at run time)
-  int n_h_flags;                // flags the combine clears once the FFN launch has used them
 };
 
 #ifdef DES_FFN_STAMPS  // development aid (build with DES_FFN_STAMPS=1): per-task 100 MHz
@@ -608,391 +601,6 @@ __device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F&&
   (f(std::integral_constant<int, I>{}), ...);
 }
 
-// ------------------------------------- short blocks (T <= 32): one persistent launch
-// At most 32 tokens: the whole block is two token tiles, and an expert's pairs are a
-// subset of them.  The launch has one workgroup of four wavefronts per compute unit
-// and treats the live experts' weights as two tapes of 16-row tiles - gate/up tile
-// pairs, then down tiles - that are cut into equal contiguous pieces, one per
-// workgroup, so that every compute unit streams the same number of bytes (+-1 tile)
-// whatever the number of live experts.  Inside a workgroup the REDUCTION dimension is
-// split in four fixed quarters, one per wavefront (one per SIMD):
-//   * gate/up: the B operand is the block itself (tokens 0..31 in order, not the
-//     expert's own pairs), so a wavefront keeps its quarter of x in registers for the
-//     whole phase and the weight stream is the only memory traffic; rows of tokens
-//     that were not routed to the expert are computed and dropped at the store;
-//   * down: the B operand is the expert's H rows (its pairs in token order), loaded
-//     when the expert changes;
-//   * the four partial tiles meet in LDS and are added in wavefront order 0..3 - a
-//     fixed order, and a fixed split of the reduction range, so the result does not
-//     depend on how many experts are live or on which compute unit a tile lands.
-// gate/up and down share the launch: a workgroup that has stored its H rows raises one
-// flag per gate/up tile (value = the call's epoch), a workgroup about to multiply by an
-// expert's H waits for that expert's flags, with its first down-projection weights
-// already in flight.  H travels with device-scope stores and loads (the compute units
-// of different XCDs share no cache level below that).  Every workgroup is resident (one
-// per compute unit, never more than the device has), so the producers of a flag can
-// always run; the wait is bounded all the same and gives up with n_unique = -1.
-constexpr int kFfnMaxWaitIters = 1 << 22;  // bounded waits (~ seconds), then give up
-struct ShortTile {
-  const uint16_t *w0, *w1;  // gate and up rows (or down rows, -) of this tile, lane offset included
-  int row0;                 // first H / O row of the expert's pairs
-  int count;                // pairs of the expert
-  uint32_t mask;            // tokens routed to the expert
-  int col0;                 // first intermediate unit (gate/up) or output coordinate (down)
-  bool valid;
-};
-
-#ifndef DES_SHORT_SKG
-#define DES_SHORT_SKG 2
-#endif
-#ifndef DES_SHORT_RT
-#define DES_SHORT_RT 2
-#endif
-template <int KQ, int FQ>
-__global__ __launch_bounds__(256, 1) void ffn_short_kernel(FfnArgs a) {
-  constexpr int SKG = KQ >= 8 ? DES_SHORT_SKG : KQ / 2;  // k-steps per gate/up stage
-  constexpr int NSG = KQ / SKG;                          // stages per chunk (even)
-  constexpr int RT = DES_SHORT_RT;                       // down row tiles per chunk (2 or 4)
-  static_assert(NSG % 2 == 0 && SKG * NSG == KQ, "stage split of the gate/up quarter");
-  __shared__ __align__(16) f32x4 part[2][4][8][64];  // [buffer][wavefront][accumulator][lane]
-  __shared__ int4 s_rec[kShortMaxSlots + 1];          // slot records, shared expert last
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int q = __builtin_amdgcn_readfirstlane(tid >> 6);  // this wavefront's quarter
-  const int G = gridDim.x, b = blockIdx.x;
-  const int T = a.T, D = a.D, F = a.F;
-  const int TK = T * a.K;
-  const bool has_shared = a.Fs > 0;
-  int n_live = a.meta[0];
-  n_live = n_live < 0 ? 0 : (n_live > a.n_slots ? a.n_slots : n_live);
-  for (int i = tid; i <= n_live; i += 256) {
-    int4 r;
-    if (i < n_live) {
-      r = a.slots[i];
-      // refuse a record that does not fit the problem: it would index weights and rows
-      if (r.x < 0 || r.x >= a.M || r.y < 0 || r.z < 1 || r.z > T || r.y + r.z > TK) r = make_int4(-1, 0, 0, 0);
-    } else {
-      r = make_int4(0, TK, T, T >= 32 ? -1 : static_cast<int>((1u << T) - 1u));  // shared: every token
-    }
-    s_rec[i] = r;
-  }
-  const int tpe = F / 16, dpe = D / 16;
-  const int n_gu = n_live * tpe + (has_shared ? tpe : 0);
-  const int n_dn = (n_live + (has_shared ? 1 : 0)) * dpe;
-  const int gu0 = static_cast<int>(static_cast<long long>(b) * n_gu / G);
-  const int gu1 = static_cast<int>(static_cast<long long>(b + 1) * n_gu / G);
-  const int dn0 = static_cast<int>(static_cast<long long>(b) * n_dn / G);
-  const int dn1 = static_cast<int>(static_cast<long long>(b + 1) * n_dn / G);
-  const bool packed = a.packed != 0;
-  // element offset of this lane inside a 16-row tile, and between k-steps of a tile
-  const int lrow = lane & 15, lkg = lane >> 4;
-  const uint16_t* xq = static_cast<const uint16_t*>(a.x) + static_cast<size_t>(q) * KQ * 32 + lkg * 8;
-  DES_FSTAMP(b * 2, 0);
-  __syncthreads();
-
-  // ---------------------------------------------------------------- gate / up
-  {
-    const int lane_off = packed ? lane * 8 : lrow * D + lkg * 8;
-    const int kstep = packed ? 512 : 32;
-    auto tile_at = [&](int p) {
-      ShortTile t;
-      t.valid = p < gu1;
-      const int pp = t.valid ? p : gu0;  // (gu0 < gu1 whenever this is called)
-      const int slot = min(pp / tpe, n_live);
-      const int rt = pp - slot * tpe;
-      const int4 r = s_rec[slot];
-      t.valid = t.valid && r.x >= 0;
-      const size_t mat = static_cast<size_t>(F) * D;
-      const uint16_t* g = slot < n_live ? static_cast<const uint16_t*>(a.wg) + (r.x < 0 ? 0 : r.x) * mat
-                                        : static_cast<const uint16_t*>(a.sg);
-      const uint16_t* u = slot < n_live ? static_cast<const uint16_t*>(a.wu) + (r.x < 0 ? 0 : r.x) * mat
-                                        : static_cast<const uint16_t*>(a.su);
-      const size_t o = static_cast<size_t>(rt) * 16 * D + static_cast<size_t>(q) * KQ * kstep + lane_off;
-      t.w0 = g + o;
-      t.w1 = u + o;
-      t.row0 = r.y;
-      t.count = r.z;
-      t.mask = static_cast<uint32_t>(r.w);
-      t.col0 = rt * 16;
-      return t;
-    };
-    // this wavefront's quarter of the block, as B operands, for the whole phase
-    bf16x8 xs[KQ][2];
-    if (gu0 < gu1) {
-#pragma unroll
-      for (int k = 0; k < KQ; ++k)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-          xs[k][i] = ld8(xq + static_cast<size_t>(min(i * 16 + lrow, T - 1)) * D + k * 32);
-    }
-    bf16x8 wg[2][SKG][2], wu[2][SKG][2];
-    auto issue = [&](const ShortTile (&t)[2], auto stage, auto buf) {
-      constexpr int st = decltype(stage)::value, bf = decltype(buf)::value;
-#pragma unroll
-      for (int f = 0; f < 2; ++f)
-#pragma unroll
-        for (int k = 0; k < SKG; ++k) {
-          if (t[f].valid) {
-            wg[bf][k][f] = ld8_stream(t[f].w0 + (st * SKG + k) * kstep);
-            wu[bf][k][f] = ld8_stream(t[f].w1 + (st * SKG + k) * kstep);
-          } else {
-            wg[bf][k][f] = zero8();
-            wu[bf][k][f] = zero8();
-          }
-        }
-    };
-    f32x4 accg[2][2], accu[2][2];
-    auto clear = [&]() {
-#pragma unroll
-      for (int f = 0; f < 2; ++f)
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          accg[f][i] = f32x4{0.f, 0.f, 0.f, 0.f};
-          accu[f][i] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-    };
-    clear();
-    int pb = 0;
-    ShortTile cur[2], nxt[2];
-    if (gu0 < gu1) {
-      cur[0] = tile_at(gu0);
-      cur[1] = tile_at(gu0 + 1);
-      issue(cur, S0{}, S0{});
-    }
-    for (int p = gu0; p < gu1; p += 2) {
-      const bool more = p + 2 < gu1;
-      if (more) {
-        nxt[0] = tile_at(p + 2);
-        nxt[1] = tile_at(p + 3);
-      }
-      static_for(std::make_integer_sequence<int, NSG>{}, [&](auto sc) {
-        constexpr int st = decltype(sc)::value;
-        typedef std::integral_constant<int, st % 2> Cur;
-        typedef std::integral_constant<int, (st + 1) % 2> Nxt;
-        if constexpr (st + 1 < NSG) {
-          issue(cur, std::integral_constant<int, st + 1>{}, Nxt{});
-        } else {
-          if (more) issue(nxt, S0{}, Nxt{});  // NSG is even: the next chunk starts in buffer 0
-        }
-#pragma unroll
-        for (int k = 0; k < SKG; ++k)
-#pragma unroll
-          for (int f = 0; f < 2; ++f)
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-              accg[f][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wg[Cur::value][k][f], xs[st * SKG + k][i],
-                                                                   accg[f][i], 0, 0, 0);
-              accu[f][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wu[Cur::value][k][f], xs[st * SKG + k][i],
-                                                                   accu[f][i], 0, 0, 0);
-            }
-      });
-      // the four quarters meet: accumulator (f, i, gate|up) of wavefront q at part[pb][q][..]
-#pragma unroll
-      for (int f = 0; f < 2; ++f)
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          part[pb][q][(f * 2 + i) * 2 + 0][lane] = accg[f][i];
-          part[pb][q][(f * 2 + i) * 2 + 1][lane] = accu[f][i];
-        }
-      clear();
-      __syncthreads();
-      {  // wavefront q finishes row tile f = q / 2, token tile i = q % 2
-        const int f = q >> 1, i = q & 1;
-        // (selected field by field: indexing the pair with f would put it in scratch memory)
-        const bool t_valid = f ? cur[1].valid : cur[0].valid;
-        const uint32_t t_mask = f ? cur[1].mask : cur[0].mask;
-        const int t_row0 = f ? cur[1].row0 : cur[0].row0;
-        const int t_col0 = f ? cur[1].col0 : cur[0].col0;
-        f32x4 g = part[pb][0][(f * 2 + i) * 2 + 0][lane];
-        f32x4 u = part[pb][0][(f * 2 + i) * 2 + 1][lane];
-#pragma unroll
-        for (int w = 1; w < 4; ++w) {  // fixed order
-          g += part[pb][w][(f * 2 + i) * 2 + 0][lane];
-          u += part[pb][w][(f * 2 + i) * 2 + 1][lane];
-        }
-        const int tok = i * 16 + lrow;
-        if (t_valid && tok < T && ((t_mask >> tok) & 1u)) {
-          const int row = t_row0 + __popc(t_mask & ((1u << tok) - 1u));
-          u16x4 v;
-#pragma unroll
-          for (int c = 0; c < 4; ++c) v[c] = f32_to_bf16_bits(silu_f(g[c]) * u[c]);
-          uint16_t* dst = static_cast<uint16_t*>(a.h) + static_cast<size_t>(row) * F + t_col0 + 4 * lkg;
-          __hip_atomic_store(reinterpret_cast<unsigned long long*>(dst),
-                             __builtin_bit_cast(unsigned long long, v), __ATOMIC_RELAXED,
-                             __HIP_MEMORY_SCOPE_AGENT);
-        }
-      }
-      pb ^= 1;
-      if (more) {
-        cur[0] = nxt[0];
-        cur[1] = nxt[1];
-      }
-    }
-  }
-  DES_FSTAMP(b * 2, 1);
-
-  // ------------------------------------------------------------------- down
-  const int lane_off_d = packed ? lane * 8 : lrow * F + lkg * 8;
-  const int kstep_d = packed ? 512 : 32;
-  struct DownChunk {
-    const uint16_t* w;  // first tile of the chunk, this wavefront's quarter, lane offset included
-    int slot, cnt;      // tiles in the chunk (1..2), all of one expert
-    int row0, count, col0;
-    bool valid;
-  };
-  auto chunk_at = [&](int t) {
-    DownChunk c;
-    const int slot = min(t / dpe, n_live);
-    const int dt = t - slot * dpe;
-    const int4 r = s_rec[slot];
-    c.slot = slot;
-    c.cnt = min(RT, min(dn1 - t, dpe - dt));
-    c.valid = r.x >= 0;
-    const size_t mat = static_cast<size_t>(F) * D;
-    const uint16_t* w = slot < n_live ? static_cast<const uint16_t*>(a.wd) + (r.x < 0 ? 0 : r.x) * mat
-                                      : static_cast<const uint16_t*>(a.sd);
-    c.w = w + static_cast<size_t>(dt) * 16 * F + static_cast<size_t>(q) * FQ * kstep_d + lane_off_d;
-    c.row0 = r.y;
-    c.count = r.z;
-    c.col0 = dt * 16;
-    return c;
-  };
-  bf16x8 wd[2][FQ][RT], hb[2][FQ][2];
-  auto issue_w = [&](const DownChunk& c, auto buf) {
-    constexpr int bf = decltype(buf)::value;
-#pragma unroll
-    for (int r = 0; r < RT; ++r)
-#pragma unroll
-      for (int k = 0; k < FQ; ++k)
-        wd[bf][k][r] = (c.valid && r < c.cnt) ? ld8_stream(c.w + static_cast<size_t>(r) * 16 * F + k * kstep_d)
-                                              : zero8();
-  };
-  auto issue_h = [&](const DownChunk& c, auto buf) {
-    constexpr int bf = decltype(buf)::value;
-    const uint16_t* h = static_cast<const uint16_t*>(a.h);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int pi = min(i * 16 + lrow, c.count - 1);
-      const uint16_t* hp = h + static_cast<size_t>(c.row0 + pi) * F + static_cast<size_t>(q) * FQ * 32 + lkg * 8;
-#pragma unroll
-      for (int k = 0; k < FQ; ++k) {
-        if (c.valid) {
-          struct { unsigned long long lo, hi; } v;
-          v.lo = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(hp + k * 32), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-          v.hi = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(hp + k * 32 + 4), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-          hb[bf][k][i] = __builtin_bit_cast(bf16x8, v);
-        } else {
-          hb[bf][k][i] = zero8();
-        }
-      }
-    }
-  };
-  auto copy_h = [&](auto from, auto to) {
-#pragma unroll
-    for (int k = 0; k < FQ; ++k)
-#pragma unroll
-      for (int i = 0; i < 2; ++i) hb[decltype(to)::value][k][i] = hb[decltype(from)::value][k][i];
-  };
-  int pb = 0;
-  auto run_chunk = [&](const DownChunk& c, auto buf) {
-    constexpr int bf = decltype(buf)::value;
-    f32x4 acc[RT][2];
-#pragma unroll
-    for (int r = 0; r < RT; ++r)
-#pragma unroll
-      for (int i = 0; i < 2; ++i) acc[r][i] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int k = 0; k < FQ; ++k)
-#pragma unroll
-      for (int r = 0; r < RT; ++r)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-          acc[r][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[bf][k][r], hb[bf][k][i], acc[r][i], 0, 0, 0);
-#pragma unroll
-    for (int r = 0; r < RT; ++r)
-#pragma unroll
-      for (int i = 0; i < 2; ++i) part[pb][q][r * 2 + i][lane] = acc[r][i];
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < RT / 2; ++j) {  // wavefront q finishes (row tile, token tile) items q, q + 4
-      const int item = q + 4 * j;
-      const int r = item >> 1, i = item & 1;
-      f32x4 o = part[pb][0][item][lane];
-#pragma unroll
-      for (int w = 1; w < 4; ++w) o += part[pb][w][item][lane];  // fixed order
-      const int pi = i * 16 + lrow;
-      if (c.valid && r < c.cnt && pi < c.count) {
-        float* dst = a.o + static_cast<size_t>(c.row0 + pi) * D + c.col0 + r * 16 + 4 * lkg;
-        *reinterpret_cast<f32x4*>(dst) = o;
-      }
-    }
-    pb ^= 1;
-  };
-
-  // The H rows of this workgroup's gate/up tiles have been stored: raise their flags.
-  // (every wavefront waits for its own stores, then the workgroup meets)
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  for (int p = gu0 + tid; p < gu1; p += 256)
-    __hip_atomic_store(a.h_flags + p, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  DES_FSTAMP(b * 2, 2);
-  if (dn0 >= dn1) return;
-
-  DownChunk c0 = chunk_at(dn0), c1 = c0;
-  issue_w(c0, S0{});  // the weights do not depend on H: in flight while the flags are awaited
-  {
-    // flags of every gate/up tile of the experts this workgroup multiplies by
-    const int s_lo = min(dn0 / dpe, n_live), s_hi = min((dn1 - 1) / dpe, n_live);
-    const int f_lo = s_lo * tpe, f_hi = min((s_hi + 1) * tpe, n_gu);
-    bool ok = true;
-    for (int p = f_lo + tid; p < f_hi; p += 256) {
-      int it = 0;
-      while (__hip_atomic_load(a.h_flags + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch) {
-        __builtin_amdgcn_s_sleep(2);
-        if (++it > a.max_wait) { ok = false; break; }
-      }
-    }
-    if (!__syncthreads_and(ok ? 1 : 0)) {  // gave up: H is not read, O stays unwritten
-      if (tid == 0) a.n_unique[0] = -1;
-      return;
-    }
-  }
-  DES_FSTAMP(b * 2, 3);
-  issue_h(c0, S0{});
-  int t = dn0;
-  while (true) {
-    int tn = t + c0.cnt;
-    bool more = tn < dn1;
-    if (more) {
-      c1 = chunk_at(tn);
-      issue_w(c1, S1{});
-      if (c1.slot != c0.slot) issue_h(c1, S1{});
-      else copy_h(S0{}, S1{});
-    }
-    run_chunk(c0, S0{});
-    if (!more) break;
-    t = tn;
-    tn = t + c1.cnt;
-    more = tn < dn1;
-    if (more) {
-      c0 = chunk_at(tn);
-      issue_w(c0, S0{});
-      if (c0.slot != c1.slot) issue_h(c0, S0{});
-      else copy_h(S1{}, S0{});
-    }
-    run_chunk(c1, S1{});
-    if (!more) break;
-    t = tn;
-  }
-  DES_FSTAMP(b * 2 + 1, 0);
-#ifdef DES_FFN_STAMPS
-  if (tid == 0)
-    g_ffn_stamps[(b * 2 + 1) * 4 + 1] = (static_cast<long long>(__builtin_amdgcn_s_getreg(20 | (31 << 11))) << 32) |
-                                        static_cast<unsigned>(__builtin_amdgcn_s_getreg(4 | (31 << 11)));
-#endif
-}
-
 // acc0/acc1 += A0/A1 (this wavefront's two 16-row weight tiles, reduction
 // length kd) x token rows.  KC = reduction elements per chunk (128 or 64), KD =
 // the reduction length if known at compile time (then kd == KD), else 0; kd is a
@@ -1414,11 +1022,6 @@ template <bool BF16>
 __global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
   const int t = blockIdx.x;
   const int d = (blockIdx.y * 256 + threadIdx.x) * 4;
-  // The flags of the short-block FFN launch have served this call: clear them, so that
-  // a replay of a captured launch (same flag value) cannot be satisfied by stale ones.
-  for (int i = (blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x; i < a.n_h_flags;
-       i += gridDim.x * gridDim.y * 256)
-    a.h_flags[i] = 0ull;
   if (d >= a.D) return;
   const int K = a.K;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -1532,19 +1135,6 @@ int launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st)
   return e == hipSuccess ? DES_OK : hip_fail(e, "read probe launch");
 }
 
-// Workgroups of the persistent short-block launch (one per compute unit), or 0 if the
-// shape is not one it is built for.
-int short_ffn_grid(const des_shape_t& s) {
-  if (s.dtype != DES_BF16 || s.n_seqs * s.n_tokens > 32) return 0;
-  if (s.ffn_shared != 0 && s.ffn_shared != s.ffn) return 0;
-  if (max_live_experts(s) > kShortMaxSlots) return 0;
-  const bool shape_ok = (s.hidden == 2048 && (s.ffn == 768 || s.ffn == 512)) ||
-                        (s.hidden == 256 && (s.ffn == 256 || s.ffn == 128));
-  if (!shape_ok) return 0;
-  const int cus = device_compute_units();
-  return cus < 1 ? 0 : (cus > 1024 ? 1024 : cus);
-}
-
 // ------------------------------------------------------------------ launcher
 int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const void* w_up,
                const void* w_down, const void* ws_gate, const void* ws_up, const void* ws_down,
@@ -1571,12 +1161,6 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
   a.n_slots = max_live_experts(s);
   a.residual = s.residual;
   a.splits = 1;
-  a.h_flags = reinterpret_cast<unsigned long long*>(ws + w.h_flags);
-  a.epoch = epoch;
-  a.max_wait = g_test_max_wait > 0 ? g_test_max_wait : kFfnMaxWaitIters;
-  a.n_unique = n_unique;
-  a.packed = s.weight_layout == DES_LAYOUT_PACKED;
-  a.n_h_flags = 0;
   const int TK = a.T * a.K;
 
   if (s.dtype == DES_BF16) {
@@ -1618,22 +1202,7 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
     else DES_LAUNCH_FFN(16, PK);                                                            \
   } while (0)
     const bool chunked = a.D % kKC == 0 && a.F % kKC == 0 && a.Fs % kKC == 0;
-    // Short blocks in the shapes it is instantiated for: the persistent launch.
-    const int short_grid = short_ffn_grid(s);
-    bool short_done = false;
-    if (short_grid > 0) {
-      const dim3 sg(short_grid), sb(256);
-      short_done = true;
-      if (a.D == 2048 && a.F == 768) launch(kKFfn, ffn_short_kernel<16, 6>, sg, sb, 0, st, a);
-      else if (a.D == 2048 && a.F == 512) launch(kKFfn, ffn_short_kernel<16, 4>, sg, sb, 0, st, a);
-      else if (a.D == 256 && a.F == 256) launch(kKFfn, ffn_short_kernel<2, 2>, sg, sb, 0, st, a);
-      else if (a.D == 256 && a.F == 128) launch(kKFfn, ffn_short_kernel<2, 1>, sg, sb, 0, st, a);
-      else short_done = false;
-      if (short_done) a.n_h_flags = (a.n_slots + 1) * (a.F / 16);
-    }
-    if (short_done) {
-      // gate/up and down are done; the combine follows below
-    } else if (a.T > 32 && chunked) {
+    if (a.T > 32 && chunked) {
       // Larger blocks: activations staged through LDS.  Token rows per workgroup
       // pass: 64 while no expert can have more, else 128; an expert with more
       // pairs is spread over up to kMaxSplits workgroups (the unit list).  Wavefronts per workgroup:

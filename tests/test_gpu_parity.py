@@ -141,11 +141,9 @@ MID = dict(
     mid_f32=W.LayerConfig("mid_f32", "f32", 2, 9, 72, 24, 20, 12, 3, 6, 1.1, 12),
     wide_tok=W.LayerConfig("wide_tok", "bf16", 1, 150, 128, 12, 64, 0, 4, 3, 0.0, 13),
     many_tok=W.LayerConfig("many_tok", "bf16", 3, 100, 64, 8, 32, 32, 2, 2, 0.0, 14),
-    # blocks of at most 32 tokens in the shapes of the persistent short-block launch (one
-    # workgroup per compute unit, reduction split over its four wavefronts): a shared
-    # expert with F = 128 (one k-step per wavefront); two sequences, F = 256; 300 experts
-    # for 5 tokens (most workgroups get one tile or none, ragged tile pairs); exactly 32
-    # tokens (a full token bitmap) with few experts (several tiles of one expert per workgroup)
+    # blocks of at most 32 tokens with D = 256: a shared expert with F = 128; two
+    # sequences, F = 256; 300 experts for 5 tokens (most experts idle, one pair each);
+    # exactly 32 tokens (a full token bitmap per expert) on few experts (two token tiles)
     short_a=W.LayerConfig("short_a", "bf16", 1, 20, 256, 40, 128, 128, 4, 10, 1.1, 25),
     short_b=W.LayerConfig("short_b", "bf16", 2, 13, 256, 24, 256, 0, 3, 6, 0.5, 26),
     short_c=W.LayerConfig("short_c", "bf16", 1, 5, 256, 300, 128, 0, 8, 40, 0.3, 27),
@@ -425,8 +423,8 @@ def test_graph_replay_matches_eager(name):
     the eager result every time (the routing flags are cleared by their consumer,
     so a replay with the captured epoch cannot be satisfied by stale flags).
     mid_bf16: two selector workgroups and a permutation workgroup; sel_groups: six
-    selectors that also exchange their election partials; short_a: the persistent
-    short-block launch, whose workgroups wait for each other's flags."""
+    selectors that also exchange their election partials; short_a: a block of 20 tokens
+    (selection and permutation in one workgroup, one-task-per-wavefront FFN kernels)."""
     cfg = MID[name]
     layer = W.make_layer(cfg)
     dev = H.layer_to_device(layer)
