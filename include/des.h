@@ -224,6 +224,30 @@ int des_moe_forward(const des_shape_t* shape, const void* x, const void* w_route
                     size_t workspace_bytes, void* hip_stream);
 
 /*
+ * des_moe_forward for callers that cannot allocate device memory or have none to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and errors as des_moe_forward,
+ * except that the scratch is a buffer built into the library (one copy of
+ * DES_BUILTIN_WORKSPACE_BYTES per GPU, held until the process ends) instead of
+ * the caller's workspace.  The call allocates and frees nothing.  A shape whose
+ * des_workspace_bytes() exceeds DES_BUILTIN_WORKSPACE_BYTES is refused with
+ * DES_ERR_WORKSPACE before anything is launched (the 128- and 256-expert
+ * single-layer benchmark shapes need about 3 MiB).  All calls on one GPU share
+ * that GPU's buffer: calls that overlap in time (different streams or threads,
+ * or an overlapping des_moe_forward that was handed the same memory) race.
+ * Nothing in the buffer has to survive between calls and nothing has to be
+ * cleared.  The first call on a device looks the buffer's address up
+ * (hipGetSymbolAddress); make that call outside graph capture.
+ */
+#define DES_BUILTIN_WORKSPACE_BYTES (8u << 20)
+int des_moe_forward_builtin_ws(const des_shape_t* shape, const void* x, const void* w_router,
+                               const float* router_bias, const void* w_gate, const void* w_up,
+                               const void* w_down, const void* ws_gate, const void* ws_up,
+                               const void* ws_down, void* y, float* logits, int32_t* topk_idx,
+                               float* topk_w, int32_t* expert_counts, int32_t* n_unique,
+                               int32_t* coreset_idx, int32_t* coreset_size, void* hip_stream);
+
+/*
  * A residual stack of n_layers such layers, x_{l+1} = x_l + MoE_l(x_l)
  * (shape->residual is taken as 1).  Layer l's tensors start at
  * base + l * stride elements: w_router [L][M][D], router_bias [L][M] (or NULL),

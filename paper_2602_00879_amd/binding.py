@@ -22,7 +22,7 @@ MODES = {"vanilla": DES_VANILLA, "seq": DES_SEQ, "vote": DES_VOTE}
 
 EXPORTS = (
     "des_coreset_capacity", "des_workspace_bytes", "des_route", "des_select_coreset",
-    "des_moe_forward", "des_stack_workspace_bytes", "des_moe_stack_forward",
+    "des_moe_forward", "des_moe_forward_builtin_ws", "des_stack_workspace_bytes", "des_moe_stack_forward",
     "des_pack_expert_weights", "des_strerror", "des_last_hip_error",
     "des_kernel_timing_enable", "des_kernel_timing_count", "des_kernel_timing_name",
     "des_kernel_timing_read", "des_hbm_read_probe", "des_coreset_from_beta", "des_test_hooks",
@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
         L.des_select_coreset.argtypes = [sp] + [vp] * 6
         L.des_moe_forward.restype = ctypes.c_int
         L.des_moe_forward.argtypes = [sp] + [vp] * 18 + [sz, vp]
+        L.des_moe_forward_builtin_ws.restype = ctypes.c_int
+        L.des_moe_forward_builtin_ws.argtypes = [sp] + [vp] * 18
         L.des_moe_stack_forward.restype = ctypes.c_int
         L.des_moe_stack_forward.argtypes = [sp, i32] + [vp] * 13 + [sz, vp]
         L.des_pack_expert_weights.restype = ctypes.c_int
@@ -185,10 +187,14 @@ def des_select_coreset(shape: DesShape, logits: torch.Tensor,
     return out
 
 
-class MoeBuffers:
-    """Outputs and workspace of des_moe_forward, allocated once per shape."""
+BUILTIN_WORKSPACE_BYTES = 8 << 20   # DES_BUILTIN_WORKSPACE_BYTES of des.h
 
-    def __init__(self, shape: DesShape, device, out_dtype: torch.dtype):
+
+class MoeBuffers:
+    """Outputs and workspace of des_moe_forward, allocated once per shape.
+    with_workspace=False: outputs only (des_moe_forward_builtin_ws)."""
+
+    def __init__(self, shape: DesShape, device, out_dtype: torch.dtype, with_workspace: bool = True):
         B, N, D, M, K = shape.n_seqs, shape.n_tokens, shape.hidden, shape.n_experts, shape.top_k
         cap = des_coreset_capacity(shape)
         nbytes = des_workspace_bytes(shape)
@@ -203,7 +209,23 @@ class MoeBuffers:
         self.n_unique = torch.empty((1,), dtype=i32, device=device)
         self.coreset_idx = torch.empty((B, cap), dtype=i32, device=device)
         self.coreset_size = torch.empty((B,), dtype=i32, device=device)
-        self.workspace = torch.empty((nbytes,), dtype=torch.uint8, device=device)
+        self.workspace = (torch.empty((nbytes,), dtype=torch.uint8, device=device)
+                          if with_workspace else None)
+
+
+def des_moe_forward_builtin_ws(shape: DesShape, x, w_router, router_bias, w_gate, w_up, w_down,
+                               shared: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]] = None,
+                               buffers: Optional[MoeBuffers] = None) -> MoeBuffers:
+    """des_moe_forward with the library's built-in scratch: the call itself allocates
+    nothing when `buffers` (the outputs) is given."""
+    b = buffers if buffers is not None else MoeBuffers(shape, x.device, x.dtype, with_workspace=False)
+    sg, su, sd = shared if shared is not None else (None, None, None)
+    _check(lib().des_moe_forward_builtin_ws(
+        ctypes.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(w_gate), _ptr(w_up),
+        _ptr(w_down), _ptr(sg), _ptr(su), _ptr(sd), _ptr(b.y), _ptr(b.logits), _ptr(b.topk_idx),
+        _ptr(b.topk_w), _ptr(b.expert_counts), _ptr(b.n_unique), _ptr(b.coreset_idx),
+        _ptr(b.coreset_size), _stream()))
+    return b
 
 
 def des_moe_forward(shape: DesShape, x, w_router, router_bias, w_gate, w_up, w_down,

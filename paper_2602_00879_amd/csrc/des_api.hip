@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <atomic>
+#include <mutex>
 #include <vector>
 
 #include <math.h>
@@ -108,6 +109,36 @@ static int check_shape(const des_shape_t* s, bool need_ffn) {
 
 }  // namespace des
 
+// ---- scratch built into the library (des_moe_forward_builtin_ws) ----
+// One copy per GPU the library runs on, held until the process ends.  In host
+// code the array's name is only a stand-in for the symbol: the address a kernel
+// can use comes from hipGetSymbolAddress(), per device.
+static __device__ __align__(256) unsigned char scratch[DES_BUILTIN_WORKSPACE_BYTES];
+
+namespace des {
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device
+static std::mutex g_scratch_mutex;
+
+// Device address of the built-in scratch on the current device (looked up once
+// per device); DES_ERR_HIP if the runtime refuses.
+static int builtin_scratch(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice, "device ordinal");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return DES_OK;
+}
+}  // namespace des
+
 using namespace des;
 
 extern "C" {
@@ -169,6 +200,23 @@ int des_moe_forward(const des_shape_t* s, const void* x, const void* w_router,
   if (rc != DES_OK) return rc;
   return launch_ffn(*s, x, w_gate, w_up, w_down, ws_gate, ws_up, ws_down, topk_idx, topk_w,
                     n_unique, y, ws, epoch, st);
+}
+
+int des_moe_forward_builtin_ws(const des_shape_t* s, const void* x, const void* w_router,
+                               const float* router_bias, const void* w_gate, const void* w_up,
+                               const void* w_down, const void* ws_gate, const void* ws_up,
+                               const void* ws_down, void* y, float* logits, int32_t* topk_idx,
+                               float* topk_w, int32_t* expert_counts, int32_t* n_unique,
+                               int32_t* coreset_idx, int32_t* coreset_size, void* hip_stream) {
+  const int rc = check_shape(s, true);
+  if (rc != DES_OK) return rc;
+  if (ws_layout(*s).total > DES_BUILTIN_WORKSPACE_BYTES) return DES_ERR_WORKSPACE;
+  void* ws = nullptr;
+  const int rs = builtin_scratch(&ws);
+  if (rs != DES_OK) return rs;
+  return des_moe_forward(s, x, w_router, router_bias, w_gate, w_up, w_down, ws_gate, ws_up, ws_down,
+                         y, logits, topk_idx, topk_w, expert_counts, n_unique, coreset_idx,
+                         coreset_size, ws, DES_BUILTIN_WORKSPACE_BYTES, hip_stream);
 }
 
 // Stack scratch: two activation ping-pong buffers, per-layer routing outputs
@@ -290,7 +338,9 @@ const char* des_strerror(int code) {
     case DES_ERR_SHAPE: return "shape out of range or not supported";
     case DES_ERR_MODE: return "unknown mode";
     case DES_ERR_DTYPE: return "unsupported dtype or weight layout";
-    case DES_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned";
+    case DES_ERR_WORKSPACE:
+      return "workspace too small or not 256-byte aligned, or the shape needs more scratch than "
+             "the library's built-in buffer holds";
     case DES_ERR_HIP: return "a HIP call failed (see des_last_hip_error)";
     default: return "unknown error code";
   }
