@@ -31,12 +31,21 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 # HBM traffic of the dominant kernel from rocprofv3 counters, in bytes per
-# launch (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size); the
-# summaries are under profiles/.  None until measured for a workload/layout.
+# launch (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size).  It
+# is NOT measured by the run that prints it (counters need a profiler run of
+# their own): each entry names the committed summary it was read from and the
+# commit whose kernels that run profiled, and goes stale when the kernel changes.
 MEASURED_TRAFFIC = {
-    # profiles/hbm_traffic_m128_zipf_vote_c32_packed.txt: 202,574,600 B read + 393,216 B written
-    ("m128_zipf", "vote", "packed"): 202557235 + 393216,
+    ("m128_zipf", "vote", "packed"): {
+        "bytes": 202557235 + 393216,  # 202,557,235 B read + 393,216 B written
+        "profile": "profiles/hbm_traffic_m128_zipf_vote_c32_packed.txt",
+        "kernel_commit": "c6257bd",
+    },
 }
+
+# HBM floors of the benchmark definition: unique expert bytes / 8 TB/s.
+def floor_us(unique_bytes):
+    return unique_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
 
 
 def parse():
@@ -52,6 +61,10 @@ def parse():
     ap.add_argument("--layout", default="packed", choices=["packed", "rowmajor"])
     ap.add_argument("--replicas", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short runs of the other benchmark configurations (256-expert layer "
+                         "with a shared expert, block-length sweep, 48-layer stack) that the default "
+                         "run adds under other_configs")
     ap.add_argument("--graph", action="store_true", help="also time the steps replayed from a HIP graph")
     ap.add_argument("--sweep", action="store_true",
                     help="block-length sweep N = 4..128, vanilla against DES-Vote C=32, and the "
@@ -131,7 +144,9 @@ def main():
         wg, wu, wd = replicas[i % len(replicas)]
         B.des_moe_forward(shape, x, w_router, bias, wg, wu, wd, shared=shared, buffers=bufs)
 
-    for i in range(args.warmup):
+    # warm-up: at least one full rotation, so that every replica's pages have been
+    # touched before the timed region whatever --warmup says
+    for i in range(max(args.warmup, len(replicas))):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -210,7 +225,8 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": "gateup", "achieved": achieved, "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
-        "traffic": MEASURED_TRAFFIC.get((args.workload, args.mode, args.layout)),
+        "traffic": (MEASURED_TRAFFIC.get((args.workload, args.mode, args.layout)) or {}).get("bytes"),
+        "traffic_source": MEASURED_TRAFFIC.get((args.workload, args.mode, args.layout)),
         "algorithmic_bytes_per_launch": gateup_bytes, "avg_launch_us": dom_us,
         "read_ceiling": ceiling,
         "frac_of_read_ceiling": (achieved / ceiling["GB/s"]) if (achieved and ceiling) else None,
@@ -242,9 +258,121 @@ def main():
         "roofline": roofline,
     }
 
+    default_run = (args.workload == "m128_zipf" and args.mode == "vote" and not args.n_tokens
+                   and not args.coreset and not args.k_route and not args.skip_beta and packed)
+    if default_run and not args.no_other_configs:
+        out["other_configs"] = other_configs(args, torch, B, W, dev, cfg, layer, replicas, w_router, bias)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, layer, args.mode, C)
     print(json.dumps(out))
+
+
+def _timed_layer(torch, B, shape, x, w_router, bias, replicas, shared, steps, warm):
+    """us per block of des_moe_forward on `shape`, weights rotated over `replicas`."""
+    bufs = B.MoeBuffers(shape, x.device, x.dtype)
+
+    def step(i):
+        wg, wu, wd = replicas[i % len(replicas)]
+        B.des_moe_forward(shape, x, w_router, bias, wg, wu, wd, shared=shared, buffers=bufs)
+
+    for i in range(max(warm, len(replicas))):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e6 / steps, int(bufs.n_unique.cpu()[0])
+
+
+def other_configs(args, torch, B, W, dev, cfg2, layer2, replicas2, w_router2, bias2):
+    """Short runs of the other benchmark configurations, each with its HBM floor
+    (unique expert bytes / 8 TB/s): the 256-expert layer with a shared expert under
+    DES-Vote and DES-Seq at C = 16 / 32 / 64; the block-length sweep N = 4..128 on the
+    128-expert layer, vanilla against DES-Vote C = 32; the 48-layer stack when enough
+    HBM is free.  Context for the headline line above, same build, same run."""
+    steps, warm = 100, 10
+    res = {}
+
+    def dev_t(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    def row(us, U, per_expert, shared_bytes=0):
+        ub = U * per_expert + shared_bytes
+        return {"us": round(us, 2), "n_unique": U, "floor_us": round(floor_us(ub), 2),
+                "pct_of_hbm_peak_whole_step": round(100.0 * floor_us(ub) / us, 1)}
+
+    # ---- block-length sweep on the 128-expert layer (the benchmark layer's weights)
+    per2 = 3 * cfg2.hidden * cfg2.ffn * 2
+    sweep = []
+    for N in (4, 8, 16, 32, 64, 128):
+        rng = np.random.default_rng([cfg2.seed, N])
+        x = dev_t(W._normal(rng, (1, N, cfg2.hidden), 1.0, cfg2.dtype))
+        for mode in ("vanilla", "vote"):
+            shape = B.make_shape(1, N, cfg2.hidden, cfg2.n_experts, cfg2.ffn, cfg2.top_k, cfg2.coreset, mode,
+                                 cfg2.dtype, weight_layout=B.DES_LAYOUT_PACKED)
+            us, U = _timed_layer(torch, B, shape, x, w_router2, bias2, replicas2, None, steps, warm)
+            sweep.append({"N": N, "mode": mode, **row(us, U, per2)})
+    res["m128_sweep"] = {"workload": "128-expert layer, N = 4..128, vanilla vs DES-Vote C=32", "rows": sweep}
+
+    # ---- 256 experts + shared expert
+    cfg3 = W.CONFIGS["m256_shared"]
+    layer3 = W.make_layer(cfg3)
+    x3, wr3 = dev_t(layer3["x"]), dev_t(layer3["w_router"])
+    base3 = [B.des_pack_expert_weights(dev_t(layer3[k])) for k in ("w_gate", "w_up", "w_down")]
+    shared3 = tuple(B.des_pack_expert_weights(dev_t(m)) for m in layer3["shared"])
+    torch.cuda.synchronize()
+    reps3 = [base3] + [[t.clone() for t in base3] for _ in range(5)]  # 6 x 1.6 GB
+    per3 = 3 * cfg3.hidden * cfg3.ffn * 2
+    sh3 = 3 * cfg3.hidden * cfg3.ffn_shared * 2
+    rows3 = []
+    for mode in ("vote", "seq"):
+        for C in (16, 32, 64):
+            shape = B.make_shape(1, cfg3.n_tokens, cfg3.hidden, cfg3.n_experts, cfg3.ffn, cfg3.top_k, C, mode,
+                                 cfg3.dtype, ffn_shared=cfg3.ffn_shared, weight_layout=B.DES_LAYOUT_PACKED)
+            us, U = _timed_layer(torch, B, shape, x3, wr3, None, reps3, shared3, steps, warm)
+            rows3.append({"mode": mode, "C": C, **row(us, U, per3, sh3)})
+    res["m256_shared"] = {"workload": "256-expert layer + shared expert, N=32, C = 16 / 32 / 64", "rows": rows3}
+    del reps3, base3, shared3, layer3
+    torch.cuda.empty_cache()
+
+    # ---- 48-layer stack: needs ~60 GB for the weights and a transient for packing
+    free, _ = torch.cuda.mem_get_info()
+    if free < 75e9:
+        res["stack48"] = {"skipped": f"only {free / 1e9:.0f} GB of HBM free"}
+        return res
+    from paper_2602_00879_amd import device_workloads as DW
+    cfg5 = W.CONFIGS["stack48"]
+    st = DW.make_stack(cfg5, dev)
+    for k in ("w_gate", "w_up", "w_down"):
+        for l in range(cfg5.n_layers):
+            st[k][l] = B.des_pack_expert_weights(st[k][l])
+    torch.cuda.synchronize()
+    shape = B.make_shape(cfg5.n_seqs, cfg5.n_tokens, cfg5.hidden, cfg5.n_experts, cfg5.ffn, cfg5.top_k,
+                         cfg5.coreset, "vote", cfg5.dtype, weight_layout=B.DES_LAYOUT_PACKED, residual=1)
+    bufs = B.StackBuffers(shape, cfg5.n_layers, dev, torch.bfloat16)
+
+    def sstep():
+        B.des_moe_stack_forward(shape, cfg5.n_layers, st["x"], st["w_router"], st["bias"], st["w_gate"],
+                                st["w_up"], st["w_down"], buffers=bufs)
+
+    for _ in range(2):
+        sstep()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        sstep()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / 10
+    uniq = bufs.n_unique.cpu().numpy()
+    ub = int(uniq.sum()) * per2
+    res["stack48"] = {"workload": "48 layers x 8 sequences x 32 tokens, DES-Vote C=32 per sequence and layer",
+                      "ms_per_step": round(ms, 3), "unique_experts_per_layer_mean": round(float(uniq.mean()), 1),
+                      "floor_ms": round(floor_us(ub) / 1e3, 3),
+                      "pct_of_hbm_peak_whole_step": round(100.0 * floor_us(ub) / (ms * 1e3), 1)}
+    return res
 
 
 def bench_selection(args, torch, B, W, dev):
@@ -545,16 +673,30 @@ def cpu_baseline(cfg, layer, mode, C):
 
     wg, wu, wd = Lazy(layer["w_gate"]), Lazy(layer["w_up"]), Lazy(layer["w_down"])
     shared = tuple(W.to_f64(m) for m in layer["shared"]) if layer["shared"] else None
-    blocks, t0 = 0, time.perf_counter()
-    while True:
-        O.moe_forward(x, wr, bias, wg, wu, wd, cfg.top_k, C, mode, shared=shared)
-        blocks += 1
-        dt = time.perf_counter() - t0
-        if dt >= 12.0 or blocks >= 200:
-            break
+
+    def run(budget_s):
+        blocks, t0 = 0, time.perf_counter()
+        while True:
+            O.moe_forward(x, wr, bias, wg, wu, wd, cfg.top_k, C, mode, shared=shared)
+            blocks += 1
+            dt = time.perf_counter() - t0
+            if dt >= budget_s or blocks >= 200:
+                return blocks, dt
+
+    blocks, dt = run(10.0)
+    single = None
+    try:  # the same oracle held to one thread
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):
+            b1, d1 = run(8.0)
+        single = {"value": d1 / b1 * 1e6, "unit": "us/block", "cores": 1,
+                  "sample": f"{b1} whole blocks in {d1:.1f} s (float64 numpy, one BLAS thread)"}
+    except Exception:  # pragma: no cover
+        pass
     return {"value": dt / blocks * 1e6, "unit": "us/block", "cores": threads, "kind": "oracle",
             "sample": f"{blocks} whole blocks of the same workload in {dt:.1f} s "
                       f"(float64 numpy, BLAS threads = cores)",
+            "single_thread": single,
             "host_cpus": len(os.sched_getaffinity(0))}
 
 

@@ -200,7 +200,7 @@ __device__ __forceinline__ bool make_task(const FfnArgs& a, int slot_or_shared, 
     // the slot record and (for gate/up) this lane's tokens are fetched together:
     // both addresses depend on the slot number only
     const int4 sl = a.slots[slot_or_shared];
-    if (!down) {
+    if (!down && a.T > 32) {
       const uint16_t* st = a.slot_tok + slot_or_shared * kSlotToks + (lane & 15);
       t.pre_tok[0] = st[0];
       t.pre_tok[1] = st[16];
@@ -212,6 +212,18 @@ __device__ __forceinline__ bool make_task(const FfnArgs& a, int slot_or_shared, 
       return false;
     const int e = sl.x;
     const int off = sl.y;
+    if (!down && a.T <= 32) {
+      // at most 32 tokens: the record carries the bitmap of the expert's tokens; its pairs
+      // in order are the set bits in order (positions past the count repeat the last one)
+      const uint32_t m = static_cast<uint32_t>(sl.w);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int want = min(i * 16 + (lane & 15), sl.z - 1);
+        uint32_t mm = m;
+        for (int k = 0; k < want; ++k) mm &= mm - 1u;
+        t.pre_tok[i] = mm ? min(__builtin_ctz(mm), a.T - 1) : 0;
+      }
+    }
     t.slot = slot_or_shared;
     t.count = sl.z;
     t.pair0 = off;

@@ -90,6 +90,8 @@ struct RoutingArgs {
                                  // value there is carried into this layer's n_unique
   int do_router, do_select, do_permute, use_flags, bf16;
   int skip_router_tiles;  // test hook: the fused launch runs without its router tiles
+  int small_perm;         // one selector workgroup, at most 32 tokens, no skipping: the permutation
+                          // is built from per-expert token bitmaps recorded during stage 2
 };
 
 // ------------------------------------------------------------------ flags
@@ -296,7 +298,11 @@ struct SelLds {
   static constexpr int rank = key + 4 * MP;                      // int [MP]
   static constexpr int core = rank + 4 * MP;                     // int [MP]
   static constexpr int hist = core + 4 * MP;                     // int [36]
-  static constexpr int total = hist + 4 * 36;
+  static constexpr int mask = hist + 4 * 36;                     // u32 [MP] tokens routed to an expert (T <= 32)
+  static constexpr int vsum = mask + 4 * MP;                     // float [MP] the votes, all waves added
+  static constexpr int off = vsum + 4 * MP;                      // int [MP + 1] first pair of an expert
+  static constexpr int liv = off + 4 * (MP + 1);                 // int [MP + 1] live experts before it
+  static constexpr int total = liv + 4 * (MP + 1);
 };
 
 // Per-token state of one lane while candidates are drawn best-first.
@@ -349,6 +355,8 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
   int* s_rank = reinterpret_cast<int*>(smem + L::rank);
   int* s_core = reinterpret_cast<int*>(smem + L::core);
   int* s_hist = reinterpret_cast<int*>(smem + L::hist);  // [0..32] histogram, [33] k used, [34] size
+  uint32_t* s_mask = reinterpret_cast<uint32_t*>(smem + L::mask);
+  float* s_vsum = reinterpret_cast<float*>(smem + L::vsum);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane / LPT, rl = lane % LPT;
@@ -366,6 +374,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
     s_key[e] = 0u;
     s_core[e] = (a.mode == DES_VANILLA && e < M) ? 1 : 0;
     s_vpart[e] = 0.f;  // the accumulator of the atomic vote variant
+    s_mask[e] = 0u;
   }
   if (threadIdx.x < 36) s_hist[threadIdx.x] = 0;
   // the LDS set-up above does not need the logits: only now wait for the router
@@ -519,20 +528,19 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
     __syncthreads();
     DES_STAMP(a, 11);
 
-    if (vote && !(EXT && a.vote_atomic)) {  // this workgroup's votes: waves in order
-      float vloc[(MP + kRtThreads - 1) / kRtThreads];
-      int q = 0;
-      for (int e = threadIdx.x; e < MP; e += kRtThreads, ++q) {
-        float v = 0.f;
+    // this workgroup's votes: waves in order (into an array of their own, so that no
+    // barrier is needed between reading the partials and writing the sums)
+    for (int e = threadIdx.x; e < MP; e += kRtThreads) {
+      float v = 0.f;
+      if (vote && !(EXT && a.vote_atomic)) {
 #pragma unroll
         for (int w = 0; w < kRtWaves; ++w) v += s_vpart[w * MP + e];
-        vloc[q] = v;
+      } else if (vote) {
+        v = s_vpart[e];
       }
-      __syncthreads();
-      q = 0;
-      for (int e = threadIdx.x; e < MP; e += kRtThreads, ++q) s_vpart[e] = vloc[q];
-      __syncthreads();
+      s_vsum[e] = v;
     }
+    if (G > 1) __syncthreads();
     if (G > 1) {
       // The sequence's tokens are spread over G workgroups: each publishes what
       // its tokens contributed (votes, best nomination rank, top-1 nominations),
@@ -541,7 +549,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
       // The records travel with device-scope accesses, like the logits.
       uint32_t* mine = a.sel_part + static_cast<size_t>(b * G + g) * 3 * kSelPartStride;
       for (int e = threadIdx.x; e < MP; e += kRtThreads) {
-        __hip_atomic_store(mine + e, __float_as_uint(vote ? s_vpart[e] : 0.f), __ATOMIC_RELAXED,
+        __hip_atomic_store(mine + e, __float_as_uint(vote ? s_vsum[e] : 0.f), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(mine + kSelPartStride + e, static_cast<uint32_t>(s_level[e]),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -564,16 +572,17 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
           c1 += static_cast<int>(__hip_atomic_load(rec + 2 * kSelPartStride + e, __ATOMIC_RELAXED,
                                                    __HIP_MEMORY_SCOPE_AGENT));
         }
-        s_vpart[e] = v;
+        s_vsum[e] = v;
         s_level[e] = lvl;
         s_cnt1[e] = c1;
       }
       __syncthreads();
     }
 
+    // (without an exchange every thread reads back only the s_vsum entry it wrote itself)
     if (vote) {
       for (int e = threadIdx.x; e < MP; e += kRtThreads) {
-        const float v = s_vpart[e];
+        const float v = s_vsum[e];
         const bool nominated = e < M && s_level[e] < K;
         s_key[e] = nominated ? order_key(v) : 0u;
         if (a.votes && e < M && !dry && g == 0) a.votes[static_cast<size_t>(b) * M + e] = v;
@@ -630,22 +639,22 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
         }
         if (rank) atomicAdd(&s_rank[e], rank);
       }
-      __syncthreads();
-      DES_STAMP(a, 13);
-      for (int e = threadIdx.x; e < MP; e += kRtThreads)
-        s_core[e] = (s_key[e] != 0u && s_rank[e] < a.C) ? 1 : 0;
     }
     __syncthreads();
   }
 
   DES_STAMP(a, 3);
   // ------------------------------------- coreset as an ascending index list
+  // (where the election ranked keys, membership = "rank below C": the first wavefront
+  // derives it here and records it for stage 2, which saves a pass and a barrier)
+  const bool from_rank = a.mode != DES_VANILLA && (a.mode == DES_VOTE || s_hist[33] == 0);
   if (wave == 0) {
     int base = 0;
     int32_t* out = a.coreset_idx + static_cast<size_t>(b) * a.cap;
     for (int c = 0; c < MP; c += 64) {
       const int e = c + lane;
-      const bool f = e < MP && s_core[e] != 0;
+      const bool f = e < MP && (from_rank ? (s_key[e] != 0u && s_rank[e] < a.C) : (s_core[e] != 0));
+      if (from_rank && e < MP) s_core[e] = f ? 1 : 0;
       const unsigned long long bal = __ballot(f);
       const int pre = __popcll(bal & ((1ull << lane) - 1ull));
       if (f && base + pre < a.cap && !dry && g == 0) out[base + pre] = e;
@@ -708,7 +717,13 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
       for (int q = 0; q < NW; ++q)
         if (it == q * LPT + rl) mkey[q] = m;
       if (mine) {
-        if (live) put_idx(a.topk_idx + o + it, rl * kEpl + static_cast<int>((sidx >> (3 * hd.h)) & 7u));
+        const int e = rl * kEpl + static_cast<int>((sidx >> (3 * hd.h)) & 7u);
+        if (live) {
+          put_idx(a.topk_idx + o + it, e);
+          // (a block of at most 32 tokens in one workgroup: the expert's token bitmap is
+          // all the permutation needs; integer LDS atomics, independent of arrival order)
+          if (a.small_perm) atomicOr(&s_mask[e], 1u << n);
+        }
         head_set(hd, hd.mask & (hd.mask - 1u), my_sorted);
       }
     }
@@ -893,7 +908,9 @@ __device__ void permute_all(const RoutingArgs& a, char* smem, bool idx_dev) {
   for (int s = n_live + tid; s < a.n_slots; s += kRtThreads) a.slots[s] = make_int4(-1, 0, 0, 0);
   // entries of the slot-major token table past a slot's count must still name a
   // valid token: clear the table, then (after the barrier) fill it
-  for (int i = tid; i < a.n_slots * kSlotToks; i += kRtThreads) a.slot_tok[i] = 0;
+  // (up to 32 tokens the FFN kernels take an expert's tokens from the bitmap in its record)
+  if (T > 32)
+    for (int i = tid; i < a.n_slots * kSlotToks; i += kRtThreads) a.slot_tok[i] = 0;
   __syncthreads();
   auto place = [&](int p, int e) {
     if (e < 0) { a.pos[p] = -1; return; }
@@ -906,7 +923,7 @@ __device__ void permute_all(const RoutingArgs& a, char* smem, bool idx_dev) {
     a.pos[p] = r;
     const int within = r - s_off[e];
     const int sl = by_count ? s_slot[e] : s_liv[e];
-    if (within < kSlotToks && sl < a.n_slots)
+    if (T > 32 && within < kSlotToks && sl < a.n_slots)
       a.slot_tok[sl * kSlotToks + within] = static_cast<uint16_t>(t);
   };
 #pragma unroll
@@ -937,6 +954,74 @@ __device__ void publish_empty(const RoutingArgs& a, int n_flags) {
   if (a.use_flags)
     for (int i = tid; i < n_flags; i += kRtThreads) a.flags[i] = 0ull;
   if (tid == 0 && a.n_unique) a.n_unique[0] = -1;
+}
+
+// The same outputs as permute_all for a block of at most 32 tokens whose selection
+// ran in this workgroup: stage 2 has left, per expert, the bitmap of the tokens routed
+// to it (s_mask), so counts are popcounts, an expert's pairs in token order are its set
+// bits in order, and a pair's sorted position is a popcount below its token's bit.  No
+// second pass over the indices to build bitmaps, no token table (the FFN kernels take
+// the bitmap from the slot record).
+template <int LPT>
+__device__ void permute_small(const RoutingArgs& a, char* smem) {
+  using L = SelLds<LPT>;
+  constexpr int MP = L::MP;
+  const uint32_t* s_mask = reinterpret_cast<const uint32_t*>(smem + L::mask);
+  int* s_off = reinterpret_cast<int*>(smem + L::off);
+  int* s_liv = reinterpret_cast<int*>(smem + L::liv);
+  const int tid = threadIdx.x, M = a.M, K = a.K, TK = a.B * a.N * a.K;
+  if (tid < 64) {  // exclusive scans of counts and of (count > 0), 64 experts at a time
+    int base_c = 0, base_l = 0;
+    for (int c0 = 0; c0 < M; c0 += 64) {
+      const int e = c0 + tid;
+      const int c = e < M ? __popc(s_mask[e]) : 0;
+      int inc = c;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(inc, d);
+        if (tid >= d) inc += o;
+      }
+      const unsigned long long bal = __ballot(c > 0);
+      const int lpre = __popcll(bal & ((1ull << tid) - 1ull));
+      if (e < M) {
+        s_off[e] = base_c + inc - c;
+        s_liv[e] = base_l + lpre;
+      }
+      base_c += __shfl(inc, 63);
+      base_l += __popcll(bal);
+    }
+    if (tid == 0) {
+      s_off[M] = base_c;
+      s_liv[M] = base_l;
+      a.meta[0] = base_l;
+      a.meta[1] = base_c;
+      a.meta[2] = 0;
+      a.n_unique[0] = (a.prev_n_unique != nullptr && a.prev_n_unique[0] < 0) ? -1 : base_l;
+    }
+  }
+  __syncthreads();
+  const int n_live = s_liv[M];
+  for (int e = tid; e <= M; e += kRtThreads) a.offsets[e] = s_off[e];
+  for (int e = tid; e < M; e += kRtThreads) {
+    const uint32_t m = s_mask[e];
+    const int c = __popc(m), sl = s_liv[e];
+    const bool live = c > 0 && sl < a.n_slots;
+    a.expert_counts[e] = c;
+    if (live) a.slots[sl] = make_int4(e, s_off[e], c, static_cast<int>(m));
+    a.slot_of[e] = live ? sl : -1;
+  }
+  for (int s = n_live + tid; s < a.n_slots; s += kRtThreads) a.slots[s] = make_int4(-1, 0, 0, 0);
+  for (int p = tid; p < TK; p += kRtThreads) {
+    const int e = a.topk_idx[p];  // (stored by this workgroup before the barrier above)
+    if (e < 0) {
+      a.pos[p] = -1;
+      continue;
+    }
+    const int t = p / K;
+    const int r = s_off[e] + __popc(s_mask[e] & ((1u << t) - 1u));
+    a.pair_tok[r] = t;
+    a.pos[p] = r;
+  }
 }
 
 // ---------------------------------------------------------------- the kernel
@@ -982,7 +1067,8 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
       // stores before the loads below, no device-scope fence needed
       __syncthreads();
       DES_STAMP(a, 6);
-      permute_all<SelLds<LPT>::MP>(a, smem, false);
+      if (a.small_perm) permute_small<LPT>(a, smem);
+      else permute_all<SelLds<LPT>::MP>(a, smem, false);
       DES_STAMP(a, 7);
       // every flag of this call has been consumed: clear them, so that a replay
       // of a captured launch (same epoch) cannot be satisfied by stale flags
@@ -1153,8 +1239,13 @@ int launch_routing(const des_shape_t& s, const void* x, const void* w_router, co
   if (groups > kMaxSelGroups / a.B) groups = kMaxSelGroups / a.B > 0 ? kMaxSelGroups / a.B : 1;
   if (n_tiles + a.B * groups + 1 > fused_limit) groups = 1;
   const int roles = n_tiles + a.B * groups + (a.B * groups > 1 ? 1 : 0);
+  // One selector workgroup and at most 32 tokens: the short permutation.  (Skipping
+  // drops a token's experts after they were drawn, so the bitmaps of stage 2 would name
+  // pairs that no longer exist: it keeps the general permutation.)
+  const bool small = a.B == 1 && groups == 1 && s.n_tokens <= 32 && !(s.skip_beta > 0.0f);
   if (roles <= fused_limit) {  // all workgroups resident at once: one launch
     a.groups = groups;
+    a.small_perm = small;
     a.do_router = a.do_select = a.do_permute = 1;
     a.use_flags = 1;
     if (g_test_skip_router) {  // test hook: nobody computes the logits, the selectors' wait expires
@@ -1172,6 +1263,7 @@ int launch_routing(const des_shape_t& s, const void* x, const void* w_router, co
   RoutingArgs sel = a;
   sel.do_select = 1;
   sel.do_permute = a.B == 1 ? 1 : 0;
+  sel.small_perm = a.B == 1 && s.n_tokens <= 32 && !(s.skip_beta > 0.0f);
   rc = launch_routing_grid(sel, a.B, kKSelect, st);
   if (rc != DES_OK || a.B == 1) return rc;
   RoutingArgs p = a;
