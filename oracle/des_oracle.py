@@ -26,6 +26,10 @@ one passage of the paper:
   expert_ffn           E_i(x): SwiGLU sub-network (form fixed by the workload)
   moe_forward          Alg. 1 as a whole (+ Eq. 1 when mode == "vanilla")
   moe_stack_forward    residual stack of such layers
+  block_attention      the attention sub-layer around the MoE layers in a decoding step
+                       (Fig. 2 left names its share of the latency; Sec. 5.1 fixes the
+                       window: the block plus cached prefix and suffix positions)
+  decoder_stack_forward     x <- x + Attn_l(x); x <- x + MoE_l(x), layer by layer
   expected_unique_uniform   closed form of Sec. 3 (Motivation)
   coreset_size_from_beta    M_core = beta * M (Sec. 5.1), floor (Table 1)
 
@@ -493,6 +497,77 @@ def moe_stack_forward(x: np.ndarray, layers: Sequence[dict], K: int, C: int, mod
         r = moe_forward(cur, lw["w_router"], lw.get("bias"), lw["w_gate"], lw["w_up"],
                         lw["w_down"], K, C, mode, k_seq, shared=lw.get("shared"),
                         residual=True)
+        per_layer.append(r)
+        cur = r["y"]
+    return cur, per_layer
+
+
+# --------------------------------------------------------------------------
+# Attention around the MoE layers (the wider decoding step)
+# --------------------------------------------------------------------------
+def block_attention(x: np.ndarray, wq: np.ndarray, wk: np.ndarray, wv: np.ndarray, wo: np.ndarray,
+                    k_cache: np.ndarray, v_cache: np.ndarray, n_heads: int, n_kv_heads: int,
+                    residual: bool = False) -> np.ndarray:
+    """The attention sub-layer of one decoding step of a block-parallel decoder with
+    cached context (Sec. 5.1: a block of N tokens, cached prefix and suffix positions).
+    The paper treats attention as a fixed, non-MoE cost (Fig. 2 left, Sec. 5.2) and
+    does not define it; this is plain multi-head scaled-dot-product attention, every
+    block token attending to every cached position and to every token of its own block
+    (no causal mask: all block tokens are decoded together), no positional encoding,
+    no bias (readings listed in the design notes).
+
+      x        [B, N, D]        hidden states of the block
+      wq       [H*dh, D]        row r produces query coordinate r   (likewise wk, wv: [Hkv*dh, D])
+      wo       [D, H*dh]        row d produces output coordinate d
+      k_cache, v_cache  [B, Hkv, P, dh]   keys / values of the P cached positions
+      q = wq x, k = wk x, v = wv x for the block's own tokens; head h of the H query heads
+      reads key/value head h // (H / Hkv); for token n and head h
+        s_j = <q_n, key_j> / sqrt(dh) over the P cached and the N block keys,
+        p = softmax(s),  o_n = sum_j p_j value_j;   y_n = wo [o_n over heads] (+ x_n).
+    Everything in float64.  Returns y [B, N, D]."""
+    x = np.asarray(x, dtype=np.float64)
+    B, N, D = x.shape
+    wq, wk, wv, wo = (np.asarray(m, dtype=np.float64) for m in (wq, wk, wv, wo))
+    kc = np.asarray(k_cache, dtype=np.float64)
+    vc = np.asarray(v_cache, dtype=np.float64)
+    H, Hkv = n_heads, n_kv_heads
+    dh = wq.shape[0] // H
+    assert wq.shape == (H * dh, D) and wk.shape == (Hkv * dh, D) and wv.shape == (Hkv * dh, D)
+    assert wo.shape == (D, H * dh) and H % Hkv == 0
+    P = kc.shape[2]
+    assert kc.shape == (B, Hkv, P, dh) and vc.shape == (B, Hkv, P, dh)
+    y = np.zeros((B, N, D), dtype=np.float64)
+    for b in range(B):
+        q = x[b] @ wq.T                      # [N, H*dh]
+        k = x[b] @ wk.T                      # [N, Hkv*dh]
+        v = x[b] @ wv.T
+        heads = np.zeros((N, H * dh), dtype=np.float64)
+        for h in range(H):
+            g = h // (H // Hkv)
+            keys = np.concatenate([kc[b, g], k[:, g * dh:(g + 1) * dh]], axis=0)   # [P + N, dh]
+            vals = np.concatenate([vc[b, g], v[:, g * dh:(g + 1) * dh]], axis=0)
+            for n in range(N):
+                s = keys @ q[n, h * dh:(h + 1) * dh] / math.sqrt(dh)
+                p = np.exp(s - s.max())
+                p /= p.sum()
+                heads[n, h * dh:(h + 1) * dh] = p @ vals
+        y[b] = heads @ wo.T
+    return y + x if residual else y
+
+
+def decoder_stack_forward(x: np.ndarray, layers: Sequence[dict], K: int, C: int, mode: str,
+                          n_heads: int, n_kv_heads: int) -> Tuple[np.ndarray, List[Dict[str, object]]]:
+    """A stack of decoder layers, each an attention sub-layer followed by a MoE sub-layer,
+    both with a residual connection:  a = x + Attn_l(x);  x' = a + MoE_l(a).  Each layer is
+    a dict with wq, wk, wv, wo, k_cache, v_cache and the MoE tensors of moe_stack_forward.
+    Returns the final hidden states and the per-layer MoE results."""
+    cur = np.asarray(x, dtype=np.float64)
+    per_layer = []
+    for lw in layers:
+        a = block_attention(cur, lw["wq"], lw["wk"], lw["wv"], lw["wo"], lw["k_cache"], lw["v_cache"],
+                            n_heads, n_kv_heads, residual=True)
+        r = moe_forward(a, lw["w_router"], lw.get("bias"), lw["w_gate"], lw["w_up"], lw["w_down"],
+                        K, C, mode, shared=lw.get("shared"), residual=True)
         per_layer.append(r)
         cur = r["y"]
     return cur, per_layer

@@ -554,3 +554,110 @@ def test_group_limit_in_the_layer():
         r = O.route_block(L, "vote", K, C, n_group=ng, topk_group=tg)
         assert r["coreset"] == base["coreset"] and np.array_equal(r["topk_idx"], base["topk_idx"])
         np.testing.assert_array_equal(r["topk_w"], base["topk_w"])
+
+
+# ------------------------------------------------ attention around the MoE layers
+def _attn_case(seed, B=2, N=5, D=12, H=4, Hkv=2, dh=3, P=6):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((B, N, D))
+    wq = rng.standard_normal((H * dh, D)) * 0.4
+    wk = rng.standard_normal((Hkv * dh, D)) * 0.4
+    wv = rng.standard_normal((Hkv * dh, D)) * 0.4
+    wo = rng.standard_normal((D, H * dh)) * 0.4
+    kc = rng.standard_normal((B, Hkv, P, dh))
+    vc = rng.standard_normal((B, Hkv, P, dh))
+    return x, wq, wk, wv, wo, kc, vc, H, Hkv
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_block_attention_equals_library_attention(seed):
+    """The oracle's loops against torch's scaled_dot_product_attention on the CPU (a library
+    routine, float64): projections, grouped key/value heads, the window of cached and block
+    positions, the scale 1/sqrt(dh), the output projection, the residual."""
+    import torch
+    x, wq, wk, wv, wo, kc, vc, H, Hkv = _attn_case(seed)
+    B, N, D = x.shape
+    dh = wq.shape[0] // H
+    y = O.block_attention(x, wq, wk, wv, wo, kc, vc, H, Hkv, residual=True)
+    tx = torch.from_numpy(x)
+    q = (tx @ torch.from_numpy(wq).T).reshape(B, N, H, dh).permute(0, 2, 1, 3)
+    k = (tx @ torch.from_numpy(wk).T).reshape(B, N, Hkv, dh).permute(0, 2, 1, 3)
+    v = (tx @ torch.from_numpy(wv).T).reshape(B, N, Hkv, dh).permute(0, 2, 1, 3)
+    keys = torch.cat([torch.from_numpy(kc), k], dim=2).repeat_interleave(H // Hkv, dim=1)
+    vals = torch.cat([torch.from_numpy(vc), v], dim=2).repeat_interleave(H // Hkv, dim=1)
+    o = torch.nn.functional.scaled_dot_product_attention(q, keys, vals)   # no mask, scale 1/sqrt(dh)
+    ref = o.permute(0, 2, 1, 3).reshape(B, N, H * dh) @ torch.from_numpy(wo).T + tx
+    np.testing.assert_allclose(y, ref.numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_block_attention_invariants():
+    """What the definition fixes whatever the numbers: (1) with all scores equal the weights
+    are uniform, so a head's output is the mean of its values; (2) the result does not depend
+    on the order of the cached positions; (3) with no cached position and a single block token
+    the token attends to itself only; (4) sequences are independent; (5) adding one cached key
+    of score 0 moves a head's output by p * (value - output) with p = 1 / (Z + 1)."""
+    x, wq, wk, wv, wo, kc, vc, H, Hkv = _attn_case(7)
+    B, N, D = x.shape
+    dh = wq.shape[0] // H
+    P = kc.shape[2]
+    # (1) zero queries: every score is 0; cached values all equal c, block values 0 (wv = 0)
+    c = np.arange(1, dh + 1, dtype=np.float64)
+    y = O.block_attention(x, wq * 0.0, wk, np.zeros_like(wv), wo, kc, np.broadcast_to(c, vc.shape).copy(), H, Hkv)
+    head = np.tile(c * P / (P + N), H)
+    np.testing.assert_allclose(y, np.broadcast_to(head @ wo.T, y.shape), rtol=1e-12, atol=1e-12)
+    # (2) permutation of the cache
+    perm = np.random.default_rng(1).permutation(P)
+    y0 = O.block_attention(x, wq, wk, wv, wo, kc, vc, H, Hkv)
+    y1 = O.block_attention(x, wq, wk, wv, wo, kc[:, :, perm], vc[:, :, perm], H, Hkv)
+    np.testing.assert_allclose(y0, y1, rtol=1e-12, atol=1e-13)
+    # (3) one token, empty cache: y = wo [wv x, each query head reading its key/value group]
+    x1 = x[:1, :1]
+    e = np.zeros((1, Hkv, 0, dh))
+    y3 = O.block_attention(x1, wq, wk, wv, wo, e, e, H, Hkv)
+    v = wv @ x1[0, 0]
+    heads = np.concatenate([v[(h // (H // Hkv)) * dh:(h // (H // Hkv) + 1) * dh] for h in range(H)])
+    np.testing.assert_allclose(y3[0, 0], wo @ heads, rtol=1e-12, atol=1e-13)
+    # (4) sequences are independent
+    yb = O.block_attention(x[1:], wq, wk, wv, wo, kc[1:], vc[1:], H, Hkv)
+    np.testing.assert_allclose(y0[1:], yb, rtol=1e-12, atol=1e-13)
+    # (5) one more cached key with score 0 (a zero key) and value 1e6 in every coordinate;
+    # an identity output projection exposes the heads
+    kc5 = np.concatenate([kc, np.zeros((B, Hkv, 1, dh))], axis=2)
+    vc5 = np.concatenate([vc, np.full((B, Hkv, 1, dh), 1e6)], axis=2)
+    eye = np.eye(D, H * dh)
+    y5 = O.block_attention(x, wq, wk, wv, eye, kc5, vc5, H, Hkv)
+    y5_0 = O.block_attention(x, wq, wk, wv, eye, kc, vc, H, Hkv)
+    h, n = 1, 2
+    g = h // (H // Hkv)
+    keys = np.concatenate([kc[0, g], (x[0] @ wk.T)[:, g * dh:(g + 1) * dh]], axis=0)
+    s = keys @ (x[0] @ wq.T)[n, h * dh:(h + 1) * dh] / math.sqrt(dh)
+    p_extra = 1.0 / (np.exp(s).sum() + 1.0)
+    o_old = y5_0[0, n, h * dh:(h + 1) * dh]
+    np.testing.assert_allclose(y5[0, n, h * dh:(h + 1) * dh], o_old + p_extra * (1e6 - o_old), rtol=1e-9)
+
+
+def test_decoder_stack_is_the_two_sublayers_in_turn():
+    """decoder_stack_forward against the two pinned sub-layers applied by hand, and the
+    identity that zero attention output weights reduce it to the MoE stack."""
+    rng = np.random.default_rng(5)
+    B, N, D, M, F, K, C, H, Hkv, dh, P = 2, 4, 8, 6, 5, 2, 3, 2, 1, 4, 3
+    layers = []
+    for _ in range(3):
+        layers.append(dict(
+            wq=rng.standard_normal((H * dh, D)) * 0.3, wk=rng.standard_normal((Hkv * dh, D)) * 0.3,
+            wv=rng.standard_normal((Hkv * dh, D)) * 0.3, wo=rng.standard_normal((D, H * dh)) * 0.3,
+            k_cache=rng.standard_normal((B, Hkv, P, dh)), v_cache=rng.standard_normal((B, Hkv, P, dh)),
+            w_router=rng.standard_normal((M, D)), bias=None, w_gate=rng.standard_normal((M, F, D)) * 0.3,
+            w_up=rng.standard_normal((M, F, D)) * 0.3, w_down=rng.standard_normal((M, D, F)) * 0.3))
+    x = rng.standard_normal((B, N, D))
+    y, per = O.decoder_stack_forward(x, layers, K, C, "vote", H, Hkv)
+    cur = x
+    for lw in layers:
+        a = cur + O.block_attention(cur, lw["wq"], lw["wk"], lw["wv"], lw["wo"], lw["k_cache"], lw["v_cache"], H, Hkv)
+        cur = a + O.moe_forward(a, lw["w_router"], None, lw["w_gate"], lw["w_up"], lw["w_down"], K, C, "vote")["y"]
+    np.testing.assert_allclose(y, cur, rtol=1e-12, atol=1e-12)
+    zero = [dict(lw, wo=np.zeros_like(lw["wo"])) for lw in layers]
+    y0, _ = O.decoder_stack_forward(x, zero, K, C, "vote", H, Hkv)
+    y1, _ = O.moe_stack_forward(x, layers, K, C, "vote")
+    np.testing.assert_allclose(y0, y1, rtol=1e-12, atol=1e-12)
+
