@@ -264,6 +264,58 @@ int des_moe_stack_forward(const des_shape_t* shape, int32_t n_layers, const void
                           size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The attention sub-layer around the MoE layers of a decoding step (the wider step of
+ * Fig. 2 left, where attention is the other large share of the latency; Sec. 5.1: a
+ * block of N tokens with cached prefix and suffix positions).  The paper does not define
+ * it; this is plain multi-head scaled-dot-product attention: every block token attends
+ * to every cached position and to every token of its own block (no causal mask - the
+ * block is decoded together), no positional encoding, no bias.
+ *   q = Wq x, k = Wk x, v = Wv x for the block's tokens; query head h reads key/value head
+ *   h / (n_heads / n_kv_heads);  p = softmax(<q, key_j> / sqrt(head_dim)) over the
+ *   n_prefix + n_suffix cached and the N block positions;  o = sum_j p_j value_j;
+ *   y = Wo [o over heads] (+ x if shape->residual).
+ * bf16 only (DES_ERR_DTYPE otherwise).  Layouts: wq [H*dh][D], wk, wv [Hkv*dh][D],
+ * wo [D][H*dh] (rows along the reduction dimension, row-major); k_cache, v_cache
+ * [B][Hkv][n_prefix + n_suffix][dh] (prefix positions first; may be NULL if both are 0);
+ * x, y [B][N][D].  Limits (DES_ERR_SHAPE): D and H*dh multiples of 128; Hkv*dh a
+ * multiple of 32; dh a multiple of 8, at most 128; n_heads a multiple of n_kv_heads; one
+ * head's values fit 160 KB of LDS ((dh rounded up to 16) x (P + N rounded up to 32, + 4)
+ * bf16: up to 600 positions at dh = 128).
+ * Of `shape` only n_seqs, n_tokens, hidden, dtype and residual are read.  y must not alias x.
+ * workspace: >= des_attention_workspace_bytes(), 256-byte aligned, contents irrelevant.
+ */
+typedef struct {
+  int32_t n_heads;     /* H: query heads                                         */
+  int32_t n_kv_heads;  /* Hkv: key / value heads (grouped queries when < H)      */
+  int32_t head_dim;    /* dh                                                     */
+  int32_t n_prefix;    /* cached positions before the block (Sec. 5.1 uses 16)   */
+  int32_t n_suffix;    /* cached positions after the block  (Sec. 5.1 uses 16)   */
+} des_attn_shape_t;
+
+size_t des_attention_workspace_bytes(const des_shape_t* shape, const des_attn_shape_t* attn);
+int des_block_attention(const des_shape_t* shape, const des_attn_shape_t* attn, const void* x,
+                        const void* wq, const void* wk, const void* wv, const void* wo,
+                        const void* k_cache, const void* v_cache, void* y, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
+
+/*
+ * A stack of decoder layers, each the attention sub-layer above followed by the MoE
+ * layer, both with a residual connection:  a = x_l + Attn_l(x_l);  x_{l+1} = a + MoE_l(a).
+ * Layer l's tensors start at base + l * (their size): wq [L][H*dh][D], wk, wv, wo,
+ * k_cache / v_cache [L][B][Hkv][P][dh], and the MoE tensors as in des_moe_stack_forward.
+ * Outputs as des_moe_stack_forward.  workspace: >= des_decoder_workspace_bytes().
+ */
+size_t des_decoder_workspace_bytes(const des_shape_t* shape, const des_attn_shape_t* attn);
+int des_decoder_stack_forward(const des_shape_t* shape, const des_attn_shape_t* attn, int32_t n_layers,
+                              const void* x, const void* wq, const void* wk, const void* wv,
+                              const void* wo, const void* k_cache, const void* v_cache,
+                              const void* w_router, const float* router_bias, const void* w_gate,
+                              const void* w_up, const void* w_down, const void* ws_gate,
+                              const void* ws_up, const void* ws_down, void* y,
+                              int32_t* expert_counts, int32_t* n_unique, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+
+/*
  * Re-tile bf16 expert weights for DES_LAYOUT_PACKED.  `src` is n_mats
  * row-major matrices [rows][cols] (cols = reduction dimension; rows a
  * multiple of 16, cols a multiple of 32); `dst` (same size, must not alias)
@@ -307,7 +359,7 @@ int des_hbm_read_probe(const void* src, size_t bytes, void* sink, void* hip_stre
  * recorded events and returns the accumulated duration and launch count of one
  * kernel id in [0, des_kernel_timing_count()); des_kernel_timing_name() names
  * it (router, softmax, select, permute, gateup, down, combine, pack, routing,
- * ffn, read_probe).
+ * ffn, read_probe, attn_proj, attn_core, attn_out).
  * des_kernel_timing_enable() also clears the accumulators.  Not thread-safe.
  */
 int des_kernel_timing_enable(int enable);

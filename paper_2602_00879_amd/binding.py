@@ -26,6 +26,8 @@ EXPORTS = (
     "des_pack_expert_weights", "des_strerror", "des_last_hip_error",
     "des_kernel_timing_enable", "des_kernel_timing_count", "des_kernel_timing_name",
     "des_kernel_timing_read", "des_hbm_read_probe", "des_coreset_from_beta", "des_test_hooks",
+    "des_attention_workspace_bytes", "des_block_attention", "des_decoder_workspace_bytes",
+    "des_decoder_stack_forward",
 )
 
 
@@ -42,6 +44,10 @@ class DesShape(ctypes.Structure):
         ("skip_beta", ctypes.c_float), ("router_act", ctypes.c_int32), ("vote_renorm", ctypes.c_int32),
         ("n_group", ctypes.c_int32), ("topk_group", ctypes.c_int32), ("group_score", ctypes.c_int32),
         ("vote_atomic", ctypes.c_int32)]
+
+
+class DesAttnShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_heads", "n_kv_heads", "head_dim", "n_prefix", "n_suffix")]
 
 
 class DesError(RuntimeError):
@@ -70,6 +76,15 @@ def lib() -> ctypes.CDLL:
         L.des_workspace_bytes.argtypes = [sp]
         L.des_stack_workspace_bytes.restype = sz
         L.des_stack_workspace_bytes.argtypes = [sp]
+        ap = ctypes.POINTER(DesAttnShape)
+        L.des_attention_workspace_bytes.restype = sz
+        L.des_attention_workspace_bytes.argtypes = [sp, ap]
+        L.des_decoder_workspace_bytes.restype = sz
+        L.des_decoder_workspace_bytes.argtypes = [sp, ap]
+        L.des_block_attention.restype = ctypes.c_int
+        L.des_block_attention.argtypes = [sp, ap] + [vp] * 9 + [sz, vp]
+        L.des_decoder_stack_forward.restype = ctypes.c_int
+        L.des_decoder_stack_forward.argtypes = [sp, ap, i32] + [vp] * 19 + [sz, vp]
         L.des_route.restype = ctypes.c_int
         L.des_route.argtypes = [sp] + [vp] * 6
         L.des_select_coreset.restype = ctypes.c_int
@@ -260,6 +275,65 @@ def des_moe_stack_forward(shape: DesShape, n_layers: int, x, w_router, router_bi
     sg, su, sd = shared if shared is not None else (None, None, None)
     _check(lib().des_moe_stack_forward(
         ctypes.byref(shape), n_layers, _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(w_gate),
+        _ptr(w_up), _ptr(w_down), _ptr(sg), _ptr(su), _ptr(sd), _ptr(b.y), _ptr(b.expert_counts),
+        _ptr(b.n_unique), _ptr(b.workspace), ctypes.c_size_t(b.workspace.numel()), _stream()))
+    return b
+
+
+def make_attn_shape(n_heads: int, n_kv_heads: int, head_dim: int, n_prefix: int = 0,
+                    n_suffix: int = 0) -> DesAttnShape:
+    return DesAttnShape(n_heads, n_kv_heads, head_dim, n_prefix, n_suffix)
+
+
+def des_attention_workspace_bytes(shape: DesShape, attn: DesAttnShape) -> int:
+    return int(lib().des_attention_workspace_bytes(ctypes.byref(shape), ctypes.byref(attn)))
+
+
+def des_decoder_workspace_bytes(shape: DesShape, attn: DesAttnShape) -> int:
+    return int(lib().des_decoder_workspace_bytes(ctypes.byref(shape), ctypes.byref(attn)))
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    if nbytes == 0:
+        raise DesError(-2, "shape rejected by the library (workspace size 0)")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def des_block_attention(shape: DesShape, attn: DesAttnShape, x, wq, wk, wv, wo, k_cache=None,
+                        v_cache=None, y: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The attention sub-layer of one block-parallel decoding step; returns y [B, N, D]."""
+    if y is None:
+        y = torch.empty_like(x)
+    if workspace is None:
+        workspace = _workspace(des_attention_workspace_bytes(shape, attn), x.device)
+    _check(lib().des_block_attention(
+        ctypes.byref(shape), ctypes.byref(attn), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
+        _ptr(k_cache), _ptr(v_cache), _ptr(y), _ptr(workspace), ctypes.c_size_t(workspace.numel()),
+        _stream()))
+    return y
+
+
+class DecoderBuffers:
+    """Outputs and scratch of des_decoder_stack_forward."""
+
+    def __init__(self, shape: DesShape, attn: DesAttnShape, n_layers: int, device, dtype):
+        B, N, M = shape.n_seqs, shape.n_tokens, shape.n_experts
+        i32 = torch.int32
+        self.y = torch.empty((B, N, shape.hidden), dtype=dtype, device=device)
+        self.expert_counts = torch.empty((n_layers, M), dtype=i32, device=device)
+        self.n_unique = torch.empty((n_layers,), dtype=i32, device=device)
+        self.workspace = _workspace(des_decoder_workspace_bytes(shape, attn), device)
+
+
+def des_decoder_stack_forward(shape: DesShape, attn: DesAttnShape, n_layers: int, x, wq, wk, wv, wo,
+                              k_cache, v_cache, w_router, router_bias, w_gate, w_up, w_down,
+                              shared=None, buffers: Optional[DecoderBuffers] = None) -> DecoderBuffers:
+    b = buffers if buffers is not None else DecoderBuffers(shape, attn, n_layers, x.device, x.dtype)
+    sg, su, sd = shared if shared is not None else (None, None, None)
+    _check(lib().des_decoder_stack_forward(
+        ctypes.byref(shape), ctypes.byref(attn), n_layers, _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv),
+        _ptr(wo), _ptr(k_cache), _ptr(v_cache), _ptr(w_router), _ptr(router_bias), _ptr(w_gate),
         _ptr(w_up), _ptr(w_down), _ptr(sg), _ptr(su), _ptr(sd), _ptr(b.y), _ptr(b.expert_counts),
         _ptr(b.n_unique), _ptr(b.workspace), ctypes.c_size_t(b.workspace.numel()), _stream()))
     return b

@@ -8,7 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdes_hip.so")
-SOURCES = ["des_api.hip", "des_routing.hip", "des_ffn.hip"]
+SOURCES = ["des_api.hip", "des_routing.hip", "des_ffn.hip", "des_attention.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 arithmetic is switched off (some of its forms are unreliable here)

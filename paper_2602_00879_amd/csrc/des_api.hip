@@ -300,6 +300,119 @@ int des_moe_stack_forward(const des_shape_t* s_in, int32_t n_layers, const void*
   return DES_OK;
 }
 
+// ---- attention sub-layer and decoder stack ----
+static int check_attn(const des_shape_t* s, const des_attn_shape_t* t) {
+  if (!s || !t) return DES_ERR_NULL;
+  if (s->dtype != DES_BF16) return DES_ERR_DTYPE;
+  if (s->n_seqs < 1 || s->n_tokens < 1 || s->hidden < 128 || s->hidden % 128) return DES_ERR_SHAPE;
+  if (static_cast<long long>(s->n_seqs) * s->n_tokens > 4096) return DES_ERR_SHAPE;
+  if (s->residual != 0 && s->residual != 1) return DES_ERR_SHAPE;
+  if (t->n_heads < 1 || t->n_kv_heads < 1 || t->head_dim < 8 || t->head_dim % 8 || t->head_dim > 128)
+    return DES_ERR_SHAPE;
+  if (t->n_heads % t->n_kv_heads) return DES_ERR_SHAPE;
+  if (t->n_prefix < 0 || t->n_suffix < 0 || t->n_prefix + t->n_suffix > 4096) return DES_ERR_SHAPE;
+  const long long hd = static_cast<long long>(t->n_heads) * t->head_dim;
+  const long long kd = static_cast<long long>(t->n_kv_heads) * t->head_dim;
+  if (hd % 128 || kd % 32 || hd > 16384) return DES_ERR_SHAPE;
+  if (attn_core_lds(*s, *t) > 160 * 1024) return DES_ERR_SHAPE;
+  return DES_OK;
+}
+
+size_t des_attention_workspace_bytes(const des_shape_t* s, const des_attn_shape_t* t) {
+  if (check_attn(s, t) != DES_OK) return 0;
+  return attn_layout(*s, *t).total;
+}
+
+int des_block_attention(const des_shape_t* s, const des_attn_shape_t* t, const void* x, const void* wq,
+                        const void* wk, const void* wv, const void* wo, const void* k_cache,
+                        const void* v_cache, void* y, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+  const int rc = check_attn(s, t);
+  if (rc != DES_OK) return rc;
+  if (!x || !wq || !wk || !wv || !wo || !y || !workspace) return DES_ERR_NULL;
+  if (attn_cached(*t) > 0 && (!k_cache || !v_cache)) return DES_ERR_NULL;
+  if (x == y) return DES_ERR_SHAPE;
+  if (workspace_bytes < attn_layout(*s, *t).total) return DES_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return DES_ERR_WORKSPACE;
+  return launch_attention(*s, *t, x, wq, wk, wv, wo, k_cache, v_cache, y, static_cast<char*>(workspace),
+                          static_cast<hipStream_t>(hip_stream));
+}
+
+size_t des_decoder_workspace_bytes(const des_shape_t* s, const des_attn_shape_t* t) {
+  if (check_shape(s, true) != DES_OK || check_attn(s, t) != DES_OK) return 0;
+  return align256(stack_layout(*s).total) + attn_layout(*s, *t).total;
+}
+
+int des_decoder_stack_forward(const des_shape_t* s_in, const des_attn_shape_t* t, int32_t n_layers,
+                              const void* x, const void* wq, const void* wk, const void* wv,
+                              const void* wo, const void* k_cache, const void* v_cache,
+                              const void* w_router, const float* router_bias, const void* w_gate,
+                              const void* w_up, const void* w_down, const void* ws_gate,
+                              const void* ws_up, const void* ws_down, void* y, int32_t* expert_counts,
+                              int32_t* n_unique, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  int rc = check_shape(s_in, true);
+  if (rc != DES_OK) return rc;
+  rc = check_attn(s_in, t);
+  if (rc != DES_OK) return rc;
+  if (n_layers < 1) return DES_ERR_SHAPE;
+  if (!x || !wq || !wk || !wv || !wo || !w_router || !w_gate || !w_up || !w_down || !y ||
+      !expert_counts || !n_unique || !workspace)
+    return DES_ERR_NULL;
+  if (attn_cached(*t) > 0 && (!k_cache || !v_cache)) return DES_ERR_NULL;
+  if (x == y) return DES_ERR_SHAPE;
+  des_shape_t s = *s_in;
+  s.residual = 1;
+  if (s.ffn_shared > 0 && (!ws_gate || !ws_up || !ws_down)) return DES_ERR_NULL;
+  const StackLayout l = stack_layout(s);
+  const size_t attn_ws = align256(l.total);
+  if (workspace_bytes < attn_ws + attn_layout(s, *t).total) return DES_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return DES_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  const size_t el = 2;
+  const size_t M = s.n_experts, D = s.hidden, F = s.ffn, Fs = s.ffn_shared;
+  const size_t HD = static_cast<size_t>(t->n_heads) * t->head_dim;
+  const size_t KD = static_cast<size_t>(t->n_kv_heads) * t->head_dim;
+  const size_t cache = static_cast<size_t>(s.n_seqs) * t->n_kv_heads * attn_cached(*t) * t->head_dim;
+  const char* cur = static_cast<const char*>(x);
+  for (int layer = 0; layer < n_layers; ++layer) {
+    const size_t li = static_cast<size_t>(layer);
+    // a = cur + Attn(cur) -> xa;  out = a + MoE(a) -> xb (the last layer: y)
+    char* a = ws + l.xa;
+    char* out = layer == n_layers - 1 ? static_cast<char*>(y) : ws + l.xb;
+    rc = launch_attention(s, *t, cur, static_cast<const char*>(wq) + li * HD * D * el,
+                          static_cast<const char*>(wk) + li * KD * D * el,
+                          static_cast<const char*>(wv) + li * KD * D * el,
+                          static_cast<const char*>(wo) + li * D * HD * el,
+                          k_cache ? static_cast<const char*>(k_cache) + li * cache * el : nullptr,
+                          v_cache ? static_cast<const char*>(v_cache) + li * cache * el : nullptr, a,
+                          ws + attn_ws, st);
+    if (rc != DES_OK) return rc;
+    const char* wr = static_cast<const char*>(w_router) + li * M * D * el;
+    const float* rb = router_bias ? router_bias + li * M : nullptr;
+    const char* wg = static_cast<const char*>(w_gate) + li * M * F * D * el;
+    const char* wu = static_cast<const char*>(w_up) + li * M * F * D * el;
+    const char* wd = static_cast<const char*>(w_down) + li * M * F * D * el;
+    const char* sg = ws_gate ? static_cast<const char*>(ws_gate) + li * Fs * D * el : nullptr;
+    const char* su = ws_up ? static_cast<const char*>(ws_up) + li * Fs * D * el : nullptr;
+    const char* sd = ws_down ? static_cast<const char*>(ws_down) + li * Fs * D * el : nullptr;
+    float* logits = reinterpret_cast<float*>(ws + l.logits);
+    int32_t* tidx = reinterpret_cast<int32_t*>(ws + l.topk_idx);
+    float* tw = reinterpret_cast<float*>(ws + l.topk_w);
+    char* lws = ws + l.layer_ws;
+    const unsigned long long epoch = next_epoch();
+    rc = launch_routing(s, a, wr, rb, logits, reinterpret_cast<int32_t*>(ws + l.core_idx),
+                        reinterpret_cast<int32_t*>(ws + l.core_size), tidx, tw, expert_counts + li * M,
+                        n_unique + li, layer > 0 ? n_unique + li - 1 : nullptr, lws, epoch, st);
+    if (rc != DES_OK) return rc;
+    rc = launch_ffn(s, a, wg, wu, wd, sg, su, sd, tidx, tw, n_unique + li, out, lws, epoch, st);
+    if (rc != DES_OK) return rc;
+    cur = out;
+  }
+  return DES_OK;
+}
+
 int des_pack_expert_weights(const void* src, void* dst, int64_t n_mats, int32_t rows, int32_t cols,
                             void* hip_stream) {
   if (!src || !dst) return DES_ERR_NULL;
@@ -359,7 +472,8 @@ int des_kernel_timing_count(void) { return kKCount; }
 
 const char* des_kernel_timing_name(int kernel_id) {
   static const char* names[kKCount] = {"router", "softmax", "select", "permute", "gateup",
-                                       "down", "combine", "pack", "routing", "ffn", "read_probe"};
+                                       "down", "combine", "pack", "routing", "ffn", "read_probe",
+                                       "attn_proj", "attn_core", "attn_out"};
   return (kernel_id >= 0 && kernel_id < kKCount) ? names[kernel_id] : "";
 }
 

@@ -1,0 +1,318 @@
+// The attention sub-layer of a block-parallel decoding step, for gfx950: every token of
+// the block attends to the cached prefix / suffix positions and to the whole block
+// (Sec. 5.1 fixes that window; Fig. 2 left and Sec. 5.2 count attention among the fixed,
+// non-MoE costs of a step).  The paper does not define the sub-layer; this is plain
+// multi-head scaled-dot-product attention without mask, positional encoding or bias.
+//
+// Three launches per sub-layer:
+//   1. q, k, v = x Wq^T, x Wk^T, x Wv^T     one dense-projection launch over the three
+//                                            weight matrices (bf16 MFMA, fp32 accumulate)
+//   2. softmax(q K^T / sqrt(dh)) V           one workgroup per (sequence, head), bf16 MFMA
+//   3. y = heads Wo^T (+ x)                  the same projection kernel, residual fused
+// The projections are weight scans like the expert FFN (a 2048 x 2048 matrix is 8 MB for
+// at most a few hundred token rows), so they reuse its streaming building block: weights
+// from HBM straight into MFMA operands, token rows staged through LDS.
+#include "des_common.h"
+#include "des_stream_gemm.h"
+
+namespace des {
+
+struct LinearArgs {
+  const uint16_t* in;    // [T][Din] bf16 token rows
+  const uint16_t* w[3];  // up to three weight matrices [fout[i]][Din], rows along the reduction
+  uint16_t* out[3];      // [T][fout[i]] bf16
+  const uint16_t* res;   // [T][fout[0]] bf16 added to out[0] before rounding, or null
+  int fout[3];
+  int n_mats, T, Din;
+};
+
+// out[m][t][f] = sum_d in[t][d] * w[m][f][d].  A workgroup of LW wavefronts owns LW pairs
+// of 16-row weight tiles of one matrix and walks the token rows in passes of up to 128
+// (the weights are streamed once per pass).  KD = the reduction length if it is the
+// unrolled one (2048), else 0.
+template <int LW, int KD>
+__global__ __launch_bounds__(LW* kWave, 2) void linear_lds_kernel(LinearArgs a) {
+  constexpr int kRows = 128;
+  __shared__ __align__(16) uint16_t lds[lds_elems(KD)];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  int bx = blockIdx.x, m = 0;
+  for (; m < a.n_mats; ++m) {  // which matrix this workgroup belongs to
+    const int per = (a.fout[m] / 32 + LW - 1) / LW;
+    if (bx < per) break;
+    bx -= per;
+  }
+  if (m >= a.n_mats) return;
+  const int fout = a.fout[m], Din = a.Din;
+  const int pair = bx * LW + wave;          // pair of row tiles this wavefront owns
+  const bool active = pair * 2 < fout / 16;
+  const uint16_t* w = uniform_ptr(a.w[m]);
+  const uint16_t* p0 = tile_base<false>(w, active ? pair * 2 : 0, Din);
+  const uint16_t* p1 = tile_base<false>(w, active ? pair * 2 + 1 : 0, Din);
+  const uint32_t wlo = tile_lane_off<false>(Din, lane);
+  const uint16_t* in = uniform_ptr(a.in);
+  uint16_t* out = a.out[m];
+  const uint16_t* res = m == 0 ? a.res : nullptr;
+  for (int g0 = 0; g0 < a.T; g0 += kRows) {
+    const int rows = min(kRows, a.T - g0);
+    const int nt = (rows + 15) / 16;
+    auto row_off = [&](int r) { return (g0 + r) * Din; };
+    auto run = [&](auto ntc) {
+      constexpr int NT = decltype(ntc)::value;
+      f32x4 acc0[NT], acc1[NT];
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        acc0[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc1[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+      constexpr int KC = NT <= 4 ? 128 : 64;
+      dma_stream_gemm<NT, kLdsBufElems / KC, false, LW, KC, KD>(p0, p1, wlo, wave, Din, rows, in, row_off, lds,
+                                                                 acc0, acc1);
+      if (!active) return;
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        const int pi = g0 + i * 16 + (lane & 15);
+        if (pi < a.T) {
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const f32x4 v = half ? acc1[i] : acc0[i];
+            const size_t o = static_cast<size_t>(pi) * fout + (pair * 2 + half) * 16 + 4 * (lane >> 4);
+            f32x4 r = v;
+            if (res != nullptr) {
+              const u16x4 rv = *reinterpret_cast<const u16x4*>(res + o);
+#pragma unroll
+              for (int q = 0; q < 4; ++q) r[q] += bf16_bits_to_f32(rv[q]);
+            }
+            u16x4 ob;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) ob[q] = f32_to_bf16_bits(r[q]);
+            *reinterpret_cast<u16x4*>(out + o) = ob;
+          }
+        }
+      }
+    };
+    if (nt <= 1) run(std::integral_constant<int, 1>{});
+    else if (nt <= 2) run(std::integral_constant<int, 2>{});
+    else if (nt <= 4) run(std::integral_constant<int, 4>{});
+    else if (nt <= 6) run(std::integral_constant<int, 6>{});
+    else run(std::integral_constant<int, 8>{});
+  }
+}
+
+struct AttnArgs {
+  const uint16_t *q, *k, *v;           // [T][H*dh], [T][Hkv*dh], [T][Hkv*dh] of the block's own tokens
+  const uint16_t *k_cache, *v_cache;   // [B][Hkv][P][dh] cached positions (prefix, then suffix)
+  uint16_t* o;                         // [T][H*dh] per-head outputs
+  int B, N, H, Hkv, dh, P;
+  float scale;                         // 1 / sqrt(dh)
+};
+
+// One workgroup (four wavefronts) per (sequence, query head); each wavefront takes tiles
+// of 16 queries.  Scores and the weighted sum of values are bf16 MFMA contractions with
+// fp32 accumulation, laid out so that no operand needs a transpose between them:
+//   S^T = K Q^T    A = keys (16 per tile, straight from global memory), B = the 16 queries
+//                  -> lane l holds query l % 16, keys 4 (l / 16) .. + 3 of the tile
+//   O^T = V^T P^T  B = the weights of two score tiles as they sit in those registers (the
+//                  contraction only needs A and B to agree on which key a slot means),
+//                  A = values transposed in LDS, read with that same key order
+//                  -> lane l holds query l % 16, coordinates 4 (l / 16) .. + 3 of the tile
+// The softmax is two passes over the keys (maximum first, then weights and sums, the
+// scores recomputed - a handful of MFMAs) instead of a running rescale; weights are
+// rounded to bf16 for the second contraction, their sum is kept in fp32.  Sums run in a
+// fixed order, so results are reproducible.
+__global__ __launch_bounds__(256) void attention_core_kernel(AttnArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  uint16_t* vt = reinterpret_cast<uint16_t*>(smem_raw);  // [ndt * 16][ldv]: values, transposed
+  const int N = a.N, dh = a.dh, P = a.P, nk = a.P + a.N;
+  const int nkp = (nk + 31) & ~31, ldv = nkp + 4;
+  const int ndt = (dh + 15) / 16, nks = (dh + 31) / 32, nkt = (nk + 15) / 16;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
+  const int g = h / (a.H / a.Hkv);
+  const size_t cbase = (static_cast<size_t>(b) * a.Hkv + g) * P * dh;
+  const uint16_t* kc = a.k_cache + cbase;  // cached keys / values of this head (unused if P == 0)
+  const uint16_t* vc = a.v_cache + cbase;
+  const size_t brow = static_cast<size_t>(b) * N * a.Hkv * dh + static_cast<size_t>(g) * dh;
+  const uint16_t* kb = a.k + brow;         // the block's own keys / values, row stride Hkv * dh
+  const uint16_t* vb = a.v + brow;
+  const int bstride = a.Hkv * dh;
+  // values -> LDS, transposed; key slots beyond the window hold zeros (their weights are
+  // zero too, but 0 x garbage could be NaN)
+  const int vec = dh / 8;
+  for (int i = tid; i < nkp * vec; i += 256) {
+    const int j = i / vec, c = (i % vec) * 8;
+    uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+    if (j < nk) {
+      const uint16_t* src = j < P ? vc + static_cast<size_t>(j) * dh : vb + static_cast<size_t>(j - P) * bstride;
+      raw = *reinterpret_cast<const uint4*>(src + c);
+    }
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      vt[(c + 2 * q) * ldv + j] = static_cast<uint16_t>(w[q] & 0xffffu);
+      vt[(c + 2 * q + 1) * ldv + j] = static_cast<uint16_t>(w[q] >> 16);
+    }
+  }
+  __syncthreads();
+  const int col = lane & 15, grp = lane >> 4;
+  const float neg_inf = -__builtin_inff();
+  auto key_row = [&](int j) -> const uint16_t* {
+    return j < P ? kc + static_cast<size_t>(j) * dh : kb + static_cast<size_t>(j - P) * bstride;
+  };
+  auto load8 = [&](const uint16_t* row, int s) -> bf16x8 {  // elements 32 s + 8 grp .. + 7, zeros past dh
+    const int e = 32 * s + 8 * grp;
+    uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+    if (e < dh) raw = *reinterpret_cast<const uint4*>(row + e);
+    return __builtin_bit_cast(bf16x8, raw);
+  };
+  for (int qt = wave; qt * 16 < N; qt += 4) {
+    const int n = min(qt * 16 + col, N - 1);  // rows past the block repeat the last query, not stored
+    const uint16_t* qrow = a.q + (static_cast<size_t>(b) * N + n) * (a.H * dh) + static_cast<size_t>(h) * dh;
+    bf16x8 qf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) qf[s] = s < nks ? load8(qrow, s) : bf16x8{};
+    auto score_tile = [&](int t) -> f32x4 {  // keys 16 t + 4 grp + r for this lane's query
+      const uint16_t* krow = key_row(min(16 * t + col, nk - 1));
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        if (s < nks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(load8(krow, s), qf[s], acc, 0, 0, 0);
+      return acc;
+    };
+    float mx = neg_inf;
+    for (int t = 0; t < nkt; ++t) {
+      const f32x4 sc = score_tile(t);
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (16 * t + 4 * grp + r < nk) mx = fmaxf(mx, sc[r]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    f32x4 oacc[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float lsum = 0.f;
+    for (int c = 0; c < nkp / 32; ++c) {
+      u16x4 pw[2];
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int t = 2 * c + half;
+        f32x4 sc = {0.f, 0.f, 0.f, 0.f};
+        if (t < nkt) sc = score_tile(t);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float pr = 16 * t + 4 * grp + r < nk ? expf((sc[r] - mx) * a.scale) : 0.f;
+          lsum += pr;
+          pw[half][r] = f32_to_bf16_bits(pr);
+        }
+      }
+      struct { u16x4 lo, hi; } pp = {pw[0], pw[1]};
+      const bf16x8 pb = __builtin_bit_cast(bf16x8, pp);
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        if (dt < ndt) {
+          const uint16_t* vrow = vt + (16 * dt + col) * ldv + 32 * c + 4 * grp;
+          struct { u16x4 lo, hi; } vv = {*reinterpret_cast<const u16x4*>(vrow),
+                                         *reinterpret_cast<const u16x4*>(vrow + 16)};
+          oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), pb, oacc[dt], 0, 0, 0);
+        }
+      }
+    }
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
+    const float inv = 1.0f / lsum;
+    if (qt * 16 + col < N) {
+      uint16_t* orow = a.o + (static_cast<size_t>(b) * N + n) * (a.H * dh) + static_cast<size_t>(h) * dh;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const int d0 = 16 * dt + 4 * grp;
+        if (d0 < dh) {
+          u16x4 ob;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) ob[r] = f32_to_bf16_bits(oacc[dt][r] * inv);
+          *reinterpret_cast<u16x4*>(orow + d0) = ob;
+        }
+      }
+    }
+  }
+}
+
+// Scratch of one attention sub-layer (bytes from a 256-byte aligned base): q, k, v and the
+// per-head outputs of the block's tokens, bf16.
+AttnLayout attn_layout(const des_shape_t& s, const des_attn_shape_t& t) {
+  const size_t T = static_cast<size_t>(s.n_seqs) * s.n_tokens;
+  AttnLayout l;
+  size_t p = 0;
+  l.q = p; p = align256(p + 2 * T * t.n_heads * t.head_dim);
+  l.k = p; p = align256(p + 2 * T * t.n_kv_heads * t.head_dim);
+  l.v = p; p = align256(p + 2 * T * t.n_kv_heads * t.head_dim);
+  l.o = p; p = align256(p + 2 * T * t.n_heads * t.head_dim);
+  l.total = p;
+  return l;
+}
+
+size_t attn_core_lds(const des_shape_t& s, const des_attn_shape_t& t) {
+  // the head's values, transposed: (dh rounded up to 16) rows of (window rounded up to 32) + 4 bf16
+  const size_t nk = static_cast<size_t>(attn_cached(t)) + s.n_tokens;
+  const size_t nkp = (nk + 31) / 32 * 32;
+  return static_cast<size_t>((t.head_dim + 15) / 16 * 16) * (nkp + 4) * 2;
+}
+
+template <int LW>
+static void launch_linear(const LinearArgs& a, int kernel_id, hipStream_t st) {
+  int blocks = 0;
+  for (int m = 0; m < a.n_mats; ++m) blocks += (a.fout[m] / 32 + LW - 1) / LW;
+  const dim3 g(blocks), b(LW * kWave);
+  if (a.Din == 2048) launch(kernel_id, linear_lds_kernel<LW, 2048>, g, b, 0, st, a);
+  else launch(kernel_id, linear_lds_kernel<LW, 0>, g, b, 0, st, a);
+}
+
+int launch_attention(const des_shape_t& s, const des_attn_shape_t& t, const void* x, const void* wq,
+                     const void* wk, const void* wv, const void* wo, const void* k_cache,
+                     const void* v_cache, void* y, char* ws, hipStream_t st) {
+  const AttnLayout l = attn_layout(s, t);
+  const int T = s.n_seqs * s.n_tokens;
+  const int HD = t.n_heads * t.head_dim, KD_ = t.n_kv_heads * t.head_dim;
+  LinearArgs p{};
+  p.in = static_cast<const uint16_t*>(x);
+  p.w[0] = static_cast<const uint16_t*>(wq);
+  p.w[1] = static_cast<const uint16_t*>(wk);
+  p.w[2] = static_cast<const uint16_t*>(wv);
+  p.out[0] = reinterpret_cast<uint16_t*>(ws + l.q);
+  p.out[1] = reinterpret_cast<uint16_t*>(ws + l.k);
+  p.out[2] = reinterpret_cast<uint16_t*>(ws + l.v);
+  p.fout[0] = HD; p.fout[1] = KD_; p.fout[2] = KD_;
+  p.n_mats = 3; p.T = T; p.Din = s.hidden; p.res = nullptr;
+  launch_linear<4>(p, kKAttnProj, st);
+
+  AttnArgs c{};
+  c.q = p.out[0]; c.k = p.out[1]; c.v = p.out[2];
+  c.k_cache = static_cast<const uint16_t*>(k_cache);
+  c.v_cache = static_cast<const uint16_t*>(v_cache);
+  c.o = reinterpret_cast<uint16_t*>(ws + l.o);
+  c.B = s.n_seqs; c.N = s.n_tokens; c.H = t.n_heads; c.Hkv = t.n_kv_heads; c.dh = t.head_dim;
+  c.P = attn_cached(t);
+  c.scale = 1.0f / sqrtf(static_cast<float>(t.head_dim));
+  const size_t lds = attn_core_lds(s, t);
+  static bool big_lds_set = false;  // (the limit is a property of the function, set once)
+  if (lds > 48 * 1024 && !big_lds_set) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_core_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return hip_fail(e, "attention LDS size");
+    big_lds_set = true;
+  }
+  launch(kKAttnCore, attention_core_kernel, dim3(s.n_seqs * t.n_heads), dim3(256), lds, st, c);
+
+  LinearArgs o{};
+  o.in = c.o;
+  o.w[0] = static_cast<const uint16_t*>(wo);
+  o.out[0] = static_cast<uint16_t*>(y);
+  o.fout[0] = s.hidden;
+  o.n_mats = 1; o.T = T; o.Din = HD;
+  o.res = s.residual ? static_cast<const uint16_t*>(x) : nullptr;
+  launch_linear<4>(o, kKAttnOut, st);
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? DES_OK : hip_fail(e, "attention launch");
+}
+
+}  // namespace des

@@ -187,6 +187,15 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
                const void* w_down, const void* ws_gate, const void* ws_up, const void* ws_down,
                const int32_t* topk_idx, const float* topk_w, int32_t* n_unique, void* y, char* ws,
                unsigned long long epoch, hipStream_t st);
+// Attention sub-layer (des_attention.hip): scratch layout, LDS need of the per-head
+// kernel, and the three launches.
+struct AttnLayout { size_t q, k, v, o, total; };
+inline int attn_cached(const des_attn_shape_t& t) { return t.n_prefix + t.n_suffix; }
+AttnLayout attn_layout(const des_shape_t& s, const des_attn_shape_t& t);
+size_t attn_core_lds(const des_shape_t& s, const des_attn_shape_t& t);
+int launch_attention(const des_shape_t& s, const des_attn_shape_t& t, const void* x, const void* wq,
+                     const void* wk, const void* wv, const void* wo, const void* k_cache,
+                     const void* v_cache, void* y, char* ws, hipStream_t st);
 int launch_pack(const void* src, void* dst, int64_t n_mats, int rows, int cols, hipStream_t st);
 int launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st);
 
@@ -194,7 +203,7 @@ int hip_fail(hipError_t e, const char* what);  // records text, returns DES_ERR_
 
 // Kernel ids for the optional per-kernel event timing (des_kernel_timing_*).
 enum KernelId { kKRouter = 0, kKSoftmax, kKSelect, kKPermute, kKGateUp, kKDown, kKCombine, kKPack,
-                kKRouting, kKFfn, kKProbe, kKCount };
+                kKRouting, kKFfn, kKProbe, kKAttnProj, kKAttnCore, kKAttnOut, kKCount };
 extern bool g_timing_on;
 // Creates the event pair of one timed launch and remembers it under kernel_id.
 bool timing_events(int kernel_id, hipEvent_t* start, hipEvent_t* stop);

@@ -965,7 +965,6 @@ __device__ void publish_empty(const RoutingArgs& a, int n_flags) {
 template <int LPT>
 __device__ void permute_small(const RoutingArgs& a, char* smem) {
   using L = SelLds<LPT>;
-  constexpr int MP = L::MP;
   const uint32_t* s_mask = reinterpret_cast<const uint32_t*>(smem + L::mask);
   int* s_off = reinterpret_cast<int*>(smem + L::off);
   int* s_liv = reinterpret_cast<int*>(smem + L::liv);

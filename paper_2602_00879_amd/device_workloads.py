@@ -55,3 +55,25 @@ def make_stack(cfg: W.LayerConfig, device="cuda") -> Dict[str, torch.Tensor]:
             bias[l] = W.zipf_bias(M, cfg.zipf_s, np.random.default_rng([cfg.seed, l]))
     out["bias"] = torch.from_numpy(bias).to(device) if cfg.zipf_s > 0 else None
     return out
+
+
+def make_decoder_attention(cfg: W.LayerConfig, attn: W.AttnConfig, device="cuda") -> Dict[str, torch.Tensor]:
+    """Layer-stacked attention tensors for `cfg.n_layers` decoder layers: wq [L, H*dh, D],
+    wk, wv [L, Hkv*dh, D], wo [L, D, H*dh], k_cache, v_cache [L, B, Hkv, P, dh].  As for
+    w_down in make_stack, the projection that writes into the residual stream (wo) is
+    drawn with std 0.02 / sqrt(2 L)."""
+    L, B, D = cfg.n_layers, cfg.n_seqs, cfg.hidden
+    H, G, dh, P = attn.n_heads, attn.n_kv_heads, attn.head_dim, attn.n_prefix + attn.n_suffix
+    assert (attn.n_seqs, attn.n_tokens, attn.hidden) == (cfg.n_seqs, cfg.n_tokens, cfg.hidden)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(attn.seed * 100003 + 29)
+    o_std = 0.02 / float(np.sqrt(2.0 * L)) if L > 1 else 0.02
+    out = {
+        "wq": _randn_bf16((L, H * dh, D), 0.02, gen, device),
+        "wk": _randn_bf16((L, G * dh, D), 0.02, gen, device),
+        "wv": _randn_bf16((L, G * dh, D), 0.02, gen, device),
+        "wo": _randn_bf16((L, D, H * dh), o_std, gen, device),
+        "k_cache": _randn_bf16((L, B, G, P, dh), 1.0, gen, device),
+        "v_cache": _randn_bf16((L, B, G, P, dh), 1.0, gen, device),
+    }
+    return out

@@ -126,6 +126,53 @@ def make_layer(cfg: LayerConfig, layer: int = 0, with_x: bool = True) -> Dict[st
     return out
 
 
+@dataclass(frozen=True)
+class AttnConfig:
+    """Attention sub-layer around the MoE layer (bf16): H query heads, Hkv key/value
+    heads of width dh, n_prefix + n_suffix cached positions (Sec. 5.1 uses 16 + 16)."""
+    name: str
+    n_seqs: int
+    n_tokens: int
+    hidden: int
+    n_heads: int
+    n_kv_heads: int
+    head_dim: int
+    n_prefix: int
+    n_suffix: int
+    seed: int
+
+
+# The per-layer attention shape that goes with the 2048-wide, 128-expert MoE layer of the
+# benchmark definition (32 query heads, 4 key/value heads of width 128), and small ones.
+ATTN_CONFIGS: Dict[str, AttnConfig] = {
+    "attn_block32": AttnConfig("attn_block32", 1, 32, 2048, 32, 4, 128, 16, 16, 31),
+    "attn_batch8": AttnConfig("attn_batch8", 8, 32, 2048, 32, 4, 128, 16, 16, 32),
+    "attn_small": AttnConfig("attn_small", 1, 8, 256, 4, 2, 64, 3, 2, 33),
+    "attn_nocache": AttnConfig("attn_nocache", 3, 20, 256, 4, 4, 32, 0, 0, 34),
+    "attn_ragged": AttnConfig("attn_ragged", 2, 70, 384, 8, 2, 48, 5, 9, 35),
+    "attn_one_token": AttnConfig("attn_one_token", 1, 1, 128, 2, 1, 64, 7, 0, 36),
+}
+
+
+def make_attention(cfg: AttnConfig, layer: int = 0, with_x: bool = True) -> Dict[str, Optional[np.ndarray]]:
+    """bf16 tensors of one attention sub-layer, seeded by (cfg.seed, layer): x [B, N, D]
+    N(0, 1); wq [H*dh, D], wk, wv [Hkv*dh, D], wo [D, H*dh] N(0, 0.02); cached keys
+    and values [B, Hkv, P, dh] N(0, 1) (the scale a projection of N(0, 1) hidden states
+    by N(0, 0.02) weights of this width has, to the nearest power of ten)."""
+    rng = np.random.default_rng([cfg.seed, layer, 7])
+    B, N, D, H, G, dh = cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+    P = cfg.n_prefix + cfg.n_suffix
+    out: Dict[str, Optional[np.ndarray]] = {}
+    out["x"] = _normal(rng, (B, N, D), 1.0, "bf16") if with_x else None
+    out["wq"] = _normal(rng, (H * dh, D), 0.02, "bf16")
+    out["wk"] = _normal(rng, (G * dh, D), 0.02, "bf16")
+    out["wv"] = _normal(rng, (G * dh, D), 0.02, "bf16")
+    out["wo"] = _normal(rng, (D, H * dh), 0.02, "bf16")
+    out["k_cache"] = _normal(rng, (B, G, P, dh), 1.0, "bf16")
+    out["v_cache"] = _normal(rng, (B, G, P, dh), 1.0, "bf16")
+    return out
+
+
 def make_logits(n_tokens: int, n_experts: int, seed: int, zipf_s: float = 0.0,
                 scale: float = 1.0) -> np.ndarray:
     """Synthetic fp32 router logits [N, M] for routing-only tests."""

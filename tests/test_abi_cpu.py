@@ -114,6 +114,42 @@ def test_null_and_workspace_errors():
     assert L.des_moe_forward(ctypes.byref(s), *alias, ctypes.c_size_t(1 << 40), None) == -2
 
 
+def test_attention_shapes_are_checked_on_the_host():
+    s = _shape()
+    ok = B.make_attn_shape(32, 4, 128, 16, 16)
+    n = B.des_attention_workspace_bytes(s, ok)
+    T = 32
+    assert n >= T * (32 * 128 * 2 + 2 * 4 * 128) * 2 and n % 256 == 0
+    assert B.des_decoder_workspace_bytes(s, ok) >= n + B.des_stack_workspace_bytes(s)
+    for bad in (B.make_attn_shape(32, 5, 128, 16, 16),     # heads do not split into groups
+                B.make_attn_shape(32, 4, 100, 16, 16),     # head_dim not a multiple of 8
+                B.make_attn_shape(3, 3, 8, 0, 0),          # H * dh not a multiple of 128
+                B.make_attn_shape(32, 4, 128, -1, 0),
+                B.make_attn_shape(32, 4, 128, 4000, 200),  # window beyond the limit
+                B.make_attn_shape(16, 16, 256, 16, 16),    # head_dim beyond 128
+                B.make_attn_shape(32, 4, 128, 600, 200)):  # one head's window exceeds LDS
+        assert B.des_attention_workspace_bytes(s, bad) == 0
+        assert B.des_decoder_workspace_bytes(s, bad) == 0
+    assert B.des_attention_workspace_bytes(_shape(dtype="f32"), ok) == 0
+    L = B.lib()
+    a = [ctypes.c_void_p(256 * (i + 1)) for i in range(9)]      # never dereferenced
+    call = lambda sh, at, args, nbytes: L.des_block_attention(ctypes.byref(sh), ctypes.byref(at), *args,
+                                                              ctypes.c_size_t(nbytes), None)
+    assert call(_shape(dtype="f32"), ok, a, 1 << 40) == -4
+    assert call(s, ok, a, 16) == -5
+    no_cache = list(a)
+    no_cache[5] = None
+    assert call(s, ok, no_cache, 1 << 40) == -1
+    alias = list(a)
+    alias[7] = alias[0]
+    assert call(s, ok, alias, 1 << 40) == -2
+    d = [ctypes.c_void_p(256 * (i + 1)) for i in range(19)]
+    assert L.des_decoder_stack_forward(ctypes.byref(s), ctypes.byref(ok), 0, *d, ctypes.c_size_t(1 << 40), None) == -2
+    assert L.des_decoder_stack_forward(ctypes.byref(s), ctypes.byref(ok), 2, *d, ctypes.c_size_t(16), None) == -5
+    d[0] = None
+    assert L.des_decoder_stack_forward(ctypes.byref(s), ctypes.byref(ok), 2, *d, ctypes.c_size_t(1 << 40), None) == -1
+
+
 def test_coreset_from_beta_matches_table_1_rounding():
     """M_core = floor(beta * M): the sizes printed in Table 1 of the paper, and the
     oracle's exact-fraction version on a grid of decimal budgets."""

@@ -1,4 +1,5 @@
-"""Checks on the generated gfx950 code of the FFN kernels (no GPU needed).
+"""Checks on the generated gfx950 code of the FFN kernels and of the attention
+projections, which share the streaming building block (no GPU needed).
 
 The kernels for blocks of more than 32 tokens issue their loads from inline asm
 and wait for them with explicit counts.  The compiler neither inserts the wait
@@ -24,10 +25,10 @@ import pytest
 from paper_2602_00879_amd import build as B
 
 
-@pytest.fixture(scope="module")
-def ffn_asm(tmp_path_factory):
-    out = str(tmp_path_factory.mktemp("isa") / "des_ffn.s")
-    B.device_asm("des_ffn.hip", out)
+@pytest.fixture(scope="module", params=["des_ffn.hip", "des_attention.hip"])
+def ffn_asm(request, tmp_path_factory):
+    out = str(tmp_path_factory.mktemp("isa") / (request.param + ".s"))
+    B.device_asm(request.param, out)
     return open(out).read()
 
 
@@ -149,6 +150,7 @@ def test_no_read_of_an_asynchronously_loaded_register_before_its_wait(ffn_asm):
     copy on the back edge."""
     errors = []
     n = 0
+    _TRACKED[0] = 0
     for m in re.finditer(r"\n(_ZN3des\w*lds_kernel\w+):[^\n]*\n(.*?)\n\s*s_endpgm", ffn_asm, re.S):
         n += 1
         lines = [l.split(";")[0].strip() for l in m.group(2).split("\n")]
@@ -165,6 +167,6 @@ def test_no_read_of_an_asynchronously_loaded_register_before_its_wait(ffn_asm):
             if tgt in label_at and label_at[tgt] < i:  # a back edge: once more round the loop
                 body = [x for x in lines[label_at[tgt]:i + 1] if not x.endswith(":")]
                 _scan_pending_reads(m.group(1), body, list(pending), errors)
-    assert n > 0 and _TRACKED[0] > 100
+    assert n > 0 and _TRACKED[0] > 40
     assert not errors, "\n".join(errors[:10])
 
