@@ -338,6 +338,8 @@ def other_configs(args, torch, B, W, dev, cfg2, layer2, replicas2, w_router2, bi
     del reps3, base3, shared3, layer3
     torch.cuda.empty_cache()
 
+    res["decoder_step"] = decoder_breakdown(torch, B, W, dev)
+
     # ---- 48-layer stack: needs ~60 GB for the weights and a transient for packing
     free, _ = torch.cuda.mem_get_info()
     if free < 75e9:
@@ -373,6 +375,67 @@ def other_configs(args, torch, B, W, dev, cfg2, layer2, replicas2, w_router2, bi
                       "floor_ms": round(floor_us(ub) / 1e3, 3),
                       "pct_of_hbm_peak_whole_step": round(100.0 * floor_us(ub) / (ms * 1e3), 1)}
     return res
+
+
+def decoder_breakdown(torch, B, W, dev, n_layers=12, steps=20, warm=3):
+    """Where the time of a decoding step goes once attention sits around the MoE layers
+    (the paper's Fig. 2 left, re-measured here with synthetic weights): a stack of
+    `n_layers` decoder layers (attention with 32 query / 4 key-value heads of width 128
+    over 16 + 16 cached positions and the block, then the 128-expert MoE layer), one
+    block of 32 tokens, vanilla routing against DES-Vote C = 32.  Every layer has its own
+    weights (14.5 GB for 12 layers), so each is read cold once per step."""
+    from paper_2602_00879_amd import device_workloads as DW
+    cfg = W.CONFIGS["m128_zipf"].with_(n_layers=n_layers, seed=61)
+    acfg = W.ATTN_CONFIGS["attn_block32"]
+    st = DW.make_stack(cfg, dev)
+    at = DW.make_decoder_attention(cfg, acfg, dev)
+    for k in ("w_gate", "w_up", "w_down"):
+        for l in range(n_layers):
+            st[k][l] = B.des_pack_expert_weights(st[k][l])
+    torch.cuda.synchronize()
+    attn = B.make_attn_shape(acfg.n_heads, acfg.n_kv_heads, acfg.head_dim, acfg.n_prefix, acfg.n_suffix)
+    attn_bytes = 2 * (2 * cfg.hidden * acfg.n_heads * acfg.head_dim + 2 * cfg.hidden * acfg.n_kv_heads * acfg.head_dim)
+    per = 3 * cfg.hidden * cfg.ffn * 2
+    rows = []
+    for mode in ("vanilla", "vote"):
+        shape = B.make_shape(cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k, cfg.coreset,
+                             mode, cfg.dtype, weight_layout=B.DES_LAYOUT_PACKED, residual=1)
+        bufs = B.DecoderBuffers(shape, attn, n_layers, dev, torch.bfloat16)
+
+        def step():
+            B.des_decoder_stack_forward(shape, attn, n_layers, st["x"], at["wq"], at["wk"], at["wv"], at["wo"],
+                                        at["k_cache"], at["v_cache"], st["w_router"], st["bias"], st["w_gate"],
+                                        st["w_up"], st["w_down"], buffers=bufs)
+
+        for _ in range(warm):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        us_layer = (time.perf_counter() - t0) * 1e6 / steps / n_layers
+        B.des_kernel_timing_enable(True)
+        for _ in range(5):
+            step()
+        torch.cuda.synchronize()
+        kt = B.des_kernel_timing_read()
+        B.des_kernel_timing_enable(False)
+        k_us = {k: v[0] * 1e3 / v[1] for k, v in kt.items() if v[1] > 0}
+        a_us = sum(k_us.get(k, 0.0) for k in ("attn_proj", "attn_core", "attn_out"))
+        m_us = sum(k_us.get(k, 0.0) for k in ("routing", "gateup", "down", "combine"))
+        U = float(bufs.n_unique.float().mean())
+        rows.append({"mode": mode, "us_per_layer": round(us_layer, 2), "n_unique_mean": round(U, 1),
+                     "kernel_us": {k: round(v, 2) for k, v in k_us.items() if k.startswith("attn") or k in
+                                   ("routing", "gateup", "down", "combine")},
+                     "attention_us": round(a_us, 2), "moe_us": round(m_us, 2),
+                     "moe_share_of_kernel_time": round(m_us / (a_us + m_us), 3),
+                     "floor_us": round(floor_us(U * per + attn_bytes), 2),
+                     "attention_floor_us": round(floor_us(attn_bytes), 2)})
+    del st, at
+    torch.cuda.empty_cache()
+    return {"workload": f"{n_layers} decoder layers (attention 32/4 heads x 128 over 16+16 cached + block, then "
+                        "128-expert MoE), 1 block x 32 tokens, per layer", "rows": rows}
 
 
 def bench_selection(args, torch, B, W, dev):

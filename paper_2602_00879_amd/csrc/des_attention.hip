@@ -27,9 +27,9 @@ struct LinearArgs {
 };
 
 // out[m][t][f] = sum_d in[t][d] * w[m][f][d].  A workgroup of LW wavefronts owns LW pairs
-// of 16-row weight tiles of one matrix and walks the token rows in passes of up to 128
-// (the weights are streamed once per pass).  KD = the reduction length if it is the
-// unrolled one (2048), else 0.
+// of 16-row weight tiles of one matrix and up to 128 token rows (blockIdx.y names which;
+// the weights are streamed once per 128 rows).  KD = the reduction length if it is one
+// of the unrolled ones (2048, 4096), else 0.
 template <int LW, int KD>
 __global__ __launch_bounds__(LW* kWave, 2) void linear_lds_kernel(LinearArgs a) {
   constexpr int kRows = 128;
@@ -53,7 +53,8 @@ __global__ __launch_bounds__(LW* kWave, 2) void linear_lds_kernel(LinearArgs a) 
   const uint16_t* in = uniform_ptr(a.in);
   uint16_t* out = a.out[m];
   const uint16_t* res = m == 0 ? a.res : nullptr;
-  for (int g0 = 0; g0 < a.T; g0 += kRows) {
+  {  // one pass of up to 128 token rows per workgroup (blockIdx.y)
+    const int g0 = blockIdx.y * kRows;
     const int rows = min(kRows, a.T - g0);
     const int nt = (rows + 15) / 16;
     auto row_off = [&](int r) { return (g0 + r) * Din; };
@@ -99,6 +100,111 @@ __global__ __launch_bounds__(LW* kWave, 2) void linear_lds_kernel(LinearArgs a) 
   }
 }
 
+// The same projection for blocks of at most 32 token rows, where the weights are a pure
+// stream and what matters is how many wavefronts pull on it at once: a workgroup owns RT
+// 16-row weight tiles, its wavefronts split the reduction dimension (each streams a
+// contiguous run of every row straight into MFMA A operands, two stages of U k-steps
+// in flight; the token rows come from L2 as the B operand, each fragment used for the RT
+// tiles), and the partial tiles are added through LDS in wavefront order, so the result
+// does not depend on timing.
+template <int RT, int NT>
+__global__ __launch_bounds__(512) void linear_splitk_kernel(LinearArgs a) {
+  constexpr int U = RT >= 4 ? 2 : 4;
+  __shared__ __align__(16) float part[8 * RT * NT * 256];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n_waves = blockDim.x >> 6;
+  int grp_i = blockIdx.x, m = 0;
+  for (; m < a.n_mats; ++m) {  // which matrix this workgroup belongs to
+    const int per = (a.fout[m] / 16 + RT - 1) / RT;
+    if (grp_i < per) break;
+    grp_i -= per;
+  }
+  if (m >= a.n_mats) return;
+  const int fout = a.fout[m], Din = a.Din;
+  const int n_tiles = fout / 16;
+  const int kper = Din / n_waves, nks = kper / 32;  // the host makes kper a multiple of 32
+  const int col = lane & 15, grp = lane >> 4;
+  const uint16_t* wp[RT];
+#pragma unroll
+  for (int r = 0; r < RT; ++r)  // a tile past the matrix repeats the last one, dropped at the store
+    wp[r] = a.w[m] + (static_cast<size_t>(min(grp_i * RT + r, n_tiles - 1)) * 16 + col) * Din + wave * kper + grp * 8;
+  const uint16_t* xp[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i)  // rows past the block repeat the last token, dropped at the store
+    xp[i] = a.in + static_cast<size_t>(min(i * 16 + col, a.T - 1)) * Din + wave * kper + grp * 8;
+  f32x4 acc[RT][NT];
+#pragma unroll
+  for (int r = 0; r < RT; ++r)
+#pragma unroll
+    for (int i = 0; i < NT; ++i) acc[r][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  bf16x8 aw[2][U][RT], bx[2][U][NT];
+  auto load = [&](int ks, auto stage) {
+    constexpr int st = decltype(stage)::value;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool in = ks + u < nks;
+      bf16x8 z;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) z[q] = static_cast<__bf16>(0.0f);
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+        aw[st][u][r] = in ? __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(wp[r] + (ks + u) * 32)) : z;
+#pragma unroll
+      for (int i = 0; i < NT; ++i)
+        bx[st][u][i] = in ? *reinterpret_cast<const bf16x8*>(xp[i] + (ks + u) * 32) : z;
+    }
+  };
+  auto compute = [&](auto stage) {
+    constexpr int st = decltype(stage)::value;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+          acc[r][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aw[st][u][r], bx[st][u][i], acc[r][i], 0, 0, 0);
+  };
+  load(0, S0{});
+  for (int ks = 0; ks < nks; ks += 2 * U) {
+    load(ks + U, S1{});
+    compute(S0{});
+    load(ks + 2 * U, S0{});
+    compute(S1{});
+  }
+#pragma unroll
+  for (int r = 0; r < RT; ++r)
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+      *reinterpret_cast<f32x4*>(part + (((wave * RT + r) * NT + i) * 64 + lane) * 4) = acc[r][i];
+  __syncthreads();
+  // wavefront w finishes the tiles w, w + n_waves, ... of the workgroup's RT x NT
+  uint16_t* out = a.out[m];
+  const uint16_t* res = m == 0 ? a.res : nullptr;
+  for (int t = wave; t < RT * NT; t += n_waves) {
+    const int r = t / NT, i = t % NT;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int w = 0; w < n_waves; ++w) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(part + (((w * RT + r) * NT + i) * 64 + lane) * 4);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) sum[q] += v[q];
+    }
+    const int tok = i * 16 + col, tile = grp_i * RT + r;
+    if (tok < a.T && tile < n_tiles) {
+      const size_t o = static_cast<size_t>(tok) * fout + tile * 16 + 4 * grp;
+      if (res != nullptr) {
+        const u16x4 rv = *reinterpret_cast<const u16x4*>(res + o);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sum[q] += bf16_bits_to_f32(rv[q]);
+      }
+      u16x4 ob;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) ob[q] = f32_to_bf16_bits(sum[q]);
+      *reinterpret_cast<u16x4*>(out + o) = ob;
+    }
+  }
+}
+
 struct AttnArgs {
   const uint16_t *q, *k, *v;           // [T][H*dh], [T][Hkv*dh], [T][Hkv*dh] of the block's own tokens
   const uint16_t *k_cache, *v_cache;   // [B][Hkv][P][dh] cached positions (prefix, then suffix)
@@ -116,8 +222,9 @@ struct AttnArgs {
 //                  contraction only needs A and B to agree on which key a slot means),
 //                  A = values transposed in LDS, read with that same key order
 //                  -> lane l holds query l % 16, coordinates 4 (l / 16) .. + 3 of the tile
-// The softmax is two passes over the keys (maximum first, then weights and sums, the
-// scores recomputed - a handful of MFMAs) instead of a running rescale; weights are
+// The softmax is two passes over the keys (maximum first, then weights and sums; the
+// scores are recomputed - a handful of MFMAs - when the window exceeds 64 positions)
+// instead of a running rescale; weights are
 // rounded to bf16 for the second contraction, their sum is kept in fp32.  Sums run in a
 // fixed order, so results are reproducible.
 __global__ __launch_bounds__(256) void attention_core_kernel(AttnArgs a) {
@@ -136,24 +243,6 @@ __global__ __launch_bounds__(256) void attention_core_kernel(AttnArgs a) {
   const uint16_t* kb = a.k + brow;         // the block's own keys / values, row stride Hkv * dh
   const uint16_t* vb = a.v + brow;
   const int bstride = a.Hkv * dh;
-  // values -> LDS, transposed; key slots beyond the window hold zeros (their weights are
-  // zero too, but 0 x garbage could be NaN)
-  const int vec = dh / 8;
-  for (int i = tid; i < nkp * vec; i += 256) {
-    const int j = i / vec, c = (i % vec) * 8;
-    uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-    if (j < nk) {
-      const uint16_t* src = j < P ? vc + static_cast<size_t>(j) * dh : vb + static_cast<size_t>(j - P) * bstride;
-      raw = *reinterpret_cast<const uint4*>(src + c);
-    }
-    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      vt[(c + 2 * q) * ldv + j] = static_cast<uint16_t>(w[q] & 0xffffu);
-      vt[(c + 2 * q + 1) * ldv + j] = static_cast<uint16_t>(w[q] >> 16);
-    }
-  }
-  __syncthreads();
   const int col = lane & 15, grp = lane >> 4;
   const float neg_inf = -__builtin_inff();
   auto key_row = [&](int j) -> const uint16_t* {
@@ -165,56 +254,108 @@ __global__ __launch_bounds__(256) void attention_core_kernel(AttnArgs a) {
     if (e < dh) raw = *reinterpret_cast<const uint4*>(row + e);
     return __builtin_bit_cast(bf16x8, raw);
   };
-  for (int qt = wave; qt * 16 < N; qt += 4) {
-    const int n = min(qt * 16 + col, N - 1);  // rows past the block repeat the last query, not stored
+  // values -> LDS, transposed; key slots beyond the window hold zeros (their weights are
+  // zero too, but 0 x garbage could be NaN).  A thread's first four pieces are requested
+  // here and written after the first pass over the keys, which does not need them: the
+  // three kinds of loads (values, queries, keys) then share one round trip.
+  const int vec = dh / 8, n_piece = nkp * vec;
+  auto value_piece = [&](int i) -> uint4 {
+    const int j = i / vec, c = (i % vec) * 8;
+    if (i >= n_piece || j >= nk) return make_uint4(0u, 0u, 0u, 0u);
+    const uint16_t* src = j < P ? vc + static_cast<size_t>(j) * dh : vb + static_cast<size_t>(j - P) * bstride;
+    return *reinterpret_cast<const uint4*>(src + c);
+  };
+  auto store_piece = [&](int i, const uint4& raw) {
+    if (i >= n_piece) return;
+    const int j = i / vec, c = (i % vec) * 8;
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      vt[(c + 2 * q) * ldv + j] = static_cast<uint16_t>(w[q] & 0xffffu);
+      vt[(c + 2 * q + 1) * ldv + j] = static_cast<uint16_t>(w[q] >> 16);
+    }
+  };
+  uint4 vraw[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) vraw[q] = value_piece(tid + 256 * q);
+
+  bf16x8 qf[4];
+  f32x4 sc[4];
+  int n = 0;
+  float mx = neg_inf;
+  auto load_queries = [&](int qt) {
+    n = min(qt * 16 + col, N - 1);  // rows past the block repeat the last query, not stored
     const uint16_t* qrow = a.q + (static_cast<size_t>(b) * N + n) * (a.H * dh) + static_cast<size_t>(h) * dh;
-    bf16x8 qf[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) qf[s] = s < nks ? load8(qrow, s) : bf16x8{};
-    auto score_tile = [&](int t) -> f32x4 {  // keys 16 t + 4 grp + r for this lane's query
-      const uint16_t* krow = key_row(min(16 * t + col, nk - 1));
+  };
+  // scores of four key tiles at once, every key fragment requested before the first is
+  // used (one round trip to L2 instead of sixteen); lane: keys 16 t + 4 grp + r of its query
+  auto score_batch = [&](int t0) {
+    bf16x8 kf[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint16_t* krow = key_row(min(16 * (t0 + i) + col, nk - 1));
+#pragma unroll
+      for (int s = 0; s < 4; ++s) kf[i][s] = (s < nks && t0 + i < nkt) ? load8(krow, s) : bf16x8{};
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < 4; ++s)
-        if (s < nks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(load8(krow, s), qf[s], acc, 0, 0, 0);
-      return acc;
-    };
-    float mx = neg_inf;
-    for (int t = 0; t < nkt; ++t) {
-      const f32x4 sc = score_tile(t);
+        if (s < nks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i][s], qf[s], acc, 0, 0, 0);
+      sc[i] = acc;
+    }
+  };
+  auto first_pass = [&](int qt) {  // the largest score of each query
+    load_queries(qt);
+    mx = neg_inf;
+    for (int t0 = 0; t0 < nkt; t0 += 4) {
+      score_batch(t0);
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        if (16 * t + 4 * grp + r < nk) mx = fmaxf(mx, sc[r]);
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (16 * (t0 + i) + 4 * grp + r < nk) mx = fmaxf(mx, sc[i][r]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
+  };
+  auto second_pass = [&](int qt) {  // weights, their sum, the weighted values; store
     f32x4 oacc[8];
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float lsum = 0.f;
-    for (int c = 0; c < nkp / 32; ++c) {
-      u16x4 pw[2];
+    for (int t0 = 0; t0 < nkt; t0 += 4) {
+      if (nkt > 4) score_batch(t0);  // a window of at most 64 positions still has them
 #pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const int t = 2 * c + half;
-        f32x4 sc = {0.f, 0.f, 0.f, 0.f};
-        if (t < nkt) sc = score_tile(t);
+      for (int cc = 0; cc < 2; ++cc) {
+        const int c = t0 / 2 + cc;  // 32 keys: tiles 2 c and 2 c + 1
+        if (c * 32 < nkp) {
+          u16x4 pw[2];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float pr = 16 * t + 4 * grp + r < nk ? expf((sc[r] - mx) * a.scale) : 0.f;
-          lsum += pr;
-          pw[half][r] = f32_to_bf16_bits(pr);
-        }
-      }
-      struct { u16x4 lo, hi; } pp = {pw[0], pw[1]};
-      const bf16x8 pb = __builtin_bit_cast(bf16x8, pp);
+          for (int half = 0; half < 2; ++half) {
 #pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        if (dt < ndt) {
-          const uint16_t* vrow = vt + (16 * dt + col) * ldv + 32 * c + 4 * grp;
-          struct { u16x4 lo, hi; } vv = {*reinterpret_cast<const u16x4*>(vrow),
-                                         *reinterpret_cast<const u16x4*>(vrow + 16)};
-          oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), pb, oacc[dt], 0, 0, 0);
+            for (int r = 0; r < 4; ++r) {
+              const float pr =
+                  16 * (2 * c + half) + 4 * grp + r < nk ? expf((sc[2 * cc + half][r] - mx) * a.scale) : 0.f;
+              lsum += pr;
+              pw[half][r] = f32_to_bf16_bits(pr);
+            }
+          }
+          struct { u16x4 lo, hi; } pp = {pw[0], pw[1]};
+          const bf16x8 pb = __builtin_bit_cast(bf16x8, pp);
+#pragma unroll
+          for (int dt = 0; dt < 8; ++dt) {
+            if (dt < ndt) {
+              const uint16_t* vrow = vt + (16 * dt + col) * ldv + 32 * c + 4 * grp;
+              struct { u16x4 lo, hi; } vv = {*reinterpret_cast<const u16x4*>(vrow),
+                                             *reinterpret_cast<const u16x4*>(vrow + 16)};
+              oacc[dt] =
+                  __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), pb, oacc[dt], 0, 0, 0);
+            }
+          }
         }
       }
     }
@@ -234,6 +375,17 @@ __global__ __launch_bounds__(256) void attention_core_kernel(AttnArgs a) {
         }
       }
     }
+  };
+
+  const bool has_tile = wave * 16 < N;
+  if (has_tile) first_pass(wave);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) store_piece(tid + 256 * q, vraw[q]);
+  for (int i = tid + 1024; i < n_piece; i += 256) store_piece(i, value_piece(i));
+  __syncthreads();
+  for (int qt = wave; qt * 16 < N; qt += 4) {
+    if (qt != wave) first_pass(qt);
+    second_pass(qt);
   }
 }
 
@@ -260,10 +412,35 @@ size_t attn_core_lds(const des_shape_t& s, const des_attn_shape_t& t) {
 
 template <int LW>
 static void launch_linear(const LinearArgs& a, int kernel_id, hipStream_t st) {
+  if (a.T <= 32) {
+    // Wavefronts per workgroup (k-slices): a whole number of 32-element steps each, at
+    // least 256 reduction elements per row, at most 8.  Row tiles per workgroup: two halve
+    // the token-row traffic from L2, which costs as much as the weight stream here
+    // (measured on the 2048-wide layer: q/k/v 13.6 us against 17.2 us with one), but only
+    // while the workgroups still cover most compute units (output projection, 128 tiles:
+    // 16 us with one tile per workgroup, 21 us with two).
+    int nw = 8;
+    while (nw > 1 && (a.Din % (32 * nw) != 0 || a.Din / nw < 256)) nw >>= 1;
+    int tiles = 0;
+    for (int m = 0; m < a.n_mats; ++m) tiles += a.fout[m] / 16;
+    const bool two = tiles >= 2 * 150;
+    int groups = 0;
+    for (int m = 0; m < a.n_mats; ++m) groups += two ? (a.fout[m] / 16 + 1) / 2 : a.fout[m] / 16;
+    const dim3 g(groups), b(nw * kWave);
+    if (two) {
+      if (a.T <= 16) launch(kernel_id, linear_splitk_kernel<2, 1>, g, b, 0, st, a);
+      else launch(kernel_id, linear_splitk_kernel<2, 2>, g, b, 0, st, a);
+    } else {
+      if (a.T <= 16) launch(kernel_id, linear_splitk_kernel<1, 1>, g, b, 0, st, a);
+      else launch(kernel_id, linear_splitk_kernel<1, 2>, g, b, 0, st, a);
+    }
+    return;
+  }
   int blocks = 0;
   for (int m = 0; m < a.n_mats; ++m) blocks += (a.fout[m] / 32 + LW - 1) / LW;
-  const dim3 g(blocks), b(LW * kWave);
+  const dim3 g(blocks, (a.T + 127) / 128), b(LW * kWave);
   if (a.Din == 2048) launch(kernel_id, linear_lds_kernel<LW, 2048>, g, b, 0, st, a);
+  else if (a.Din == 4096) launch(kernel_id, linear_lds_kernel<LW, 4096>, g, b, 0, st, a);
   else launch(kernel_id, linear_lds_kernel<LW, 0>, g, b, 0, st, a);
 }
 
@@ -283,7 +460,7 @@ int launch_attention(const des_shape_t& s, const des_attn_shape_t& t, const void
   p.out[2] = reinterpret_cast<uint16_t*>(ws + l.v);
   p.fout[0] = HD; p.fout[1] = KD_; p.fout[2] = KD_;
   p.n_mats = 3; p.T = T; p.Din = s.hidden; p.res = nullptr;
-  launch_linear<4>(p, kKAttnProj, st);
+  launch_linear<2>(p, kKAttnProj, st);
 
   AttnArgs c{};
   c.q = p.out[0]; c.k = p.out[1]; c.v = p.out[2];
@@ -310,7 +487,7 @@ int launch_attention(const des_shape_t& s, const des_attn_shape_t& t, const void
   o.fout[0] = s.hidden;
   o.n_mats = 1; o.T = T; o.Din = HD;
   o.res = s.residual ? static_cast<const uint16_t*>(x) : nullptr;
-  launch_linear<4>(o, kKAttnOut, st);
+  launch_linear<2>(o, kKAttnOut, st);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? DES_OK : hip_fail(e, "attention launch");
 }

@@ -84,7 +84,9 @@ def test_attention_ignores_other_sequences_and_orders_cache_positions():
     y1 = B.des_block_attention(shape1, attn1, dev["x"][b:b + 1].contiguous(), dev["wq"], dev["wk"], dev["wv"],
                                dev["wo"], dev["k_cache"][b:b + 1].contiguous(), dev["v_cache"][b:b + 1].contiguous())
     torch.cuda.synchronize()
-    assert torch.equal(y1[0], y[b])
+    # (blocks of up to 32 rows and longer ones take different projection kernels, which add
+    # the reduction dimension in different orders: equal up to the bf16 rounding of q, k, v, o)
+    assert (y1[0].float() - y[b].float()).abs().max().item() <= 2.0 ** -7 * y.float().abs().max().item()
     perm = torch.randperm(cfg.n_prefix + cfg.n_suffix, generator=torch.Generator().manual_seed(3)).cuda()
     yp = B.des_block_attention(shape, attn, dev["x"], dev["wq"], dev["wk"], dev["wv"], dev["wo"],
                                dev["k_cache"][:, :, perm].contiguous(), dev["v_cache"][:, :, perm].contiguous())
