@@ -198,8 +198,8 @@ int des_moe_forward(const des_shape_t* s, const void* x, const void* w_router,
   rc = launch_routing(*s, x, w_router, router_bias, logits, coreset_idx, coreset_size, topk_idx,
                       topk_w, expert_counts, n_unique, nullptr, ws, epoch, st);
   if (rc != DES_OK) return rc;
-  return launch_ffn(*s, x, w_gate, w_up, w_down, ws_gate, ws_up, ws_down, topk_idx, topk_w,
-                    n_unique, y, ws, epoch, st);
+  return launch_ffn(*s, x, w_gate, w_up, w_down, ws_gate, ws_up, ws_down, logits, topk_idx, topk_w,
+                    expert_counts, n_unique, y, ws, epoch, st);
 }
 
 int des_moe_forward_builtin_ws(const des_shape_t* s, const void* x, const void* w_router,
@@ -293,7 +293,8 @@ int des_moe_stack_forward(const des_shape_t* s_in, int32_t n_layers, const void*
                         expert_counts + li * M, n_unique + li,
                         layer > 0 ? n_unique + li - 1 : nullptr, lws, epoch, st);
     if (rc != DES_OK) return rc;
-    rc = launch_ffn(s, cur, wg, wu, wd, sg, su, sd, tidx, tw, n_unique + li, out, lws, epoch, st);
+    rc = launch_ffn(s, cur, wg, wu, wd, sg, su, sd, logits, tidx, tw, expert_counts + li * M,
+                    n_unique + li, out, lws, epoch, st);
     if (rc != DES_OK) return rc;
     cur = out;
   }
@@ -406,7 +407,8 @@ int des_decoder_stack_forward(const des_shape_t* s_in, const des_attn_shape_t* t
                         reinterpret_cast<int32_t*>(ws + l.core_size), tidx, tw, expert_counts + li * M,
                         n_unique + li, layer > 0 ? n_unique + li - 1 : nullptr, lws, epoch, st);
     if (rc != DES_OK) return rc;
-    rc = launch_ffn(s, a, wg, wu, wd, sg, su, sd, tidx, tw, n_unique + li, out, lws, epoch, st);
+    rc = launch_ffn(s, a, wg, wu, wd, sg, su, sd, logits, tidx, tw, expert_counts + li * M,
+                    n_unique + li, out, lws, epoch, st);
     if (rc != DES_OK) return rc;
     cur = out;
   }

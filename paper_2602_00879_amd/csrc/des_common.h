@@ -123,6 +123,38 @@ inline int selector_tokens_per_pass(int n_experts) {
   return 1024 / lpt;
 }
 
+// Short single-sequence blocks under DES ("dense" handling).  Once the coreset is elected
+// the FFN's weight addresses are known; which token goes to which coreset expert is not
+// needed to start streaming.  So for one sequence of at most 32 tokens the routing launch
+// ends with the election, gate/up computes every coreset expert for ALL tokens of the
+// block (two token tiles at most: matrix-core work that is free beside the weight
+// stream), stage 2 (re-routing and gates, Alg. 1) runs in spare wavefronts of the gate/up
+// launch, the down projection keeps only the routed (token, expert) pairs, and the
+// permutation disappears.  Not for vanilla routing (its live experts ARE the per-token
+// choices), nor where a coreset expert may end up unused (fewer experts per token than
+// the election used, skipping, group limits): there the general path streams fewer bytes.
+inline bool dense_shape(const des_shape_t& s) {
+  return s.dtype == DES_BF16 && s.n_seqs == 1 && s.n_tokens <= 32 && s.mode != DES_VANILLA &&
+         (s.k_route == 0 || s.k_route == s.top_k) && !(s.skip_beta > 0.0f) &&
+         !(s.n_group > 1 && s.topk_group < s.n_group);
+}
+bool dense_block(const des_shape_t& s);  // dense_shape and the routing fits one launch
+
+struct DenseArgs {
+  int on;                  // 0: general path
+  int lpt;                 // selector lanes per token (a power of two, 8 experts per lane)
+  int sigmoid;             // router weights are sigmoid(logit)
+  const float* logits;     // [N][M]
+  int32_t* topk_idx;       // [N][K] S_n, written by stage 2
+  float* topk_w;           // [N][K] g_n
+  const int32_t* slot_of;  // [M] slot of a coreset expert, -1 otherwise
+  uint32_t* tokmask;       // [n_slots] tokens routed to the slot's expert (bit n = token n)
+  uint8_t* choice;         // [n_slots][32] which of token n's K choices the slot's expert is
+  int32_t* pos;            // [N*K] output row of pair n*K+j (itself), -1 = unused
+  int32_t* expert_counts;  // [M] written by the combine launch
+  int32_t* n_unique;       // [1]
+};
+
 // All offsets in bytes from the (256-byte aligned) workspace base.
 struct WsLayout {
   size_t flags;     // u64   [router tiles + 2 * max(B, kMaxSelGroups)]  epoch flags of the routing launch
@@ -136,7 +168,10 @@ struct WsLayout {
   size_t pair_tok;  // int32 [T*K]     token of each pair, pairs sorted by (expert, token)
   size_t pos;       // int32 [T*K]     sorted position of pair t*K+j; -1 for unused slots
   size_t units;     // int32 [max_units]  slot | split << 16 | splits of that slot << 24
-  size_t h;         // act   [(T*K + Ts) * max(F, Fs)]   SwiGLU activations
+  size_t tokmask;   // u32   [n_slots]      dense short blocks: tokens routed to each slot's expert
+  size_t choice;    // u8    [n_slots][32]  ... and which of the token's K choices it is
+  size_t h_rows;    // routed rows of H: T*K, or n_slots * T for a dense short block
+  size_t h;         // act   [(h_rows + Ts) * max(F, Fs)]   SwiGLU activations
   size_t o;         // f32   [(T*K + Ts) * D]            per-pair expert outputs
   size_t total;
 };
@@ -163,7 +198,11 @@ inline WsLayout ws_layout(const des_shape_t& s) {
   w.pair_tok = p; p = align256(p + 4 * TK);
   w.pos = p;      p = align256(p + 4 * TK);
   w.units = p;    p = align256(p + 4 * static_cast<size_t>(max_units(s)));
-  w.h = p;        p = align256(p + act * (TK + Ts) * Fm);
+  w.tokmask = p;  p = align256(p + 4 * static_cast<size_t>(max_live_experts(s)));
+  w.choice = p;   p = align256(p + 32 * static_cast<size_t>(max_live_experts(s)));
+  const size_t dense_rows = dense_shape(s) ? static_cast<size_t>(max_live_experts(s)) * T : 0;
+  w.h_rows = dense_rows > TK ? dense_rows : TK;
+  w.h = p;        p = align256(p + act * (w.h_rows + Ts) * Fm);
   w.o = p;        p = align256(p + 4 * (TK + Ts) * static_cast<size_t>(s.hidden));
   w.total = p;
   return w;
@@ -185,8 +224,8 @@ int launch_routing(const des_shape_t& s, const void* x, const void* w_router, co
 extern int g_test_max_wait, g_test_skip_router;
 int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const void* w_up,
                const void* w_down, const void* ws_gate, const void* ws_up, const void* ws_down,
-               const int32_t* topk_idx, const float* topk_w, int32_t* n_unique, void* y, char* ws,
-               unsigned long long epoch, hipStream_t st);
+               const float* logits, int32_t* topk_idx, float* topk_w, int32_t* expert_counts,
+               int32_t* n_unique, void* y, char* ws, unsigned long long epoch, hipStream_t st);
 // Attention sub-layer (des_attention.hip): scratch layout, LDS need of the per-head
 // kernel, and the three launches.
 struct AttnLayout { size_t q, k, v, o, total; };

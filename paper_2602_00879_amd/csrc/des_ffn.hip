@@ -21,6 +21,7 @@
 #include <type_traits>
 
 #include "des_common.h"
+#include "des_select.h"
 #include "des_stream_gemm.h"
 
 namespace des {
@@ -42,6 +43,8 @@ struct FfnArgs {
   int splits;                   // units the shared expert's rows are spread over (LDS kernels)
   const int32_t* units;         // live units of the routed experts, longest expert first:
                                 // slot | split << 16 | splits of that slot << 24; meta[2] of them
+  size_t h_rows;                // routed rows of H (the shared expert's rows follow them)
+  DenseArgs dn;                 // dense short block: stage 2 beside gate/up, see des_common.h
 };
 
 #ifdef DES_FFN_STAMPS  // development aid (build with DES_FFN_STAMPS=1): per-task 100 MHz
@@ -61,6 +64,7 @@ struct Task {
   int count;                // pairs of this expert
   int pair0;                // first sorted position (routed) or 0 (shared)
   bool shared;
+  uint32_t dmask;           // dense short block, down projection: the slot's routed tokens
   size_t row_base;          // first H / O row of these pairs
   int fdim;                 // F of this expert (F or Fs)
 };
@@ -193,6 +197,7 @@ __device__ __forceinline__ void gateup_group(const FfnArgs& a, const Task& t, in
 __device__ __forceinline__ bool make_task(const FfnArgs& a, int slot_or_shared, bool shared,
                                           bool down, Task& t, int lane) {
   const size_t TK = static_cast<size_t>(a.T) * a.K;
+  t.dmask = 0u;  // (every path: the down projection tests it)
   if (!shared) {
     // the slot record and (for gate/up) this lane's tokens are fetched together:
     // both addresses depend on the slot number only
@@ -205,11 +210,29 @@ __device__ __forceinline__ bool make_task(const FfnArgs& a, int slot_or_shared, 
     // an unused slot; also refuses a record that does not fit the problem (the
     // workspace is the caller's memory: never index weights or pairs with it blindly)
     if (sl.x < 0 || sl.x >= a.M || sl.y < 0 || sl.z < 1 ||
-        static_cast<long long>(sl.y) + sl.z > static_cast<long long>(a.T) * a.K)
+        static_cast<long long>(sl.y) + sl.z > static_cast<long long>(a.h_rows))
       return false;
     const int e = sl.x;
     const int off = sl.y;
-    if (!down && a.T <= 32) {
+    if (a.dn.on) {
+      // every token of the block, in order: H row = first row of the slot + token
+      t.pre_tok[0] = min(lane & 15, a.T - 1);
+      t.pre_tok[1] = min(16 + (lane & 15), a.T - 1);
+      if (down) {
+        // the expert's pairs are the set bits of its bitmap, in order (positions past
+        // the count repeat the last one; their results are dropped)
+        t.dmask = a.dn.tokmask[slot_or_shared] & (a.T >= 32 ? 0xffffffffu : ((1u << a.T) - 1u));
+        if (t.dmask == 0u) return false;  // nobody was routed to this expert
+        const int cnt = __popc(t.dmask);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const int want = min(i * 16 + (lane & 15), cnt - 1);
+          uint32_t mm = t.dmask;
+          for (int k = 0; k < want; ++k) mm &= mm - 1u;
+          t.pre_tok[i] = __builtin_ctz(mm);
+        }
+      }
+    } else if (!down && a.T <= 32) {
       // at most 32 tokens: the record carries the bitmap of the expert's tokens; its pairs
       // in order are the set bits in order (positions past the count repeat the last one)
       const uint32_t m = static_cast<uint32_t>(sl.w);
@@ -222,7 +245,9 @@ __device__ __forceinline__ bool make_task(const FfnArgs& a, int slot_or_shared, 
       }
     }
     t.slot = slot_or_shared;
-    t.count = sl.z;
+    // (dense, down: only the routed tokens count, so a slot with at most 16 of them takes
+    // the one-tile path)
+    t.count = t.dmask ? __popc(t.dmask) : sl.z;
     t.pair0 = off;
     t.shared = false;
     t.row_base = static_cast<size_t>(off);
@@ -253,8 +278,7 @@ __device__ __forceinline__ bool make_task(const FfnArgs& a, int slot_or_shared, 
 // shifting the base pointer instead (keeps one indexing formula).
 __device__ __forceinline__ FfnArgs shared_view(const FfnArgs& a, Task& t, size_t elem_size) {
   FfnArgs v = a;
-  const size_t TK = static_cast<size_t>(a.T) * a.K;
-  v.h = static_cast<char*>(a.h) + TK * a.F * elem_size;
+  v.h = static_cast<char*>(a.h) + a.h_rows * a.F * elem_size;
   t.row_base = 0;
   return v;
 }
@@ -336,7 +360,29 @@ __device__ __forceinline__ bool gateup_task(const FfnArgs& a, int task, int lane
 template <int MAXNT, bool PACKED, int U1 = 2, int U2 = 2, int GT = kGuTiles>
 __global__ __launch_bounds__(kFfnWaves* kWave) void gateup_bf16_kernel(FfnArgs a) {
   const int lane = threadIdx.x & 63;
-  const int task = blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
+  int task = blockIdx.x * kFfnWaves + (threadIdx.x >> 6);
+  if constexpr (MAXNT <= 2) {
+    if (a.dn.on) {
+      // dense short block: the first wavefronts of the grid re-route the block's tokens
+      // (Alg. 1 stage 2) while the others stream the coreset's weights
+      const int n_s2 = (a.T * a.dn.lpt + 63) / 64;
+      if (task < n_s2) {
+        __shared__ uint32_t s_sorted[kFfnWaves * kEpl * 64];
+        uint32_t* srt = s_sorted + (threadIdx.x >> 6) * (kEpl * 64);
+        const int n_core = a.meta[0];
+        if (n_core <= 0) return;  // the routing launch gave up: nothing was elected
+        switch (a.dn.lpt) {
+          case 4: stage2_wave<4>(a.dn, a.T, a.M, a.K, n_core, task, srt); break;
+          case 8: stage2_wave<8>(a.dn, a.T, a.M, a.K, n_core, task, srt); break;
+          case 16: stage2_wave<16>(a.dn, a.T, a.M, a.K, n_core, task, srt); break;
+          case 32: stage2_wave<32>(a.dn, a.T, a.M, a.K, n_core, task, srt); break;
+          default: stage2_wave<64>(a.dn, a.T, a.M, a.K, n_core, task, srt); break;
+        }
+        return;
+      }
+      task -= n_s2;
+    }
+  }
   const int tasks = a.n_slots * (a.F / (16 * GT)) + a.Fs / (16 * GT);
   if (task < tasks) gateup_task<MAXNT, PACKED, U1, U2, GT>(a, task, lane);
 }
@@ -355,7 +401,10 @@ __device__ __forceinline__ void down_group(const FfnArgs& a, const Task& t, int 
 #pragma unroll
   for (int i = 0; i < NT; ++i) {
     const int pi = min(g0 + i * 16 + (lane & 15), t.count - 1);
-    hp[i] = h + (t.row_base + pi) * F + (lane >> 4) * 8;
+    // (dense short block: H holds every token of the block for this slot; the routed
+    // ones, in order, are this expert's pairs)
+    const int hrow = t.dmask ? t.pre_tok[i < 2 ? i : 0] : pi;
+    hp[i] = h + (t.row_base + hrow) * F + (lane >> 4) * 8;
   }
   f32x4 acc[RT][NT];
 #pragma unroll
@@ -411,9 +460,16 @@ __device__ __forceinline__ void down_group(const FfnArgs& a, const Task& t, int 
   for (int i = 0; i < NT; ++i) {
     const int pi = g0 + i * 16 + (lane & 15);
     if (pi < t.count) {
+      size_t orow = orow0 + pi;
+      if (t.dmask) {
+        // dense short block: the pair's row is token * K + (which of the token's
+        // choices this expert is)
+        const int tok = t.pre_tok[i < 2 ? i : 0];
+        orow = static_cast<size_t>(tok) * a.K + a.dn.choice[t.slot * 32 + tok];
+      }
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
-        float* dst = a.o + (orow0 + pi) * a.D + (dt0 + r) * 16 + 4 * (lane >> 4);
+        float* dst = a.o + orow * a.D + (dt0 + r) * 16 + 4 * (lane >> 4);
         *reinterpret_cast<f32x4*>(dst) = acc[r][i];
       }
     }
@@ -738,6 +794,25 @@ template <bool BF16>
 __global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
   const int t = blockIdx.x;
   const int d = (blockIdx.y * 256 + threadIdx.x) * 4;
+  if (a.dn.on && blockIdx.x == 0 && blockIdx.y == 0) {
+    // dense short block: cnt_i and the number of experts that received a token, from
+    // the bitmaps stage 2 left (integer work, the same whatever the order)
+    __shared__ int s_live;
+    if (threadIdx.x == 0) s_live = 0;
+    __syncthreads();
+    int live = 0;
+    for (int e = threadIdx.x; e < a.M; e += 256) {
+      const int sl = a.dn.slot_of[e];
+      const int c = (sl >= 0 && sl < a.n_slots) ? __popc(a.dn.tokmask[sl]) : 0;
+      a.dn.expert_counts[e] = c;
+      live += c > 0 ? 1 : 0;
+    }
+    if (live) atomicAdd(&s_live, live);
+    __syncthreads();
+    // (a negative value was put there by a routing launch that gave up, or carried over
+    // from an earlier layer of a stack: it stays)
+    if (threadIdx.x == 0 && a.dn.n_unique[0] >= 0) a.dn.n_unique[0] = s_live;
+  }
   if (d >= a.D) return;
   const int K = a.K;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -854,8 +929,8 @@ int launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st)
 // ------------------------------------------------------------------ launcher
 int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const void* w_up,
                const void* w_down, const void* ws_gate, const void* ws_up, const void* ws_down,
-               const int32_t* topk_idx, const float* topk_w, int32_t* n_unique, void* y, char* ws,
-               unsigned long long epoch, hipStream_t st) {
+               const float* logits, int32_t* topk_idx, float* topk_w, int32_t* expert_counts,
+               int32_t* n_unique, void* y, char* ws, unsigned long long epoch, hipStream_t st) {
   const WsLayout w = ws_layout(s);
   FfnArgs a;
   a.x = x;
@@ -877,12 +952,30 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
   a.n_slots = max_live_experts(s);
   a.residual = s.residual;
   a.splits = 1;
+  a.h_rows = w.h_rows;
+  a.dn = DenseArgs{};
+  int n_s2 = 0;  // wavefronts of the gate/up launch that run stage 2 (dense short block)
+  if (dense_block(s)) {
+    a.dn.on = 1;
+    a.dn.lpt = 1024 / selector_tokens_per_pass(s.n_experts);
+    a.dn.sigmoid = s.router_act == DES_ROUTER_SIGMOID;
+    a.dn.logits = logits;
+    a.dn.topk_idx = topk_idx;
+    a.dn.topk_w = topk_w;
+    a.dn.slot_of = reinterpret_cast<const int32_t*>(ws + w.slot_of);
+    a.dn.tokmask = reinterpret_cast<uint32_t*>(ws + w.tokmask);
+    a.dn.choice = reinterpret_cast<uint8_t*>(ws + w.choice);
+    a.dn.pos = reinterpret_cast<int32_t*>(ws + w.pos);
+    a.dn.expert_counts = expert_counts;
+    a.dn.n_unique = n_unique;
+    n_s2 = (a.T * a.dn.lpt + 63) / 64;
+  }
   const int TK = a.T * a.K;
 
   if (s.dtype == DES_BF16) {
     const bool packed = s.weight_layout == DES_LAYOUT_PACKED;
     const int gu_tasks = a.n_slots * (a.F / (16 * kGuTiles)) + a.Fs / (16 * kGuTiles);
-    const int gu_blocks = (gu_tasks + kFfnWaves - 1) / kFfnWaves;
+    const int gu_blocks = (gu_tasks + n_s2 + kFfnWaves - 1) / kFfnWaves;
     const int groups = (a.D / 16 + 3) / 4;
     const int dn_tasks = a.n_slots * groups + (a.Fs > 0 ? groups : 0);
     const int dn_blocks = (dn_tasks + kFfnWaves - 1) / kFfnWaves;
@@ -901,7 +994,7 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
 #define DES_LAUNCH_FFN(NTV, PK)                                                             \
   do {                                                                                      \
     if (gu_fine && NTV <= 2)                                                                \
-      launch(kKGateUp, gateup_bf16_kernel<NTV, PK, 4, 4, 1>, dim3(gu_fine_tasks), blk, 0, st, a); \
+      launch(kKGateUp, gateup_bf16_kernel<NTV, PK, 4, 4, 1>, dim3(gu_fine_tasks + n_s2), blk, 0, st, a); \
     else                                                                                    \
       launch(kKGateUp, gateup_bf16_kernel<NTV, PK>, dim3(gu_blocks), blk, 0, st, a);        \
     if (dn_fine && NTV <= 2)                                                                \

@@ -28,6 +28,7 @@
 // fixed order.  Every ranking compares order-preserving integer keys of the
 // fp32 logits with ties to the lowest expert index.
 #include "des_common.h"
+#include "des_select.h"
 
 namespace des {
 
@@ -92,6 +93,10 @@ struct RoutingArgs {
   int skip_router_tiles;  // test hook: the fused launch runs without its router tiles
   int small_perm;         // one selector workgroup, at most 32 tokens, no skipping: the permutation
                           // is built from per-expert token bitmaps recorded during stage 2
+  int dense;              // dense short block (dense_block()): the launch ends with the election
+                          // and the slot table of the coreset; stage 2 runs beside the gate/up
+                          // projection, there is no permutation
+  uint32_t* tokmask;      // [n_slots] cleared here for that stage 2
 };
 
 // ------------------------------------------------------------------ flags
@@ -203,89 +208,6 @@ __device__ __forceinline__ void router_tile_f32(const RoutingArgs& a, int tile_m
   }
 }
 
-// ------------------------------------------------------- row primitives
-// A "row" is the group of LPT adjacent lanes that owns one token; each lane
-// owns 8 consecutive experts.  All-reduce inside every row: quad swaps, the
-// half-row and row mirrors (DPP), then lane exchanges across 16-lane rows.
-template <int LPT>
-__device__ __forceinline__ uint32_t row_max_u32(uint32_t v) {
-  if (LPT >= 2) v = max(v, dpp_u32<0xB1>(0u, v));   // quad_perm [1,0,3,2]
-  if (LPT >= 4) v = max(v, dpp_u32<0x4E>(0u, v));   // quad_perm [2,3,0,1]
-  if (LPT >= 8) v = max(v, dpp_u32<0x141>(0u, v));  // row_half_mirror
-  if (LPT >= 16) v = max(v, dpp_u32<0x140>(0u, v)); // row_mirror
-  if (LPT >= 32) v = max(v, static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), 16)));
-  if (LPT >= 64) v = max(v, static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), 32)));
-  return v;
-}
-template <int LPT>
-__device__ __forceinline__ float row_sum_f32(float x) {
-  uint32_t v = __float_as_uint(x);
-#define DES_STEP(ctrl) v = __float_as_uint(__uint_as_float(v) + __uint_as_float(dpp_u32<ctrl>(0u, v)))
-  if (LPT >= 2) DES_STEP(0xB1);
-  if (LPT >= 4) DES_STEP(0x4E);
-  if (LPT >= 8) DES_STEP(0x141);
-  if (LPT >= 16) DES_STEP(0x140);
-#undef DES_STEP
-  float r = __uint_as_float(v);
-  if (LPT >= 32) r += __shfl_xor(r, 16);
-  if (LPT >= 64) r += __shfl_xor(r, 32);
-  return r;
-}
-// exp(x) for x <= 0 through the hardware exp2: the product x*log2(e) is split
-// into a rounded part and its residual, so the result is good to ~2 ulp
-// (a plain exp2(x*log2e) loses |x| ulp).  Underflows to 0 below about -87.
-__device__ __forceinline__ float exp_neg(float x) {
-  const float kL2eHi = 1.44269502162933349609375f, kL2eLo = 1.925963033500011e-8f;
-  const float t = x * kL2eHi;
-  float r = fmaf(x, kL2eHi, -t);
-  r = fmaf(x, kL2eLo, r);
-  return __builtin_amdgcn_exp2f(t) * fmaf(r, 0.693147180559945f, 1.0f);
-}
-// logistic sigmoid, the same accuracy for both signs
-__device__ __forceinline__ float sigmoid_f(float x) {
-  const float t = exp_neg(-fabsf(x));
-  return (x >= 0.f ? 1.0f : t) / (1.0f + t);
-}
-__device__ __forceinline__ float key_to_f32(uint32_t k) {
-  return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
-}
-
-constexpr int kEpl = 8;  // experts per lane
-
-// A lane's 8 (key, slot) pairs sorted once, best first; every later "best
-// remaining candidate" is then a head pointer, not a rescan.  The pair is one
-// 64-bit word, key << 3 | (7 - slot), so that equal keys order by ascending
-// slot (= ascending expert index) and a plain 19-comparator network does the
-// job.  `idx` packs the original slot of sorted position s in bits [3s, 3s+3).
-__device__ __forceinline__ void sort8_desc(uint32_t (&k)[kEpl], uint32_t& idx) {
-  unsigned long long c[kEpl];
-#pragma unroll
-  for (int j = 0; j < kEpl; ++j)
-    c[j] = (static_cast<unsigned long long>(k[j]) << 3) | static_cast<unsigned>(7 - j);
-#define DES_CE(i, j)                              \
-  do {                                            \
-    const bool sw = c[i] < c[j];                  \
-    const unsigned long long hi = sw ? c[j] : c[i]; \
-    const unsigned long long lo = sw ? c[i] : c[j]; \
-    c[i] = hi;                                    \
-    c[j] = lo;                                    \
-  } while (0)
-  DES_CE(0, 1); DES_CE(2, 3); DES_CE(4, 5); DES_CE(6, 7);
-  DES_CE(0, 2); DES_CE(1, 3); DES_CE(4, 6); DES_CE(5, 7);
-  DES_CE(1, 2); DES_CE(5, 6); DES_CE(0, 4); DES_CE(3, 7);
-  DES_CE(1, 5); DES_CE(2, 6);
-  DES_CE(1, 4); DES_CE(3, 6);
-  DES_CE(2, 4); DES_CE(3, 5);
-  DES_CE(3, 4);
-#undef DES_CE
-  idx = 0;
-#pragma unroll
-  for (int j = 0; j < kEpl; ++j) {
-    k[j] = static_cast<uint32_t>(c[j] >> 3);
-    idx |= (7u - (static_cast<uint32_t>(c[j]) & 7u)) << (3 * j);
-  }
-}
-
 // LDS carve-up of the selection (bytes).  MP = padded expert count = 8 * LPT.
 template <int LPT>
 struct SelLds {
@@ -304,32 +226,6 @@ struct SelLds {
   static constexpr int liv = off + 4 * (MP + 1);                 // int [MP + 1] live experts before it
   static constexpr int total = liv + 4 * (MP + 1);
 };
-
-// Per-token state of one lane while candidates are drawn best-first.
-struct Head {
-  uint32_t mask;  // sorted positions still in play
-  uint32_t key;   // key at the head (0 = none)
-  int h;          // head position
-};
-__device__ __forceinline__ void head_set(Head& hd, uint32_t mask, const uint32_t* my_sorted) {
-  hd.mask = mask;
-  hd.h = mask ? __builtin_ctz(mask) : 0;
-  hd.key = mask ? my_sorted[hd.h * 64] : 0u;
-}
-
-// One draw: the best head of every row.  Returns the row's best key (0 = the
-// row has no candidate); `mine` is set in the one lane that owns it.
-template <int LPT>
-__device__ __forceinline__ uint32_t row_draw(const Head& hd, bool& mine) {
-  const uint32_t m = row_max_u32<LPT>(hd.key);
-  const unsigned long long hit = __ballot(hd.key == m && m != 0u);
-  const int lane = threadIdx.x & 63;
-  const unsigned long long rowbits =
-      LPT == 64 ? hit : ((hit >> (lane & (64 - LPT))) & ((1ull << (LPT & 63)) - 1ull));
-  // lowest lane with the best key = lowest expert index among equals
-  mine = rowbits != 0ull && (lane & (LPT - 1)) == __builtin_ctzll(rowbits);
-  return m;
-}
 
 // ------------------------------------------------------- role S: selection
 // `dry` runs the same instructions on whatever the logits buffer holds and
@@ -657,6 +553,7 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
       if (from_rank && e < MP) s_core[e] = f ? 1 : 0;
       const unsigned long long bal = __ballot(f);
       const int pre = __popcll(bal & ((1ull << lane) - 1ull));
+      if (a.dense && e < MP) s_level[e] = f ? base + pre : -1;  // the expert's slot (stage 1 is done with s_level)
       if (f && base + pre < a.cap && !dry && g == 0) out[base + pre] = e;
       base += __popcll(bal);
     }
@@ -672,6 +569,30 @@ __device__ bool select_sequence(const RoutingArgs& a, int b, int g, char* smem, 
   }
   __syncthreads();
   if (a.topk_idx == nullptr) return true;
+  if (a.dense) {
+    // The slot table of the coreset in ascending expert order, every token of the block
+    // listed for every slot; stage 2 fills in who is routed where.
+    if (!dry) {
+      const int size = s_hist[34];
+      for (int e = threadIdx.x; e < M; e += kRtThreads) {
+        const int sl = s_level[e] < a.n_slots ? s_level[e] : -1;
+        a.slot_of[e] = sl;
+        if (sl >= 0) {
+          a.slots[sl] = make_int4(e, sl * N, N, 0);
+          a.tokmask[sl] = 0u;
+        }
+      }
+      for (int sl = size + threadIdx.x; sl < a.n_slots; sl += kRtThreads) a.slots[sl] = make_int4(-1, 0, 0, 0);
+      if (threadIdx.x == 0) {
+        a.meta[0] = size;
+        a.meta[1] = 0;
+        a.meta[2] = 0;
+        // provisional: the combine launch counts the experts that received a token
+        a.n_unique[0] = (a.prev_n_unique != nullptr && a.prev_n_unique[0] < 0) ? -1 : size;
+      }
+    }
+    return true;
+  }
 
   DES_STAMP(a, 4);
   // ------------------------------ stage 2: constrained local routing + gates
@@ -1061,6 +982,11 @@ __global__ __launch_bounds__(kRtThreads) void routing_kernel(RoutingArgs a) {
     }
     DES_STAMP(a, 5);
     if (a.topk_idx == nullptr) return;
+    if (a.dense) {  // no stage 2, no permutation here; the flags of this call are consumed
+      if (a.use_flags)
+        for (int i = threadIdx.x; i < n_flags; i += kRtThreads) a.flags[i] = 0ull;
+      return;
+    }
     if (n_sel == 1 && a.do_permute) {  // a single selector: permute right here
       // same workgroup, same compute unit: the barrier orders the topk_idx
       // stores before the loads below, no device-scope fence needed
@@ -1175,6 +1101,16 @@ static void fill_common(RoutingArgs& a, const des_shape_t& s) {
   }
 }
 
+// The conditions of launch_routing's single launch with one selector workgroup, for a
+// shape that qualifies (dense_shape): the FFN launches must take the same decision.
+bool dense_block(const des_shape_t& s) {
+  if (!dense_shape(s)) return false;
+  int fused_limit = device_compute_units();
+  if (fused_limit > kMaxFusedRoutingBlocks) fused_limit = kMaxFusedRoutingBlocks;
+  const int n_tiles = ((s.n_experts + 15) / 16) * ((s.n_tokens + 15) / 16);
+  return s.n_tokens <= selector_tokens_per_pass(s.n_experts) && n_tiles + 1 <= fused_limit;
+}
+
 int launch_router(const des_shape_t& s, const void* x, const void* w_router, const float* bias,
                   float* logits, hipStream_t st) {
   RoutingArgs a;
@@ -1245,6 +1181,8 @@ int launch_routing(const des_shape_t& s, const void* x, const void* w_router, co
   if (roles <= fused_limit) {  // all workgroups resident at once: one launch
     a.groups = groups;
     a.small_perm = small;
+    a.dense = dense_block(s) ? 1 : 0;
+    a.tokmask = reinterpret_cast<uint32_t*>(ws + w.tokmask);
     a.do_router = a.do_select = a.do_permute = 1;
     a.use_flags = 1;
     if (g_test_skip_router) {  // test hook: nobody computes the logits, the selectors' wait expires
