@@ -37,9 +37,9 @@ HBM_PEAK_GBS = 8000.0
 # commit whose kernels that run profiled, and goes stale when the kernel changes.
 MEASURED_TRAFFIC = {
     ("m128_zipf", "vote", "packed"): {
-        "bytes": 202557235 + 393216,  # 202,557,235 B read + 393,216 B written
+        "bytes": 202684211 + 1586483,  # 202,684,211 B read + 1,586,483 B written
         "profile": "profiles/hbm_traffic_m128_zipf_vote_c32_packed.txt",
-        "kernel_commit": "c6257bd",
+        "kernel_commit": "c737a12",
     },
 }
 
