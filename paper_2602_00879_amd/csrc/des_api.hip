@@ -336,7 +336,7 @@ int des_block_attention(const des_shape_t* s, const des_attn_shape_t* t, const v
   if (workspace_bytes < attn_layout(*s, *t).total) return DES_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return DES_ERR_WORKSPACE;
   return launch_attention(*s, *t, x, wq, wk, wv, wo, k_cache, v_cache, y, static_cast<char*>(workspace),
-                          static_cast<hipStream_t>(hip_stream));
+                          next_epoch(), static_cast<hipStream_t>(hip_stream));
 }
 
 size_t des_decoder_workspace_bytes(const des_shape_t* s, const des_attn_shape_t* t) {
@@ -388,7 +388,7 @@ int des_decoder_stack_forward(const des_shape_t* s_in, const des_attn_shape_t* t
                           static_cast<const char*>(wo) + li * D * HD * el,
                           k_cache ? static_cast<const char*>(k_cache) + li * cache * el : nullptr,
                           v_cache ? static_cast<const char*>(v_cache) + li * cache * el : nullptr, a,
-                          ws + attn_ws, st);
+                          ws + attn_ws, next_epoch(), st);
     if (rc != DES_OK) return rc;
     const char* wr = static_cast<const char*>(w_router) + li * M * D * el;
     const float* rb = router_bias ? router_bias + li * M : nullptr;

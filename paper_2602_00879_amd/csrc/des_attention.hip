@@ -24,6 +24,11 @@ struct LinearArgs {
   const uint16_t* res;   // [T][fout[0]] bf16 added to out[0] before rounding, or null
   int fout[3];
   int n_mats, T, Din;
+  // short blocks, reduction dimension split over two workgroups (ksplit = 2):
+  int ksplit;
+  float* partial;             // [workgroups][tiles of a workgroup][64 lanes][4] fp32 partial tiles
+  unsigned long long* flags;  // [workgroup pairs] set to `epoch` by the half that finishes first
+  unsigned long long epoch;   // of this call: never zero, never repeated (stale words cannot match)
 };
 
 // out[m][t][f] = sum_d in[t][d] * w[m][f][d].  A workgroup of LW wavefronts owns LW pairs
@@ -114,7 +119,8 @@ __global__ __launch_bounds__(512) void linear_splitk_kernel(LinearArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_waves = blockDim.x >> 6;
-  int grp_i = blockIdx.x, m = 0;
+  const int half = blockIdx.x % a.ksplit, pair_id = blockIdx.x / a.ksplit;
+  int grp_i = pair_id, m = 0;
   for (; m < a.n_mats; ++m) {  // which matrix this workgroup belongs to
     const int per = (a.fout[m] / 16 + RT - 1) / RT;
     if (grp_i < per) break;
@@ -123,16 +129,18 @@ __global__ __launch_bounds__(512) void linear_splitk_kernel(LinearArgs a) {
   if (m >= a.n_mats) return;
   const int fout = a.fout[m], Din = a.Din;
   const int n_tiles = fout / 16;
-  const int kper = Din / n_waves, nks = kper / 32;  // the host makes kper a multiple of 32
+  const int kwg = Din / a.ksplit;                   // reduction elements of this workgroup
+  const int kper = kwg / n_waves, nks = kper / 32;  // the host makes kper a multiple of 32
+  const int k0 = half * kwg + wave * kper;
   const int col = lane & 15, grp = lane >> 4;
   const uint16_t* wp[RT];
 #pragma unroll
   for (int r = 0; r < RT; ++r)  // a tile past the matrix repeats the last one, dropped at the store
-    wp[r] = a.w[m] + (static_cast<size_t>(min(grp_i * RT + r, n_tiles - 1)) * 16 + col) * Din + wave * kper + grp * 8;
+    wp[r] = a.w[m] + (static_cast<size_t>(min(grp_i * RT + r, n_tiles - 1)) * 16 + col) * Din + k0 + grp * 8;
   const uint16_t* xp[NT];
 #pragma unroll
   for (int i = 0; i < NT; ++i)  // rows past the block repeat the last token, dropped at the store
-    xp[i] = a.in + static_cast<size_t>(min(i * 16 + col, a.T - 1)) * Din + wave * kper + grp * 8;
+    xp[i] = a.in + static_cast<size_t>(min(i * 16 + col, a.T - 1)) * Din + k0 + grp * 8;
   f32x4 acc[RT][NT];
 #pragma unroll
   for (int r = 0; r < RT; ++r)
@@ -181,13 +189,57 @@ __global__ __launch_bounds__(512) void linear_splitk_kernel(LinearArgs a) {
   // wavefront w finishes the tiles w, w + n_waves, ... of the workgroup's RT x NT
   uint16_t* out = a.out[m];
   const uint16_t* res = m == 0 ? a.res : nullptr;
+  if (a.ksplit == 2) {
+    // Two workgroups share these rows, each with half of the reduction dimension.  Both
+    // write their partial tiles with device-scope stores, wait for them, and swap the
+    // call's epoch into the pair's flag: the one that gets the epoch back is the second to
+    // arrive, and it alone goes on - with both partials read back and added as
+    // (first half) + (second half), whoever finished first.  No spinning: nobody waits.
+    float* mine = a.partial + static_cast<size_t>(blockIdx.x) * (RT * NT * 256);
+    for (int t = wave; t < RT * NT; t += n_waves) {
+      const int r = t / NT, i = t % NT;
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+      for (int w = 0; w < n_waves; ++w) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(part + (((w * RT + r) * NT + i) * 64 + lane) * 4);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sum[q] += v[q];
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        __hip_atomic_store(mine + (t * 64 + lane) * 4 + q, sum[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's partials have left the compute unit
+    __shared__ int s_second;
+    __syncthreads();
+    if (tid == 0) {
+      const unsigned long long old =
+          __hip_atomic_exchange(a.flags + pair_id, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_second = old == a.epoch ? 1 : 0;
+      // the pair is complete: clear the flag, so that a replay of a captured launch (same
+      // epoch) starts from a flag nobody has set
+      if (old == a.epoch) __hip_atomic_store(a.flags + pair_id, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!s_second) return;
+  }
+  const float* p0 = a.partial + static_cast<size_t>(pair_id) * 2 * (RT * NT * 256);
   for (int t = wave; t < RT * NT; t += n_waves) {
     const int r = t / NT, i = t % NT;
     f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-    for (int w = 0; w < n_waves; ++w) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(part + (((w * RT + r) * NT + i) * 64 + lane) * 4);
+    if (a.ksplit == 2) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) sum[q] += v[q];
+      for (int q = 0; q < 4; ++q) {
+        const float lo = __hip_atomic_load(p0 + (t * 64 + lane) * 4 + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float hi = __hip_atomic_load(p0 + RT * NT * 256 + (t * 64 + lane) * 4 + q, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+        sum[q] = lo + hi;
+      }
+    } else {
+      for (int w = 0; w < n_waves; ++w) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(part + (((w * RT + r) * NT + i) * 64 + lane) * 4);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sum[q] += v[q];
+      }
     }
     const int tok = i * 16 + col, tile = grp_i * RT + r;
     if (tok < a.T && tile < n_tiles) {
@@ -399,6 +451,14 @@ AttnLayout attn_layout(const des_shape_t& s, const des_attn_shape_t& t) {
   l.k = p; p = align256(p + 2 * T * t.n_kv_heads * t.head_dim);
   l.v = p; p = align256(p + 2 * T * t.n_kv_heads * t.head_dim);
   l.o = p; p = align256(p + 2 * T * t.n_heads * t.head_dim);
+  // short blocks, reduction split over two workgroups: fp32 partial tiles (two halves x two
+  // token tiles x 1 KB per 16-row weight tile) and one flag per 16 rows, for the larger of
+  // the two projection launches (they run one after the other)
+  const size_t tiles_qkv = static_cast<size_t>(t.n_heads + 2 * t.n_kv_heads) * t.head_dim / 16;
+  const size_t tiles_out = static_cast<size_t>(s.hidden) / 16;
+  const size_t tiles = tiles_qkv > tiles_out ? tiles_qkv : tiles_out;
+  l.partial = p; p = align256(p + tiles * 4096);
+  l.flags = p; p = align256(p + tiles * 8);
   l.total = p;
   return l;
 }
@@ -413,26 +473,32 @@ size_t attn_core_lds(const des_shape_t& s, const des_attn_shape_t& t) {
 template <int LW>
 static void launch_linear(const LinearArgs& a, int kernel_id, hipStream_t st) {
   if (a.T <= 32) {
+    // Row tiles per workgroup: two halve the token-row traffic from L2, which costs as much
+    // as the weight stream here (measured on the 2048-wide layer: q/k/v 13.6 us against
+    // 17.2 us with one), but only while the workgroups still cover most compute units
+    // (output projection, 128 tiles: 16 us with one tile per workgroup, 21 us with two).
+    // Fewer than 150 workgroups: the reduction dimension is split over two workgroups as
+    // well (output projection 15.9 -> 13.3 us; with 160 workgroups, q/k/v, the exchange of
+    // partial tiles costs more than the better spread gains: 18.4 against 14.1 us).
     // Wavefronts per workgroup (k-slices): a whole number of 32-element steps each, at
-    // least 256 reduction elements per row, at most 8.  Row tiles per workgroup: two halve
-    // the token-row traffic from L2, which costs as much as the weight stream here
-    // (measured on the 2048-wide layer: q/k/v 13.6 us against 17.2 us with one), but only
-    // while the workgroups still cover most compute units (output projection, 128 tiles:
-    // 16 us with one tile per workgroup, 21 us with two).
-    int nw = 8;
-    while (nw > 1 && (a.Din % (32 * nw) != 0 || a.Din / nw < 256)) nw >>= 1;
+    // least 256 reduction elements per row, at most 8.
     int tiles = 0;
     for (int m = 0; m < a.n_mats; ++m) tiles += a.fout[m] / 16;
     const bool two = tiles >= 2 * 150;
     int groups = 0;
     for (int m = 0; m < a.n_mats; ++m) groups += two ? (a.fout[m] / 16 + 1) / 2 : a.fout[m] / 16;
-    const dim3 g(groups), b(nw * kWave);
+    LinearArgs b = a;
+    b.ksplit = (groups < 150 && a.Din % 64 == 0 && a.Din >= 1024 && b.partial != nullptr) ? 2 : 1;
+    const int kwg = a.Din / b.ksplit;
+    int nw = 8;
+    while (nw > 1 && (kwg % (32 * nw) != 0 || kwg / nw < 256)) nw >>= 1;
+    const dim3 g(groups * b.ksplit), blk(nw * kWave);
     if (two) {
-      if (a.T <= 16) launch(kernel_id, linear_splitk_kernel<2, 1>, g, b, 0, st, a);
-      else launch(kernel_id, linear_splitk_kernel<2, 2>, g, b, 0, st, a);
+      if (a.T <= 16) launch(kernel_id, linear_splitk_kernel<2, 1>, g, blk, 0, st, b);
+      else launch(kernel_id, linear_splitk_kernel<2, 2>, g, blk, 0, st, b);
     } else {
-      if (a.T <= 16) launch(kernel_id, linear_splitk_kernel<1, 1>, g, b, 0, st, a);
-      else launch(kernel_id, linear_splitk_kernel<1, 2>, g, b, 0, st, a);
+      if (a.T <= 16) launch(kernel_id, linear_splitk_kernel<1, 1>, g, blk, 0, st, b);
+      else launch(kernel_id, linear_splitk_kernel<1, 2>, g, blk, 0, st, b);
     }
     return;
   }
@@ -446,7 +512,7 @@ static void launch_linear(const LinearArgs& a, int kernel_id, hipStream_t st) {
 
 int launch_attention(const des_shape_t& s, const des_attn_shape_t& t, const void* x, const void* wq,
                      const void* wk, const void* wv, const void* wo, const void* k_cache,
-                     const void* v_cache, void* y, char* ws, hipStream_t st) {
+                     const void* v_cache, void* y, char* ws, unsigned long long epoch, hipStream_t st) {
   const AttnLayout l = attn_layout(s, t);
   const int T = s.n_seqs * s.n_tokens;
   const int HD = t.n_heads * t.head_dim, KD_ = t.n_kv_heads * t.head_dim;
@@ -460,6 +526,10 @@ int launch_attention(const des_shape_t& s, const des_attn_shape_t& t, const void
   p.out[2] = reinterpret_cast<uint16_t*>(ws + l.v);
   p.fout[0] = HD; p.fout[1] = KD_; p.fout[2] = KD_;
   p.n_mats = 3; p.T = T; p.Din = s.hidden; p.res = nullptr;
+  p.ksplit = 1;
+  p.partial = reinterpret_cast<float*>(ws + l.partial);
+  p.flags = reinterpret_cast<unsigned long long*>(ws + l.flags);
+  p.epoch = epoch;
   launch_linear<2>(p, kKAttnProj, st);
 
   AttnArgs c{};
@@ -486,6 +556,10 @@ int launch_attention(const des_shape_t& s, const des_attn_shape_t& t, const void
   o.out[0] = static_cast<uint16_t*>(y);
   o.fout[0] = s.hidden;
   o.n_mats = 1; o.T = T; o.Din = HD;
+  o.ksplit = 1;
+  o.partial = p.partial;
+  o.flags = p.flags;
+  o.epoch = epoch;
   o.res = s.residual ? static_cast<const uint16_t*>(x) : nullptr;
   launch_linear<2>(o, kKAttnOut, st);
   const hipError_t e = hipGetLastError();

@@ -228,13 +228,13 @@ int launch_ffn(const des_shape_t& s, const void* x, const void* w_gate, const vo
                int32_t* n_unique, void* y, char* ws, unsigned long long epoch, hipStream_t st);
 // Attention sub-layer (des_attention.hip): scratch layout, LDS need of the per-head
 // kernel, and the three launches.
-struct AttnLayout { size_t q, k, v, o, total; };
+struct AttnLayout { size_t q, k, v, o, partial, flags, total; };
 inline int attn_cached(const des_attn_shape_t& t) { return t.n_prefix + t.n_suffix; }
 AttnLayout attn_layout(const des_shape_t& s, const des_attn_shape_t& t);
 size_t attn_core_lds(const des_shape_t& s, const des_attn_shape_t& t);
 int launch_attention(const des_shape_t& s, const des_attn_shape_t& t, const void* x, const void* wq,
                      const void* wk, const void* wv, const void* wo, const void* k_cache,
-                     const void* v_cache, void* y, char* ws, hipStream_t st);
+                     const void* v_cache, void* y, char* ws, unsigned long long epoch, hipStream_t st);
 int launch_pack(const void* src, void* dst, int64_t n_mats, int rows, int cols, hipStream_t st);
 int launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st);
 
