@@ -541,12 +541,10 @@ int launch_attention(const des_shape_t& s, const des_attn_shape_t& t, const void
   c.P = attn_cached(t);
   c.scale = 1.0f / sqrtf(static_cast<float>(t.head_dim));
   const size_t lds = attn_core_lds(s, t);
-  static bool big_lds_set = false;  // (the limit is a property of the function, set once)
-  if (lds > 48 * 1024 && !big_lds_set) {
+  if (lds > 48 * 1024) {  // (a property of the function on the current device; cheap to repeat)
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_core_kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return hip_fail(e, "attention LDS size");
-    big_lds_set = true;
   }
   launch(kKAttnCore, attention_core_kernel, dim3(s.n_seqs * t.n_heads), dim3(256), lds, st, c);
 

@@ -151,6 +151,8 @@ ATTN_CONFIGS: Dict[str, AttnConfig] = {
     "attn_nocache": AttnConfig("attn_nocache", 3, 20, 256, 4, 4, 32, 0, 0, 34),
     "attn_ragged": AttnConfig("attn_ragged", 2, 70, 384, 8, 2, 48, 5, 9, 35),
     "attn_one_token": AttnConfig("attn_one_token", 1, 1, 128, 2, 1, 64, 7, 0, 36),
+    # a long cached context: the per-head values no longer fit the default LDS allowance
+    "attn_long_cache": AttnConfig("attn_long_cache", 2, 24, 256, 2, 1, 128, 200, 150, 37),
 }
 
 
