@@ -531,6 +531,29 @@ def test_stack_layer_shape_every_token():
     assert torch.equal(out.y, out_p.y) and torch.equal(out.topk_idx, out_p.topk_idx)
 
 
+@pytest.mark.parametrize("name", ["m128_zipf", "m256_shared", "short_a", "short_c", "short_d"])
+@pytest.mark.parametrize("mode", ["vote", "seq"])
+def test_short_block_path_equals_the_general_path(name, mode):
+    """One sequence of at most 32 tokens under DES ends its routing launch with the
+    election and re-routes beside the gate/up projection; a skipping threshold too small
+    to ever drop an expert sends the same problem down the general path (selection,
+    re-routing and permutation in the routing launch, gathered token lists).  Both must
+    give the same bits everywhere: indices, gates, counts, outputs."""
+    cfg = W.CONFIGS[name] if name in W.CONFIGS else MID[name]
+    _say(f"{name} {mode}: short-block path against the general path")
+    layer = W.make_layer(cfg)
+    dev = H.layer_to_device(layer)
+    for layout in (B.DES_LAYOUT_ROWMAJOR, B.DES_LAYOUT_PACKED):
+        packed = None
+        if layout == B.DES_LAYOUT_PACKED:
+            sh = None if dev["shared"] is None else tuple(B.des_pack_expert_weights(m) for m in dev["shared"])
+            packed = (*(B.des_pack_expert_weights(dev[k]) for k in ("w_gate", "w_up", "w_down")), sh)
+        a = H.run_gpu(cfg, dev, mode, layout=layout, packed_weights=packed)
+        g = H.run_gpu(cfg, dev, mode, layout=layout, packed_weights=packed, skip_beta=1e-30)
+        for f in ("logits", "coreset_idx", "coreset_size", "topk_idx", "topk_w", "expert_counts", "n_unique", "y"):
+            assert torch.equal(getattr(a, f), getattr(g, f)), f"{name} {mode} layout {layout}: {f} differs"
+
+
 def test_stale_scratch_cannot_leak_into_a_call():
     """Between calls the caller's buffers are overwritten with poison (all-ones bytes:
     NaN as floats, -1 as indices, a value no flag ever takes), so that a stage which
