@@ -238,7 +238,8 @@ def main():
     out = {
         "metric": "MoE-layer us per N-token block (DES-Vote, whole hot path)",
         "value": ms_per_step * 1e3, "unit": "us/block", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
+        "warmup": args.warmup, "warmup_steps_run": max(args.warmup, len(replicas)),
+        "ms_per_step": ms_per_step, "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: M={cfg.n_experts} D={cfg.hidden} F={cfg.ffn} "
                                f"Fs={cfg.ffn_shared} K={cfg.top_k} N={cfg.n_tokens} B={cfg.n_seqs} "
