@@ -114,6 +114,22 @@ def test_null_and_workspace_errors():
     assert L.des_moe_forward(ctypes.byref(s), *alias, ctypes.c_size_t(1 << 40), None) == -2
 
 
+def test_stack_entry_points_reject_aliased_input_and_output():
+    s = _shape(residual=1)
+    L = B.lib()
+    L.des_moe_stack_forward.restype = ctypes.c_int
+    ptrs = [ctypes.c_void_p(256 * (i + 1)) for i in range(14)]   # never dereferenced
+    # (shape, n_layers, x, w_router, bias, wg, wu, wd, sg, su, sd, y, counts, n_unique, workspace, bytes, stream)
+    args = list(ptrs)
+    args[9] = args[0]                                            # y = x
+    rc = L.des_moe_stack_forward(ctypes.byref(s), 1, *args[:13], ctypes.c_size_t(1 << 40), None)
+    assert rc == -2
+    ok = B.make_attn_shape(32, 4, 128, 16, 16)
+    d = [ctypes.c_void_p(256 * (i + 1)) for i in range(19)]
+    d[15] = d[0]                                                 # y = x
+    assert L.des_decoder_stack_forward(ctypes.byref(s), ctypes.byref(ok), 1, *d, ctypes.c_size_t(1 << 40), None) == -2
+
+
 def test_attention_shapes_are_checked_on_the_host():
     s = _shape()
     ok = B.make_attn_shape(32, 4, 128, 16, 16)
