@@ -123,11 +123,13 @@ def test_stack48_full_size():
     assert all(32 <= u <= 128 for u in uniq)
 
 
-def test_stack_carries_a_given_up_layer_forward():
+@pytest.mark.parametrize("n_seqs", [3, 1])
+def test_stack_carries_a_given_up_layer_forward(n_seqs):
     """Layer 0's routing is made to give up from the host (one launch only): its
     n_unique is -1 and every later layer, which runs normally, reports -1 as well, so a
-    caller that looks only at the last entry still learns that the step is invalid."""
-    cfg = W.LayerConfig("stack_small", "bf16", 3, 20, 128, 24, 64, 0, 4, 6, 1.1, 21, n_layers=4)
+    caller that looks only at the last entry still learns that the step is invalid.
+    (One sequence: the short-block path, whose counts come from the combine launch.)"""
+    cfg = W.LayerConfig("stack_small", "bf16", n_seqs, 20, 128, 24, 64, 0, 4, 6, 1.1, 21, n_layers=4)
     st = DW.make_stack(cfg)
     shape = B.make_shape(cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k,
                          cfg.coreset, "vote", "bf16", residual=1)
