@@ -114,6 +114,12 @@ def test_small_stack():
     _run_stack_case(cfg, oracle_layers={0, 2, 4}, n_tok_samples=12)
 
 
+def test_small_stack_one_sequence():
+    """One sequence of 20 tokens: every layer takes the short-block path."""
+    cfg = W.LayerConfig("stack_small_1", "bf16", 1, 20, 128, 24, 64, 0, 4, 6, 1.1, 22, n_layers=5)
+    _run_stack_case(cfg, oracle_layers={0, 2, 4}, n_tok_samples=12)
+
+
 def test_stack48_full_size():
     free, _ = torch.cuda.mem_get_info()
     if free < 70e9:
