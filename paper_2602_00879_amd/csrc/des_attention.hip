@@ -31,16 +31,37 @@ struct LinearArgs {
   unsigned long long epoch;   // of this call: never zero, never repeated (stale words cannot match)
 };
 
+// Arrival count of the workgroups that share an output tile (reduction dimension split
+// over several workgroups).  The word holds (call's epoch << 8 | arrivals); whatever it
+// held before this call - garbage, an earlier call's count - is not this epoch and reads
+// as zero arrivals, so nothing has to be cleared beforehand.  Returns this workgroup's
+// arrival number, 1-based.  Device-scope compare-and-swap; nobody ever waits for anybody.
+__device__ __forceinline__ int arrive(unsigned long long* word, unsigned long long epoch) {
+  const unsigned long long tag = (epoch & 0x00ffffffffffffffull) << 8;
+  unsigned long long cur = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (;;) {
+    const unsigned long long base = (cur & ~0xffull) == tag ? cur : tag;
+    const unsigned long long want = base + 1ull;
+    if (__hip_atomic_compare_exchange_strong(word, &cur, want, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT))
+      return static_cast<int>(want & 0xffull);
+  }
+}
+
 // out[m][t][f] = sum_d in[t][d] * w[m][f][d].  A workgroup of LW wavefronts owns LW pairs
-// of 16-row weight tiles of one matrix and up to 128 token rows (blockIdx.y names which;
-// the weights are streamed once per 128 rows).  KD = the reduction length if it is one
-// of the unrolled ones (2048, 4096), else 0.
-template <int LW, int KD>
+// of 16-row weight tiles of one matrix and up to ROWS (64 or 128) token rows (blockIdx.y
+// names which; the weights are streamed once per ROWS rows).  KD = the reduction length of a workgroup if
+// it is one of the unrolled ones (1024, 2048, 4096), else 0.  With ksplit > 1 the reduction
+// dimension is split over that many workgroups (blockIdx.z): each writes its fp32 partial
+// tiles with device-scope stores and counts itself in; the last to arrive adds all the
+// partials in order of their part of the reduction dimension, whoever finished when.
+template <int LW, int KD, int ROWS>
 __global__ __launch_bounds__(LW* kWave, 2) void linear_lds_kernel(LinearArgs a) {
-  constexpr int kRows = 128;
+  constexpr int kRows = ROWS;
   __shared__ __align__(16) uint16_t lds[lds_elems(KD)];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int part = blockIdx.z, kd = a.Din / a.ksplit, k0 = part * kd;
   int bx = blockIdx.x, m = 0;
   for (; m < a.n_mats; ++m) {  // which matrix this workgroup belongs to
     const int per = (a.fout[m] / 32 + LW - 1) / LW;
@@ -52,10 +73,12 @@ __global__ __launch_bounds__(LW* kWave, 2) void linear_lds_kernel(LinearArgs a) 
   const int pair = bx * LW + wave;          // pair of row tiles this wavefront owns
   const bool active = pair * 2 < fout / 16;
   const uint16_t* w = uniform_ptr(a.w[m]);
-  const uint16_t* p0 = tile_base<false>(w, active ? pair * 2 : 0, Din);
-  const uint16_t* p1 = tile_base<false>(w, active ? pair * 2 + 1 : 0, Din);
+  const uint16_t* p0 = tile_base<false>(w, active ? pair * 2 : 0, Din) + k0;
+  const uint16_t* p1 = tile_base<false>(w, active ? pair * 2 + 1 : 0, Din) + k0;
   const uint32_t wlo = tile_lane_off<false>(Din, lane);
-  const uint16_t* in = uniform_ptr(a.in);
+  const uint16_t* in = uniform_ptr(a.in) + k0;
+  // this output tile's place among the launch's (x, y) workgroups: its partials and counter
+  const size_t tile_id = static_cast<size_t>(blockIdx.y) * gridDim.x + blockIdx.x;
   uint16_t* out = a.out[m];
   const uint16_t* res = m == 0 ? a.res : nullptr;
   {  // one pass of up to 128 token rows per workgroup (blockIdx.y)
@@ -72,8 +95,49 @@ __global__ __launch_bounds__(LW* kWave, 2) void linear_lds_kernel(LinearArgs a) 
         acc1[i] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
       constexpr int KC = NT <= 4 ? 128 : 64;
-      dma_stream_gemm<NT, kLdsBufElems / KC, false, LW, KC, KD>(p0, p1, wlo, wave, Din, rows, in, row_off, lds,
+      dma_stream_gemm<NT, kLdsBufElems / KC, false, LW, KC, KD>(p0, p1, wlo, wave, kd, rows, in, row_off, lds,
                                                                  acc0, acc1);
+      if (a.ksplit > 1) {
+        // partial tiles of this wavefront: [tile][part][wave][2][8 token tiles][64 lanes][4]
+        constexpr size_t kPerWave = 2 * 8 * 256;
+        float* base = a.partial + (tile_id * a.ksplit * LW) * kPerWave;
+        float* mine = base + (static_cast<size_t>(part) * LW + wave) * kPerWave;
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            __hip_atomic_store(mine + (i * 64 + lane) * 4 + q, acc0[i][q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(mine + ((8 + i) * 64 + lane) * 4 + q, acc1[i][q], __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+          }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's partials have left the compute unit
+        __shared__ int s_last;
+        __syncthreads();
+        if (tid == 0) {
+          s_last = arrive(a.flags + tile_id, a.epoch) == a.ksplit ? 1 : 0;
+          // everybody has arrived: clear the count, so that a replay of a captured launch
+          // (same epoch) counts from zero again
+          if (s_last) __hip_atomic_store(a.flags + tile_id, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (!s_last) return;
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+          acc0[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+          acc1[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        for (int h = 0; h < a.ksplit; ++h) {  // parts in order, not in order of arrival
+          const float* src = base + (static_cast<size_t>(h) * LW + wave) * kPerWave;
+#pragma unroll
+          for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              acc0[i][q] += __hip_atomic_load(src + (i * 64 + lane) * 4 + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              acc1[i][q] += __hip_atomic_load(src + ((8 + i) * 64 + lane) * 4 + q, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+      }
       if (!active) return;
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
@@ -99,9 +163,9 @@ __global__ __launch_bounds__(LW* kWave, 2) void linear_lds_kernel(LinearArgs a) 
     };
     if (nt <= 1) run(std::integral_constant<int, 1>{});
     else if (nt <= 2) run(std::integral_constant<int, 2>{});
-    else if (nt <= 4) run(std::integral_constant<int, 4>{});
-    else if (nt <= 6) run(std::integral_constant<int, 6>{});
-    else run(std::integral_constant<int, 8>{});
+    else if (kRows <= 64 || nt <= 4) run(std::integral_constant<int, 4>{});
+    else if (nt <= 6) run(std::integral_constant<int, kRows <= 64 ? 4 : 6>{});
+    else run(std::integral_constant<int, kRows <= 64 ? 4 : 8>{});
   }
 }
 
@@ -441,6 +505,28 @@ __global__ __launch_bounds__(256) void attention_core_kernel(AttnArgs a) {
   }
 }
 
+// Long blocks (more than 32 token rows), LW = 2: workgroups of the projection and over how
+// many of them the reduction dimension is split.  Few workgroups (the output projection of
+// a 2048-wide layer has 32 per 128 token rows) leave most compute units without a stream.
+struct LdsLinearPlan { int blocks, rows, passes, ksplit; };
+static LdsLinearPlan lds_linear_plan(int T, const int* fout, int n_mats, int Din) {
+  constexpr int LW = 2;
+  LdsLinearPlan p{0, 128, 1, 1};
+  for (int m = 0; m < n_mats; ++m) p.blocks += (fout[m] / 32 + LW - 1) / LW;
+  // few workgroups: passes of 64 token rows (chunks of 128 reduction elements, half the
+  // steps of a pass of 128 rows, and twice the workgroups)
+  if (p.blocks * ((T + 127) / 128) < 100) p.rows = 64;
+  p.passes = (T + p.rows - 1) / p.rows;
+  // still few: the reduction dimension over two workgroups as well.  Measured on the
+  // output projection of the 2048-wide layer at 256 token rows: 41.3 us as one pass of 128
+  // rows per workgroup, 30.4 us with passes of 64, 25.8 us with the split on top (four-way:
+  // no better); the q/k/v launch, 160 workgroups, is best left alone (21.7 us; split 38.7 us,
+  // passes of 64 29.2 us).
+  if (p.blocks * p.passes < 150 && Din % 512 == 0) p.ksplit = 2;
+  return p;
+}
+constexpr size_t kLdsPartialBytes = 2 * 2 * 8 * 256 * 4;  // of one workgroup: LW x 2 tiles x 8 token tiles x 1 KB
+
 // Scratch of one attention sub-layer (bytes from a 256-byte aligned base): q, k, v and the
 // per-head outputs of the block's tokens, bf16.
 AttnLayout attn_layout(const des_shape_t& s, const des_attn_shape_t& t) {
@@ -457,8 +543,20 @@ AttnLayout attn_layout(const des_shape_t& s, const des_attn_shape_t& t) {
   const size_t tiles_qkv = static_cast<size_t>(t.n_heads + 2 * t.n_kv_heads) * t.head_dim / 16;
   const size_t tiles_out = static_cast<size_t>(s.hidden) / 16;
   const size_t tiles = tiles_qkv > tiles_out ? tiles_qkv : tiles_out;
-  l.partial = p; p = align256(p + tiles * 4096);
-  l.flags = p; p = align256(p + tiles * 8);
+  size_t part_bytes = tiles * 4096, n_flags = tiles;
+  if (T > 32) {  // long blocks: one 32 KB partial per workgroup, one counter per output tile
+    const int f_qkv[3] = {t.n_heads * t.head_dim, t.n_kv_heads * t.head_dim, t.n_kv_heads * t.head_dim};
+    const int f_out[1] = {s.hidden};
+    const LdsLinearPlan a = lds_linear_plan(static_cast<int>(T), f_qkv, 3, s.hidden);
+    const LdsLinearPlan b = lds_linear_plan(static_cast<int>(T), f_out, 1, t.n_heads * t.head_dim);
+    const size_t wa = static_cast<size_t>(a.blocks) * a.passes, wb = static_cast<size_t>(b.blocks) * b.passes;
+    const size_t pa = a.ksplit > 1 ? wa * a.ksplit * kLdsPartialBytes : 0;
+    const size_t pb = b.ksplit > 1 ? wb * b.ksplit * kLdsPartialBytes : 0;
+    part_bytes = pa > pb ? pa : pb;
+    n_flags = wa > wb ? wa : wb;
+  }
+  l.partial = p; p = align256(p + part_bytes);
+  l.flags = p; p = align256(p + n_flags * 8);
   l.total = p;
   return l;
 }
@@ -502,12 +600,21 @@ static void launch_linear(const LinearArgs& a, int kernel_id, hipStream_t st) {
     }
     return;
   }
-  int blocks = 0;
-  for (int m = 0; m < a.n_mats; ++m) blocks += (a.fout[m] / 32 + LW - 1) / LW;
-  const dim3 g(blocks, (a.T + 127) / 128), b(LW * kWave);
-  if (a.Din == 2048) launch(kernel_id, linear_lds_kernel<LW, 2048>, g, b, 0, st, a);
-  else if (a.Din == 4096) launch(kernel_id, linear_lds_kernel<LW, 4096>, g, b, 0, st, a);
-  else launch(kernel_id, linear_lds_kernel<LW, 0>, g, b, 0, st, a);
+  static_assert(LW == 2, "lds_linear_plan and the partial tiles assume two wavefronts");
+  const LdsLinearPlan pl = lds_linear_plan(a.T, a.fout, a.n_mats, a.Din);
+  LinearArgs c = a;
+  c.ksplit = c.partial != nullptr ? pl.ksplit : 1;
+  const dim3 g(pl.blocks, pl.passes, c.ksplit), b(LW * kWave);
+  const int kd = a.Din / c.ksplit;
+#define DES_LAUNCH_LIN(KDV)                                                                   \
+  do {                                                                                        \
+    if (pl.rows == 64) launch(kernel_id, linear_lds_kernel<LW, KDV, 64>, g, b, 0, st, c);     \
+    else launch(kernel_id, linear_lds_kernel<LW, KDV, 128>, g, b, 0, st, c);                  \
+  } while (0)
+  if (kd == 2048) DES_LAUNCH_LIN(2048);
+  else if (kd == 4096) DES_LAUNCH_LIN(4096);
+  else DES_LAUNCH_LIN(0);
+#undef DES_LAUNCH_LIN
 }
 
 int launch_attention(const des_shape_t& s, const des_attn_shape_t& t, const void* x, const void* wq,
