@@ -340,6 +340,7 @@ def other_configs(args, torch, B, W, dev, cfg2, layer2, replicas2, w_router2, bi
     torch.cuda.empty_cache()
 
     res["decoder_step"] = decoder_breakdown(torch, B, W, dev)
+    res["decoder_step_batch8"] = decoder_breakdown(torch, B, W, dev, n_seqs=8, modes=("vote",))
 
     # ---- 48-layer stack: needs ~60 GB for the weights and a transient for packing
     free, _ = torch.cuda.mem_get_info()
@@ -378,7 +379,7 @@ def other_configs(args, torch, B, W, dev, cfg2, layer2, replicas2, w_router2, bi
     return res
 
 
-def decoder_breakdown(torch, B, W, dev, n_layers=12, steps=20, warm=3):
+def decoder_breakdown(torch, B, W, dev, n_layers=12, steps=20, warm=3, n_seqs=1, modes=("vanilla", "vote")):
     """Where the time of a decoding step goes once attention sits around the MoE layers
     (the paper's Fig. 2 left, re-measured here with synthetic weights): a stack of
     `n_layers` decoder layers (attention with 32 query / 4 key-value heads of width 128
@@ -386,8 +387,9 @@ def decoder_breakdown(torch, B, W, dev, n_layers=12, steps=20, warm=3):
     block of 32 tokens, vanilla routing against DES-Vote C = 32.  Every layer has its own
     weights (14.5 GB for 12 layers), so each is read cold once per step."""
     from paper_2602_00879_amd import device_workloads as DW
-    cfg = W.CONFIGS["m128_zipf"].with_(n_layers=n_layers, seed=61)
-    acfg = W.ATTN_CONFIGS["attn_block32"]
+    cfg = W.CONFIGS["m128_zipf"].with_(n_layers=n_layers, seed=61, n_seqs=n_seqs)
+    acfg = W.ATTN_CONFIGS["attn_block32" if n_seqs == 1 else "attn_batch8"]
+    assert acfg.n_seqs == n_seqs
     st = DW.make_stack(cfg, dev)
     at = DW.make_decoder_attention(cfg, acfg, dev)
     for k in ("w_gate", "w_up", "w_down"):
@@ -398,7 +400,7 @@ def decoder_breakdown(torch, B, W, dev, n_layers=12, steps=20, warm=3):
     attn_bytes = 2 * (2 * cfg.hidden * acfg.n_heads * acfg.head_dim + 2 * cfg.hidden * acfg.n_kv_heads * acfg.head_dim)
     per = 3 * cfg.hidden * cfg.ffn * 2
     rows = []
-    for mode in ("vanilla", "vote"):
+    for mode in modes:
         shape = B.make_shape(cfg.n_seqs, cfg.n_tokens, cfg.hidden, cfg.n_experts, cfg.ffn, cfg.top_k, cfg.coreset,
                              mode, cfg.dtype, weight_layout=B.DES_LAYOUT_PACKED, residual=1)
         bufs = B.DecoderBuffers(shape, attn, n_layers, dev, torch.bfloat16)
@@ -436,7 +438,7 @@ def decoder_breakdown(torch, B, W, dev, n_layers=12, steps=20, warm=3):
     del st, at
     torch.cuda.empty_cache()
     return {"workload": f"{n_layers} decoder layers (attention 32/4 heads x 128 over 16+16 cached + block, then "
-                        "128-expert MoE), 1 block x 32 tokens, per layer", "rows": rows}
+                        f"128-expert MoE), {n_seqs} block(s) x 32 tokens, per layer", "rows": rows}
 
 
 def bench_selection(args, torch, B, W, dev):
